@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the SparseMoE expert hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch: route,
+permute, grouped GEMM forward, combine, combine backward, grouped GEMM backward
+(dgrad + wgrad), permute backward.  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line: whole-path tokens/s, the roofline of the kernel
+that takes the most time (measured with HIP events on the launch stream), a
+per-kernel table, and the CPU oracle timed on a bounded sample of the workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+
+
+def kernel_work(cfg, R):
+    """Algorithmic work of ONE launch of each kernel: ('mfma', flop) or ('hbm', bytes).
+
+    GEMM flop count uses the rows actually routed (no credit for tile padding).
+    Row movers count compulsory bytes: every source row read once and every
+    destination row written once, bf16.
+    """
+    T, d, f, k = cfg.T, cfg.d, cfg.f, cfg.k
+    rdf = float(R) * d * f
+    row = 2.0 * d
+    return {
+        "gemm_gate_up": ("mfma", 4 * rdf),
+        "gemm_down": ("mfma", 2 * rdf),
+        "gemm_dgrad_h": ("mfma", 2 * rdf),
+        "gemm_dgrad_x": ("mfma", 4 * rdf),
+        "gemm_wgrad_down": ("mfma", 2 * rdf),
+        "gemm_wgrad_gate": ("mfma", 2 * rdf),
+        "gemm_wgrad_up": ("mfma", 2 * rdf),
+        "permute_rows": ("hbm", row * (T + R)),
+        "combine": ("hbm", row * (R + T)),
+        "combine_bwd": ("hbm", row * (T + R) + row * R),
+        "permute_bwd": ("hbm", row * (R + T)),
+        "route": ("hbm", 4.0 * T * cfg.E + 8.0 * T * k),
+        "permute_count": ("hbm", 4.0 * T * k),
+        "permute_scan": ("hbm", 0.0),
+        "permute_place": ("hbm", 12.0 * T * k),
+    }
+
+
+def cpu_baseline(cfg, inp, sample_tokens):
+    """The oracle, as it stands (NumPy fp64), on the first `sample_tokens` tokens of the batch."""
+    import numpy as np
+    from oracle import moe_oracle as O
+    sub = {k: (v[:sample_tokens] if k in ("x", "dout", "logits") else v) for k, v in inp.items()}
+    t0 = time.perf_counter()
+    r = O.layer_fwd_bwd(sub, cfg.k, cfg.e_begin, cfg.n_local, cfg.renormalize)
+    dt = time.perf_counter() - t0
+    cores = len(os.sched_getaffinity(0))
+    R = int(r["expert_offsets"][-1])
+    return {
+        "value": sample_tokens / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+        "sample": f"first {sample_tokens} of {cfg.T} tokens, all {cfg.n_local} experts, full fwd+bwd in fp64 NumPy "
+                  f"({R} routed rows, {dt:.2f} s incl. bf16 decode)",
+        "gemm_gflops": 18.0 * R * cfg.d * cfg.f / dt / 1e9,
+    }, r
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="olmoe", help="olmoe (headline) | fine | ep_share | tiny | skew")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_00785_amd import binding as B
+    from paper_2604_00785_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.load(build_if_missing=True)
+    cfg = W.CONFIGS[args.workload]
+    dev = "cuda:0"
+    inp = W.make_inputs(cfg)
+
+    def up(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    x, dout = up(inp["x"]), up(inp["dout"])
+    Wg, Wu, Wd = up(inp["Wg"]), up(inp["Wu"]), up(inp["Wd"])
+    logits = torch.from_numpy(inp["logits"]).to(dev)
+    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.e_begin, cfg.n_local, cfg.renormalize, dev)
+
+    def step():
+        buf.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    R = int(buf.expert_offsets[-1].item())
+
+    # ---- timed region: exactly K steps ------------------------------------------
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    tokens_per_s = cfg.T * args.steps / elapsed
+
+    # ---- the same K steps again with every launch bracketed by HIP events ---------
+    B.moe_prof_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = B.moe_prof_read()
+    B.moe_prof_enable(False)
+
+    work = kernel_work(cfg, R)
+    kernels = {}
+    for name, total_ms, launches in prof:
+        avg_ms = total_ms / max(launches, 1)
+        kind, amount = work.get(name, ("hbm", 0.0))
+        ent = {"avg_us": round(avg_ms * 1e3, 2), "launches_per_step": launches // args.steps, "bound": kind}
+        if kind == "mfma":
+            ent["tflops"] = round(amount / (avg_ms * 1e-3) / 1e12, 1)
+            ent["frac"] = round(ent["tflops"] / PEAK_BF16_TFLOPS, 4)
+        else:
+            ent["gbs"] = round(amount / (avg_ms * 1e-3) / 1e9, 1)
+            ent["frac"] = round(ent["gbs"] / PEAK_HBM_GBS, 4)
+        kernels[name] = ent
+    dom = max(kernels, key=lambda n: kernels[n]["avg_us"] * kernels[n]["launches_per_step"])
+    dk = kernels[dom]
+    if dk["bound"] == "mfma":
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": dk["tflops"], "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": dk["frac"], "traffic": None}
+    else:
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": dk["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": dk["frac"], "traffic": None}
+    gemm_us = sum(v["avg_us"] * v["launches_per_step"] for n, v in kernels.items() if n.startswith("gemm_"))
+    gemm_tflops = 18.0 * R * cfg.d * cfg.f / (gemm_us * 1e-6) / 1e12 if gemm_us > 0 else 0.0
+
+    line = {
+        "metric": "MoE layer fwd+bwd tokens/s (grouped-GEMM TFLOP/s and % of bf16 MFMA peak alongside), 1 GPU",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} (local {cfg.n_local}) k={cfg.k} f={cfg.f}",
+                   "routed_rows": R, "renormalize": cfg.renormalize},
+        "grouped_gemm": {"tflops": round(gemm_tflops, 1), "frac_of_bf16_peak": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
+                         "flop_per_step": 18.0 * R * cfg.d * cfg.f, "us_per_step": round(gemm_us, 1)},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu:
+        n = min(args.cpu_sample_tokens, cfg.T)
+        cb, _ = cpu_baseline(cfg, inp, n)
+        cb["value"] = round(cb["value"], 2)
+        cb["gemm_gflops"] = round(cb["gemm_gflops"], 1)
+        line["cpu_baseline"] = cb
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,180 @@
+/*
+ * moe_hotpath.h - C ABI of the MI355X (gfx950) SparseMoE expert hot path.
+ *
+ * The calls follow the five stages of the paper's FastSparseMoE block
+ * (Section 3.1, Algorithm 1) for ONE GPU holding the local experts
+ * [e_begin, e_begin + e_count) of an E-expert layer (e_count == E when there is
+ * no expert parallelism):
+ *
+ *   moe_route                 Stage 1   Softmax + TopK of the router logits
+ *   moe_permute               Stages 2-3 and the gather that opens Stage 4
+ *   moe_grouped_gemm_fwd      Stage 4   three grouped products around Silu(gate)*up
+ *   moe_unpermute_combine     Stage 5   ExpertOutputReductionForward
+ *   moe_unpermute_combine_bwd Stage 5   ExpertOutputReductionBackward
+ *   moe_grouped_gemm_bwd      derivative of Stage 4 (dgrad + wgrad; left to autograd in the paper)
+ *   moe_permute_bwd           derivative of the Stage-4 gather
+ *
+ * Conventions, valid for every function below
+ * -------------------------------------------
+ * - Every pointer except `stream` is a DEVICE pointer to memory the caller owns,
+ *   16-byte aligned, dense and row-major.  The library allocates nothing, frees
+ *   nothing and never synchronises: all work is enqueued on `stream`
+ *   (a hipStream_t passed as void*; NULL is the default stream).  Results are
+ *   ready when the stream reaches them.
+ * - Outputs are overwritten, never accumulated into (weight gradients of
+ *   experts without rows are written as zeros).
+ * - Group sizes stay on the device (`expert_offsets`); no call reads them back.
+ *   R_cap is the row capacity of the grouped buffers (T*k is always enough);
+ *   rows at or beyond expert_offsets[e_count] are neither read nor written.
+ * - moe_bf16 is a raw bfloat16 bit pattern.  Products accumulate in fp32; bf16
+ *   results are rounded to nearest-even once, from the fp32 value.
+ * - Return value: MOE_OK, or a negative MOE_ERR_* code.  Argument checks run on
+ *   the host before anything is enqueued; a failed call enqueues nothing.
+ *   Not checked (preconditions): logits finite; topk_idx values in [0, E) and
+ *   distinct within a token; expert_offsets non-decreasing, starting at 0 and
+ *   ending at most at R_cap.
+ * - Calls on different streams may overlap as long as their buffers (including
+ *   workspaces) do not.
+ */
+#ifndef MOE_HOTPATH_H
+#define MOE_HOTPATH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t moe_bf16;
+
+enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID = -1,   /* null/misaligned pointer, non-positive or unsupported size */
+  MOE_ERR_WORKSPACE = -2, /* workspace smaller than the matching *_workspace_bytes() */
+  MOE_ERR_LAUNCH = -3     /* the HIP runtime refused a launch (hipGetLastError) */
+};
+
+/* Size limits (checked; MOE_ERR_INVALID beyond them):
+ *   1 <= k <= E <= 512, e_count <= 512, d % 8 == 0, f % 8 == 0 for the row
+ *   movers; the grouped products additionally need d % 64 == 0 and f % 64 == 0. */
+#define MOE_MAX_EXPERTS 512
+
+/* Library identification string (static storage). */
+const char* moe_version(void);
+
+/* Workspace sizes in bytes (host computation only). */
+size_t moe_permute_workspace_bytes(int T, int k, int e_count);
+size_t moe_grouped_gemm_bwd_workspace_bytes(int R_cap, int f);
+/* Upper bound that is enough for any call on a layer of this shape. */
+size_t moe_workspace_bytes(int T, int E, int k, int d, int f);
+
+/*
+ * Stage 1 (Algorithm 1: probs = Softmax(logits); weights, indices = TopK(probs)).
+ *   logits   [T, E] fp32
+ *   topk_idx [T, k] int32  slot i holds the expert with the i-th largest logit;
+ *                          equal logits go to the lower expert id (-0.0 == +0.0)
+ *   topk_w   [T, k] fp32   softmax probability of each chosen expert; divided by
+ *                          the sum over the k chosen ones when renormalize != 0
+ *                          (renormalize == 0 is Algorithm 1 as printed)
+ */
+int moe_route(const float* logits, int T, int E, int k, int renormalize,
+              int32_t* topk_idx, float* topk_w, void* stream);
+
+/*
+ * Stages 2-3 (token counting, index generation) and mlp_in = input[input_indices].
+ * The (token, slot) pairs whose expert is local are grouped by expert; inside an
+ * expert they keep token order (a stable counting sort, done without atomics, so
+ * the result is unique and reproducible).
+ *   x              [T, d] bf16
+ *   topk_idx       [T, k] int32, values in [0, E_total)
+ *   expert_offsets [e_count+1] int32  out: exclusive prefix sum of the per-expert
+ *                                     row counts (Algorithm 1: cum_token_counts)
+ *   row_token      [T*k] int32        out: token of each grouped row (input_indices);
+ *                                     entries at or beyond R are left untouched
+ *   slot_row       [T, k] int32       out: grouped row of pair (t, i), -1 when its
+ *                                     expert is not local (dense form of
+ *                                     output_indices / selected_expert_indices)
+ *   xp             [T*k, d] bf16      out: xp[r] = x[row_token[r]] for r < R
+ *   ws             at least moe_permute_workspace_bytes(T, k, e_count)
+ */
+int moe_permute(const moe_bf16* x, const int32_t* topk_idx,
+                int T, int d, int E_total, int k, int e_begin, int e_count,
+                int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row,
+                moe_bf16* xp, void* ws, size_t ws_bytes, void* stream);
+
+/* dx[t] = sum over the local slots i of token t of dxp[slot_row[t, i]] (fp32 sum
+ * in slot order, rounded once); a token without local slot gets zeros.
+ *   dxp [R_cap, d] bf16, slot_row [T, k] int32, dx [T, d] bf16 */
+int moe_permute_bwd(const moe_bf16* dxp, const int32_t* slot_row, int T, int k, int d,
+                    moe_bf16* dx, void* stream);
+
+/*
+ * Stage 4 (Algorithm 1: gate_out, up_out = Grouped_mm(mlp_in, gate/up_weight);
+ * mul_out = Silu(gate_out) * up_out; mlp_out = Grouped_mm(mul_out, down_weight)).
+ * For each local expert e with rows r in [expert_offsets[e], expert_offsets[e+1]):
+ *   g[r] = xp[r] . Wg[e]^T,  u[r] = xp[r] . Wu[e]^T,  h[r] = silu(g[r]) * u[r],
+ *   yp[r] = h[r] . Wd[e]^T.
+ *   xp [R_cap, d]; Wg, Wu [E, f, d]; Wd [E, d, f]  (each expert's [out, in]
+ *   weight, stacked over the E local experts); g, u, h [R_cap, f] are saved for
+ *   the backward call; yp [R_cap, d].  All bf16; h is formed from the fp32
+ *   accumulators, before g and u are rounded.
+ */
+int moe_grouped_gemm_fwd(const moe_bf16* xp, const int32_t* expert_offsets,
+                         const moe_bf16* Wg, const moe_bf16* Wu, const moe_bf16* Wd,
+                         int E, int R_cap, int d, int f,
+                         moe_bf16* g, moe_bf16* u, moe_bf16* h, moe_bf16* yp, void* stream);
+
+/*
+ * Derivative of Stage 4.  With s = sigmoid(g):
+ *   dh = dyp . Wd[e];  dg = dh * u * s * (1 + g * (1 - s));  du = dh * g * s;
+ *   dxp = dg . Wg[e] + du . Wu[e];
+ *   dWd[e] = dyp^T . h;  dWg[e] = dg^T . xp;  dWu[e] = du^T . xp   (zeros if e has no rows).
+ *   dyp, xp, dxp [R_cap, d]; g, u, h [R_cap, f]; dWg, dWu [E, f, d]; dWd [E, d, f]; all bf16.
+ *   ws at least moe_grouped_gemm_bwd_workspace_bytes(R_cap, f): holds dg and du (bf16).
+ */
+int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp,
+                         const moe_bf16* g, const moe_bf16* u, const moe_bf16* h,
+                         const int32_t* expert_offsets,
+                         const moe_bf16* Wg, const moe_bf16* Wu, const moe_bf16* Wd,
+                         int E, int R_cap, int d, int f,
+                         moe_bf16* dxp, moe_bf16* dWg, moe_bf16* dWu, moe_bf16* dWd,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stage 5, ExpertOutputReductionForward:
+ *   out[t] = sum over local slots i, in slot order, of topk_w[t, i] * yp[slot_row[t, i]]
+ * (fp32 sum, rounded once); zeros for a token without local slot.
+ *   yp [R_cap, d] bf16, slot_row [T, k] int32, topk_w [T, k] fp32, out [T, d] bf16
+ */
+int moe_unpermute_combine(const moe_bf16* yp, const int32_t* slot_row, const float* topk_w,
+                          int T, int k, int d, moe_bf16* out, void* stream);
+
+/*
+ * Stage 5, ExpertOutputReductionBackward:
+ *   dyp[slot_row[t, i]] = topk_w[t, i] * dout[t]
+ *   dgate[t, i] = <yp[slot_row[t, i]], dout[t]>   (0 where slot_row[t, i] < 0)
+ * dgate is the gradient with respect to the weights as used by the combine.
+ *   dout [T, d] bf16, yp, dyp [R_cap, d] bf16, dgate [T, k] fp32
+ */
+int moe_unpermute_combine_bwd(const moe_bf16* dout, const moe_bf16* yp,
+                              const int32_t* slot_row, const float* topk_w,
+                              int T, int k, int d, moe_bf16* dyp, float* dgate, void* stream);
+
+/*
+ * Per-kernel timing for benchmarks (not part of the paper's method).  While
+ * enabled, every kernel the library launches is bracketed by two HIP events
+ * recorded on the launch stream.  moe_prof_read synchronises on the recorded
+ * events and returns, for entry `index` (0 .. moe_prof_count()-1), the kernel's
+ * name, its summed duration in milliseconds and its launch count.  These calls
+ * create HIP events (host objects) and are not thread-safe; leave profiling off
+ * in production.
+ */
+int moe_prof_enable(int on);        /* also clears what was recorded */
+int moe_prof_count(void);
+int moe_prof_read(int index, char* name, int name_cap, float* total_ms, int* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_HOTPATH_H */

@@ -1,0 +1,156 @@
+// Stage 5 of Algorithm 1 (ExpertOutputReductionForward / Backward) and the
+// derivative of the Stage-4 gather, which is the same reduction with unit weights.
+//
+// The paper maps one thread to one output element (forward) or one routed row
+// (backward).  Here one wave owns one token and walks its row in 16-byte pieces:
+// every load and store is a full, coalesced row segment, the k source rows are
+// summed in slot order in fp32, and the token's own row (out / dout) is touched
+// exactly once.  No atomics, so results are reproducible.
+#include "common.h"
+
+namespace {
+
+__device__ __forceinline__ void fma8(float acc[8], const uint4& v, float w) {
+  acc[0] += w * bf16lo(v.x); acc[1] += w * bf16hi(v.x);
+  acc[2] += w * bf16lo(v.y); acc[3] += w * bf16hi(v.y);
+  acc[4] += w * bf16lo(v.z); acc[5] += w * bf16hi(v.z);
+  acc[6] += w * bf16lo(v.w); acc[7] += w * bf16hi(v.w);
+}
+__device__ __forceinline__ uint4 pack8(const float a[8]) {
+  return make_uint4(pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(a[4], a[5]), pack_bf16(a[6], a[7]));
+}
+__device__ __forceinline__ float dot8(const uint4& a, const uint4& b) {
+  return bf16lo(a.x) * bf16lo(b.x) + bf16hi(a.x) * bf16hi(b.x) + bf16lo(a.y) * bf16lo(b.y) + bf16hi(a.y) * bf16hi(b.y) +
+         bf16lo(a.z) * bf16lo(b.z) + bf16hi(a.z) * bf16hi(b.z) + bf16lo(a.w) * bf16lo(b.w) + bf16hi(a.w) * bf16hi(b.w);
+}
+__device__ __forceinline__ uint4 scale8(const uint4& v, float w) {
+  return make_uint4(pack_bf16(w * bf16lo(v.x), w * bf16hi(v.x)), pack_bf16(w * bf16lo(v.y), w * bf16hi(v.y)),
+                    pack_bf16(w * bf16lo(v.z), w * bf16hi(v.z)), pack_bf16(w * bf16lo(v.w), w * bf16hi(v.w)));
+}
+
+// out[t] = sum_i w[t,i] * src[slot_row[t,i]]   (WEIGHTED)  or  sum_i src[slot_row[t,i]]
+template <int VPT, bool WEIGHTED>
+__global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ src, const int32_t* __restrict__ slot_row,
+                                                      const float* __restrict__ topk_w, int T, int k, int chunks,
+                                                      uint4* __restrict__ out) {
+  const int lane = threadIdx.x % MOE_WAVE;
+  const int t = blockIdx.x * (256 / MOE_WAVE) + threadIdx.x / MOE_WAVE;
+  if (t >= T) return;
+  for (int c0 = 0; c0 < chunks; c0 += MOE_WAVE * VPT) {
+    float acc[VPT][8];
+#pragma unroll
+    for (int j = 0; j < VPT; ++j)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[j][q] = 0.f;
+    for (int i = 0; i < k; ++i) {
+      const int row = slot_row[static_cast<size_t>(t) * k + i];
+      if (row < 0) continue;
+      const float w = WEIGHTED ? topk_w[static_cast<size_t>(t) * k + i] : 1.0f;
+      const uint4* r = src + static_cast<size_t>(row) * chunks;
+      uint4 v[VPT];
+#pragma unroll
+      for (int j = 0; j < VPT; ++j) {
+        const int c = c0 + j * MOE_WAVE + lane;
+        v[j] = c < chunks ? r[c] : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < VPT; ++j) fma8(acc[j], v[j], w);
+    }
+    uint4* o = out + static_cast<size_t>(t) * chunks;
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+      const int c = c0 + j * MOE_WAVE + lane;
+      if (c < chunks) o[c] = pack8(acc[j]);
+    }
+  }
+}
+
+// dyp[row(t,i)] = w[t,i] * dout[t];  dgate[t,i] = <yp[row(t,i)], dout[t]>
+template <int VPT>
+__global__ __launch_bounds__(256) void combine_bwd_kernel(const uint4* __restrict__ dout, const uint4* __restrict__ yp,
+                                                          const int32_t* __restrict__ slot_row,
+                                                          const float* __restrict__ topk_w, int T, int k, int chunks,
+                                                          uint4* __restrict__ dyp, float* __restrict__ dgate) {
+  const int lane = threadIdx.x % MOE_WAVE;
+  const int t = blockIdx.x * (256 / MOE_WAVE) + threadIdx.x / MOE_WAVE;
+  if (t >= T) return;
+  const uint4* g = dout + static_cast<size_t>(t) * chunks;
+  for (int i = 0; i < k; ++i) {
+    const int row = slot_row[static_cast<size_t>(t) * k + i];
+    float dot = 0.f;
+    if (row >= 0) {
+      const float w = topk_w[static_cast<size_t>(t) * k + i];
+      const uint4* y = yp + static_cast<size_t>(row) * chunks;
+      uint4* dy = dyp + static_cast<size_t>(row) * chunks;
+      for (int c0 = 0; c0 < chunks; c0 += MOE_WAVE * VPT) {
+        uint4 gv[VPT], yv[VPT];
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+          const int c = c0 + j * MOE_WAVE + lane;
+          const bool ok = c < chunks;
+          gv[j] = ok ? g[c] : make_uint4(0, 0, 0, 0);
+          yv[j] = ok ? y[c] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+          const int c = c0 + j * MOE_WAVE + lane;
+          dot += dot8(yv[j], gv[j]);
+          if (c < chunks) dy[c] = scale8(gv[j], w);
+        }
+      }
+#pragma unroll
+      for (int m = 1; m < MOE_WAVE; m <<= 1) dot += __shfl_xor(dot, m, MOE_WAVE);
+    }
+    if (lane == 0) dgate[static_cast<size_t>(t) * k + i] = dot;
+  }
+}
+
+template <bool WEIGHTED>
+int launch_combine(const moe_bf16* src, const int32_t* slot_row, const float* w, int T, int k, int d, moe_bf16* out,
+                   hipStream_t s, const char* name) {
+  const int chunks = d / 8;
+  dim3 grid((T + 3) / 4), block(256);
+  const uint4* a = reinterpret_cast<const uint4*>(src);
+  uint4* o = reinterpret_cast<uint4*>(out);
+  if (chunks <= 64) MOE_LAUNCH(name, (combine_kernel<1, WEIGHTED>), grid, block, 0, s, a, slot_row, w, T, k, chunks, o);
+  else if (chunks <= 128) MOE_LAUNCH(name, (combine_kernel<2, WEIGHTED>), grid, block, 0, s, a, slot_row, w, T, k, chunks, o);
+  else MOE_LAUNCH(name, (combine_kernel<4, WEIGHTED>), grid, block, 0, s, a, slot_row, w, T, k, chunks, o);
+  return moe_check_launch();
+}
+
+bool bad_dims(int T, int k, int d) { return T <= 0 || k <= 0 || d <= 0 || d % 8 != 0; }
+
+}  // namespace
+
+extern "C" int moe_unpermute_combine(const moe_bf16* yp, const int32_t* slot_row, const float* topk_w, int T, int k, int d,
+                                     moe_bf16* out, void* stream) {
+  if (!yp || !slot_row || !topk_w || !out || bad_dims(T, k, d)) return MOE_ERR_INVALID;
+  if (!moe_aligned16(yp) || !moe_aligned16(out) || !moe_aligned16(slot_row) || !moe_aligned16(topk_w)) return MOE_ERR_INVALID;
+  return launch_combine<true>(yp, slot_row, topk_w, T, k, d, out, static_cast<hipStream_t>(stream), "combine");
+}
+
+extern "C" int moe_permute_bwd(const moe_bf16* dxp, const int32_t* slot_row, int T, int k, int d, moe_bf16* dx,
+                               void* stream) {
+  if (!dxp || !slot_row || !dx || bad_dims(T, k, d)) return MOE_ERR_INVALID;
+  if (!moe_aligned16(dxp) || !moe_aligned16(dx) || !moe_aligned16(slot_row)) return MOE_ERR_INVALID;
+  return launch_combine<false>(dxp, slot_row, nullptr, T, k, d, dx, static_cast<hipStream_t>(stream), "permute_bwd");
+}
+
+extern "C" int moe_unpermute_combine_bwd(const moe_bf16* dout, const moe_bf16* yp, const int32_t* slot_row,
+                                         const float* topk_w, int T, int k, int d, moe_bf16* dyp, float* dgate,
+                                         void* stream) {
+  if (!dout || !yp || !slot_row || !topk_w || !dyp || !dgate || bad_dims(T, k, d)) return MOE_ERR_INVALID;
+  if (!moe_aligned16(dout) || !moe_aligned16(yp) || !moe_aligned16(dyp) || !moe_aligned16(slot_row) ||
+      !moe_aligned16(topk_w) || !moe_aligned16(dgate))
+    return MOE_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int chunks = d / 8;
+  dim3 grid((T + 3) / 4), block(256);
+  const uint4* a = reinterpret_cast<const uint4*>(dout);
+  const uint4* y = reinterpret_cast<const uint4*>(yp);
+  uint4* o = reinterpret_cast<uint4*>(dyp);
+  if (chunks <= 64) MOE_LAUNCH("combine_bwd", combine_bwd_kernel<1>, grid, block, 0, s, a, y, slot_row, topk_w, T, k, chunks, o, dgate);
+  else if (chunks <= 128) MOE_LAUNCH("combine_bwd", combine_bwd_kernel<2>, grid, block, 0, s, a, y, slot_row, topk_w, T, k, chunks, o, dgate);
+  else MOE_LAUNCH("combine_bwd", combine_bwd_kernel<4>, grid, block, 0, s, a, y, slot_row, topk_w, T, k, chunks, o, dgate);
+  return moe_check_launch();
+}

@@ -1,0 +1,91 @@
+"""Helpers shared by the GPU parity tests: move seeded inputs to the device, run
+the HIP path through the binding, bring results back as numpy, compare."""
+from __future__ import annotations
+
+from typing import Dict
+
+import numpy as np
+import torch
+
+from paper_2604_00785_amd import binding as B
+from paper_2604_00785_amd import workloads as W
+
+REL_TOL = 2e-2        # max |gpu - ref| / max |ref| per tensor: bf16 inputs, fp32 accumulation
+GATE_TOL = 1e-5       # relative, fp32 softmax against the fp64 oracle
+
+
+def bf16_to_dev(bits: np.ndarray, device="cuda:0") -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def bf16_from_dev(t: torch.Tensor) -> np.ndarray:
+    """Device bf16 tensor -> float64 numpy (exact widening)."""
+    bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return W.bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    return W.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))
+
+
+def run_layer(cfg: W.MoEConfig, inp: Dict[str, np.ndarray], device="cuda:0") -> Dict[str, np.ndarray]:
+    """Whole hot path on the GPU for one generated batch; returns numpy results."""
+    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.e_begin, cfg.n_local, cfg.renormalize, device)
+    x, dout = bf16_to_dev(inp["x"], device), bf16_to_dev(inp["dout"], device)
+    Wg, Wu, Wd = (bf16_to_dev(inp[n], device) for n in ("Wg", "Wu", "Wd"))
+    logits = torch.from_numpy(inp["logits"]).to(device)
+    # poison outputs so that an element nobody wrote shows up
+    for n in ("xp", "yp", "g", "u", "h", "dyp", "dxp", "out", "dx", "dWg", "dWu", "dWd"):
+        getattr(buf, n).fill_(float("nan"))
+    buf.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
+    torch.cuda.synchronize()
+    res = {}
+    for n, t in buf.results().items():
+        res[n] = bf16_from_dev(t) if t.dtype == torch.bfloat16 else t.cpu().numpy()
+    return res
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    scale = np.abs(ref).max()
+    if scale == 0.0:
+        return float(np.abs(got).max())
+    return float(np.abs(got - ref).max() / scale)
+
+
+def outlier_fraction(got: np.ndarray, ref: np.ndarray) -> float:
+    """Share of elements off by more than 2e-2 relative plus a small absolute floor."""
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    bad = np.abs(got - ref) > REL_TOL * np.abs(ref) + 2e-2 * rms
+    return float(bad.mean())
+
+
+def assert_close(got, ref, name, tol=REL_TOL):
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), f"{name}: non-finite values (unwritten or overflowed elements)"
+    e = rel_err(got, ref)
+    assert e <= tol, f"{name}: max|d|/max|ref| = {e:.3e} > {tol}"
+    fr = outlier_fraction(got, ref)
+    assert fr <= 1e-3, f"{name}: {fr:.2e} of elements off by more than {REL_TOL} relative"
+
+
+def compare_layer(res: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], n_local: int):
+    """Bit-exact integer results, toleranced floating-point ones (rows < R only)."""
+    for n in ("topk_idx", "expert_offsets", "slot_row"):
+        assert np.array_equal(res[n], ref[n]), f"{n} differs"
+    R = int(ref["expert_offsets"][-1])
+    assert np.array_equal(res["row_token"][:R], ref["row_token"]), "row_token differs"
+    np.testing.assert_allclose(res["topk_w"], ref["topk_w"], rtol=GATE_TOL, atol=1e-30)
+    assert np.array_equal(res["xp"][:R], ref["xp"]), "xp is not an exact copy"
+    for n in ("g", "u", "h", "yp", "dyp", "dxp"):
+        assert_close(res[n][:R], ref[n], n)
+    for n in ("out", "dx", "dgate"):
+        assert_close(res[n], ref[n], n)
+    off = ref["expert_offsets"]
+    for n in ("dWg", "dWu", "dWd"):
+        for e in range(n_local):
+            if off[e] == off[e + 1]:
+                assert np.all(res[n][e] == 0.0), f"{n}[{e}]: expert without rows must get zeros"
+            else:
+                assert_close(res[n][e], ref[n][e], f"{n}[{e}]")

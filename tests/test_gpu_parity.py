@@ -1,0 +1,218 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Integer results bit-exact; floating point within
+max|d|/max|ref| <= 2e-2 per tensor (bf16 storage, fp32 accumulation)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2604_00785_amd import binding as B
+from paper_2604_00785_amd import workloads as W
+
+import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def random_topk(rng, T, E, k):
+    return np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+
+
+# ----------------------------------------------------------------------------- route
+@pytest.mark.parametrize("T,E,k", [(256, 8, 2), (1000, 64, 8), (777, 128, 8), (50, 5, 5), (130, 100, 7),
+                                   (64, 300, 70), (33, 512, 9), (1, 64, 8), (5, 1, 1)])
+@pytest.mark.parametrize("renorm", [0, 1])
+def test_route(T, E, k, renorm):
+    print(f"route T={T} E={E} k={k} renorm={renorm}", flush=True)
+    rng = np.random.default_rng(T + E + k)
+    logits = (rng.standard_normal((T, E)) * 2).astype(np.float32)
+    # ties: coarse values in some rows, all-equal rows, signed zeros
+    logits[::7] = np.round(logits[::7])
+    logits[3 % T] = 1.5
+    if T > 4:
+        logits[4] = np.where(rng.random(E) < 0.5, 0.0, -0.0).astype(np.float32)
+    idx = torch.zeros(T, k, dtype=torch.int32, device=DEV)
+    w = torch.zeros(T, k, dtype=torch.float32, device=DEV)
+    B.moe_route(torch.from_numpy(logits).to(DEV), k, renorm, idx, w)
+    torch.cuda.synchronize()
+    ridx, rw = O.route(logits, k, renorm)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=H.GATE_TOL)
+
+
+# ----------------------------------------------------------------------------- permute
+@pytest.mark.parametrize("T,E,k,d,eb,ec", [
+    (256, 8, 2, 128, 0, 8), (1000, 64, 8, 256, 0, 64), (1000, 64, 8, 64, 16, 8), (513, 128, 8, 2048, 0, 128),
+    (129, 12, 5, 4096, 3, 7), (7, 4, 1, 8, 0, 4), (4096, 512, 4, 72, 0, 512), (3000, 16, 4, 1032, 0, 16)])
+def test_permute(T, E, k, d, eb, ec):
+    print(f"permute T={T} E={E} k={k} d={d} local=[{eb},{eb+ec})", flush=True)
+    rng = np.random.default_rng(T * 3 + E)
+    # expert eb+1 is never chosen when there are enough others: an empty local group
+    pool = np.array([e for e in range(E) if e != eb + 1 or E <= 4])
+    idx = np.stack([pool[rng.permutation(len(pool))[:k]] for _ in range(T)]).astype(np.int32)
+    xb = W.f32_to_bf16_bits(rng.standard_normal((T, d)).astype(np.float32))
+    x = H.bf16_to_dev(xb)
+    R_cap = T * k
+    off = torch.full((ec + 1,), -7, dtype=torch.int32, device=DEV)
+    rt = torch.full((R_cap,), -7, dtype=torch.int32, device=DEV)
+    sr = torch.full((T, k), -7, dtype=torch.int32, device=DEV)
+    xp = torch.zeros(R_cap, d, dtype=torch.bfloat16, device=DEV)
+    ws = torch.zeros(max(B.moe_permute_workspace_bytes(T, k, ec), 16), dtype=torch.uint8, device=DEV)
+    B.moe_permute(x, dev_i32(idx), E, eb, ec, off, rt, sr, xp, ws)
+    torch.cuda.synchronize()
+    roff, rrt, rsr, rxp = O.permute(O.decode_bf16(xb), idx, eb, ec)
+    R = int(roff[-1])
+    assert np.array_equal(off.cpu().numpy(), roff)
+    assert np.array_equal(sr.cpu().numpy(), rsr)
+    assert np.array_equal(rt.cpu().numpy()[:R], rrt)
+    assert np.all(rt.cpu().numpy()[R:] == -7)          # rows past R are left untouched
+    assert np.array_equal(H.bf16_from_dev(xp)[:R], rxp)
+    # twice the same call: same bits (no atomics, no races)
+    off2, rt2, sr2 = torch.zeros_like(off), torch.zeros_like(rt), torch.zeros_like(sr)
+    B.moe_permute(x, dev_i32(idx), E, eb, ec, off2, rt2, sr2, xp, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(off, off2) and torch.equal(sr, sr2) and torch.equal(rt[:R], rt2[:R])
+
+
+# ----------------------------------------------------------------------------- combine (+bwd), permute_bwd
+@pytest.mark.parametrize("T,E,k,d,eb,ec", [(256, 8, 2, 128, 0, 8), (500, 64, 8, 2048, 0, 64), (300, 16, 4, 4096, 4, 8),
+                                           (77, 6, 3, 264, 0, 6)])
+def test_combine_and_backward(T, E, k, d, eb, ec):
+    print(f"combine T={T} E={E} k={k} d={d}", flush=True)
+    rng = np.random.default_rng(T + d)
+    idx = random_topk(rng, T, E, k)
+    _, _, rsr, _ = O.permute(np.zeros((T, 1)), idx, eb, ec)
+    R_cap = T * k
+    ypb = W.f32_to_bf16_bits(rng.standard_normal((R_cap, d)).astype(np.float32))
+    doutb = W.f32_to_bf16_bits(rng.standard_normal((T, d)).astype(np.float32))
+    w = rng.random((T, k)).astype(np.float32)
+    yp, dout, sr, wt = H.bf16_to_dev(ypb), H.bf16_to_dev(doutb), dev_i32(rsr), torch.from_numpy(w).to(DEV)
+    out = torch.full((T, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dx = torch.full((T, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dyp = torch.zeros(R_cap, d, dtype=torch.bfloat16, device=DEV)
+    dgate = torch.full((T, k), float("nan"), dtype=torch.float32, device=DEV)
+    B.moe_unpermute_combine(yp, sr, wt, out)
+    B.moe_permute_bwd(yp, sr, dx)
+    B.moe_unpermute_combine_bwd(dout, yp, sr, wt, dyp, dgate)
+    torch.cuda.synchronize()
+    ypf, doutf, wf = O.decode_bf16(ypb), O.decode_bf16(doutb), w.astype(np.float64)
+    H.assert_close(H.bf16_from_dev(out), O.combine_fwd(ypf, rsr, wf), "out", 1e-2)
+    H.assert_close(H.bf16_from_dev(dx), O.permute_bwd(ypf, rsr), "dx", 1e-2)
+    rdyp, rdgate = O.combine_bwd(doutf, ypf, rsr, wf)
+    used = np.zeros(R_cap, bool)
+    used[rsr[rsr >= 0]] = True
+    H.assert_close(H.bf16_from_dev(dyp)[used], rdyp[used], "dyp", 1e-2)
+    assert np.all(H.bf16_from_dev(dyp)[~used] == 0)          # rows of no local slot are not written
+    H.assert_close(dgate.cpu().numpy().astype(np.float64), rdgate, "dgate", 1e-4)
+
+
+def test_permute_then_combine_is_identity():
+    T, E, k, d = 512, 16, 4, 512
+    rng = np.random.default_rng(9)
+    idx = random_topk(rng, T, E, k)
+    xb = W.f32_to_bf16_bits(rng.standard_normal((T, d)).astype(np.float32))
+    buf = B.MoELayerBuffers(T, d, E, k, 64)
+    x = H.bf16_to_dev(xb)
+    B.moe_permute(x, dev_i32(idx), E, 0, E, buf.expert_offsets, buf.row_token, buf.slot_row, buf.xp, buf.ws)
+    w = torch.full((T, k), 1.0 / k, dtype=torch.float32, device=DEV)
+    B.moe_unpermute_combine(buf.xp, buf.slot_row, w, buf.out)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.out.view(torch.int16), x.view(torch.int16))
+
+
+# ----------------------------------------------------------------------------- grouped GEMMs, isolated
+@pytest.mark.parametrize("counts,d,f", [
+    ([64, 64, 64, 64], 128, 256),                 # whole tiles only partly filled
+    ([300, 0, 5, 257, 256, 1, 0, 700], 192, 320),  # ragged rows and columns, empty experts
+    ([1100, 900], 512, 128),                      # several row tiles per expert
+    ([0, 0, 40], 64, 64),                         # leading empty experts, minimum sizes
+])
+def test_grouped_gemm_fwd_bwd_isolated(counts, d, f):
+    print(f"gemm counts={counts} d={d} f={f}", flush=True)
+    rng = np.random.default_rng(sum(counts) + d + f)
+    E = len(counts)
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    R = int(off[-1])
+    R_cap = R + 37                                   # capacity beyond R must stay untouched
+    mk = lambda shape, s: W.f32_to_bf16_bits((rng.standard_normal(shape) * s).astype(np.float32))
+    xpb, dypb = mk((R_cap, d), 1.0), mk((R_cap, d), 1.0)
+    Wgb, Wub, Wdb = mk((E, f, d), 0.05), mk((E, f, d), 0.05), mk((E, d, f), 0.05)
+    xp, dyp = H.bf16_to_dev(xpb), H.bf16_to_dev(dypb)
+    Wg, Wu, Wd = H.bf16_to_dev(Wgb), H.bf16_to_dev(Wub), H.bf16_to_dev(Wdb)
+    nanbf = lambda *s: torch.full(s, float("nan"), dtype=torch.bfloat16, device=DEV)
+    g, u, h, yp, dxp = nanbf(R_cap, f), nanbf(R_cap, f), nanbf(R_cap, f), nanbf(R_cap, d), nanbf(R_cap, d)
+    dWg, dWu, dWd = nanbf(E, f, d), nanbf(E, f, d), nanbf(E, d, f)
+    ws = torch.zeros(B.moe_grouped_gemm_bwd_workspace_bytes(R_cap, f), dtype=torch.uint8, device=DEV)
+    offd = dev_i32(off)
+    B.moe_grouped_gemm_fwd(xp, offd, Wg, Wu, Wd, g, u, h, yp)
+    torch.cuda.synchronize()
+    dec = O.decode_bf16
+    fw = O.expert_mlp_fwd(dec(xpb)[:R], off, dec(Wgb), dec(Wub), dec(Wdb))
+    got = {n: H.bf16_from_dev(t) for n, t in (("g", g), ("u", u), ("h", h), ("yp", yp))}
+    for n in ("g", "u", "h", "yp"):
+        H.assert_close(got[n][:R], fw[n], n)
+        assert np.all(np.isnan(got[n][R:])), f"{n}: rows beyond R were written"
+    # backward from the GPU's own saved activations (what a training step does)
+    B.moe_grouped_gemm_bwd(dyp, xp, g, u, h, offd, Wg, Wu, Wd, dxp, dWg, dWu, dWd, ws)
+    torch.cuda.synchronize()
+    bw = O.expert_mlp_bwd(dec(dypb)[:R], dec(xpb)[:R], got["g"][:R], got["u"][:R], got["h"][:R], off,
+                          dec(Wgb), dec(Wub), dec(Wdb))
+    gdxp = H.bf16_from_dev(dxp)
+    H.assert_close(gdxp[:R], bw["dxp"], "dxp")
+    assert np.all(np.isnan(gdxp[R:]))
+    for n, t in (("dWg", dWg), ("dWu", dWu), ("dWd", dWd)):
+        gw = H.bf16_from_dev(t)
+        for e in range(E):
+            if counts[e] == 0:
+                assert np.all(gw[e] == 0.0), f"{n}[{e}] must be zero"
+            else:
+                H.assert_close(gw[e], bw[n][e], f"{n}[{e}]")
+
+
+# ----------------------------------------------------------------------------- whole path, small configs
+@pytest.mark.parametrize("name", ["tiny", "skew"])
+def test_layer_small_configs(name):
+    print(f"layer {name}", flush=True)
+    cfg = W.CONFIGS[name]
+    inp = W.make_inputs(cfg)
+    res = H.run_layer(cfg, inp)
+    ref = O.layer_fwd_bwd(inp, cfg.k, cfg.e_begin, cfg.n_local, cfg.renormalize)
+    if name == "skew":
+        assert np.diff(ref["expert_offsets"]).min() == 0
+    H.compare_layer(res, ref, cfg.n_local)
+
+
+@pytest.mark.parametrize("T,d,E,k,f,eb,ec,renorm", [
+    (700, 192, 6, 3, 320, 0, 6, 1),       # ragged in every dimension
+    (2048, 256, 16, 4, 128, 4, 8, 0),     # expert-parallel share, gates not renormalised
+    (1500, 128, 4, 2, 64, 0, 4, 1),       # several row tiles per expert
+])
+def test_layer_ragged_shapes(T, d, E, k, f, eb, ec, renorm):
+    print(f"layer T={T} d={d} E={E} k={k} f={f} local=[{eb},{eb+ec}) renorm={renorm}", flush=True)
+    cfg = W.MoEConfig("custom", T=T, d=d, E=E, k=k, f=f, e_begin=eb, e_count=ec, renormalize=renorm, seed=T)
+    inp = W.make_inputs(cfg)
+    res = H.run_layer(cfg, inp)
+    ref = O.layer_fwd_bwd(inp, k, eb, ec, renorm)
+    H.compare_layer(res, ref, ec)
+
+
+def test_argument_checks():
+    t = torch.zeros(64, 64, dtype=torch.float32, device=DEV)
+    idx = torch.zeros(64, 2, dtype=torch.int32, device=DEV)
+    w = torch.zeros(64, 2, dtype=torch.float32, device=DEV)
+    lib = B.load()
+    assert lib.moe_route(None, 64, 64, 2, 1, B._p(idx), B._p(w), None) == -1
+    assert lib.moe_route(B._p(t), 64, 64, 65, 1, B._p(idx), B._p(w), None) == -1
+    assert lib.moe_route(B._p(t), 64, 1000, 2, 1, B._p(idx), B._p(w), None) == -1
+    assert lib.moe_route(t.data_ptr() + 4, 64, 64, 2, 1, B._p(idx), B._p(w), None) == -1
+    x = torch.zeros(64, 64, dtype=torch.bfloat16, device=DEV)
+    assert lib.moe_permute(B._p(x), B._p(idx), 64, 64, 8, 2, 0, 8, B._p(idx), B._p(idx), B._p(idx), B._p(x),
+                           B._p(x), 0, None) == -2
+    assert lib.moe_grouped_gemm_fwd(B._p(x), B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 60, 64,
+                                    B._p(x), B._p(x), B._p(x), B._p(x), None) == -1
+    torch.cuda.synchronize()
