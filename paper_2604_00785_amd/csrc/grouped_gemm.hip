@@ -3,18 +3,26 @@
 //
 // One workgroup (8 waves) computes one 256x256 output tile with a 64-deep
 // K step.  Both operand tiles live in LDS as [256 rows][64 k] bf16 (128 bytes
-// per row, 16-byte pieces XOR-swizzled by the row so that both the MFMA
-// fragment reads and the fill writes spread over the banks), double-buffered:
-// while the MFMAs consume one buffer, the next K step is already in flight from
-// global memory into registers and is written to the other buffer afterwards.
+// per row, 16-byte pieces XOR-swizzled by the row so that the MFMA fragment
+// reads and the fill writes spread over the banks), double-buffered: while the
+// MFMAs consume one buffer, the next K step is fetched into the other one.
 // The waves form a 2 (M) x 4 (N) grid; each owns a 128x64 piece = 4x2
 // v_mfma_f32_32x32x16_bf16 accumulators (128 fp32 registers per lane).
 //
 // An operand that is contiguous along K in memory (activations [rows, K],
-// forward weights [N, K]) goes to LDS as it is.  An operand that is contiguous
-// along the other dimension (weights in dgrad, both operands in wgrad) is
-// transposed in registers on its way to LDS: a thread loads a 4 (k) x 8 (n)
-// block with four 16-byte loads and writes eight 8-byte K-runs.
+// forward weights [N, K]) is fetched with direct-to-LDS loads
+// (global_load_lds_dwordx4): a wave instruction fills eight 128-byte LDS rows, and
+// the swizzle is applied on the global side (which 16-byte piece a lane reads).
+// An operand that is contiguous along the other dimension (weights in dgrad,
+// both operands in wgrad) is transposed in registers on its way to LDS: a thread
+// loads a 4 (k) x 8 (n) block with four 16-byte loads and writes eight 8-byte
+// K-runs.
+//
+// The MFMAs are issued as (weight fragment) x (activation fragment), so a lane
+// ends up with four consecutive output COLUMNS of one row.  The epilogue rounds
+// to bf16, stages each wave's 128x64 piece in that wave's own 16 KB of LDS and
+// writes it out in full 128-byte row segments; the SwiGLU forward and backward
+// formulas are applied on the way, on the fp32 accumulators.
 //
 // Tiles of the row-grouped products are found on the device from
 // expert_offsets: a workgroup turns its M-tile number into (expert, first row)
@@ -28,6 +36,12 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int GEMM_THREADS = 512;
 constexpr int TILE_BYTES = BM * BK * 2;              // one operand tile
 constexpr int LDS_BYTES = 2 * 2 * TILE_BYTES;        // A and B, double-buffered
+constexpr int WAVE_STAGE_BYTES = LDS_BYTES / 8;      // epilogue staging per wave (16 KB)
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 enum GemmMode { GATE_UP = 0, DOWN = 1, DGRAD_H = 2, DGRAD_X = 3, WGRAD = 4 };
 
@@ -54,38 +68,24 @@ struct GemmArgs {
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row ^ (row >> 3)) & 7); }
 
-// ---- global -> registers ----------------------------------------------------
-// K-contiguous operand: thread covers rows tid/8 + 64*i (i<4), 16-byte piece tid%8.
-// K-strided operand: thread covers k rows (tid/32)*4 + j (j<4), columns (tid%32)*8 .. +8.
-// Either way a thread stages four 16-byte pieces per operand.
-struct Staged { uint4 v[4]; };
-
-__device__ __forceinline__ void store_kc(const Staged& r, char* tile, int tid) {
-  const int c = tid & 7;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = (tid >> 3) + 64 * i;
-    *reinterpret_cast<uint4*>(tile + row * 128 + swz(row, c) * 16) = r.v[i];
-  }
-}
+// K-strided operand: a thread stages k rows (tid/32)*4 + j (j<4), columns (tid%32)*8 .. +8.
+struct Staged { u32x4 v[4]; };
 
 __device__ __forceinline__ void store_ks(const Staged& r, char* tile, int tid) {
   const int nb = tid & 31, kq = tid >> 5;
   const int chunk = kq >> 1, half = kq & 1;
-  const uint32_t w0[4] = {r.v[0].x, r.v[0].y, r.v[0].z, r.v[0].w};
-  const uint32_t w1[4] = {r.v[1].x, r.v[1].y, r.v[1].z, r.v[1].w};
-  const uint32_t w2[4] = {r.v[2].x, r.v[2].y, r.v[2].z, r.v[2].w};
-  const uint32_t w3[4] = {r.v[3].x, r.v[3].y, r.v[3].z, r.v[3].w};
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
     const int row = nb * 8 + q;
     const uint32_t sel = (q & 1) ? 0x07060302u : 0x05040100u;
-    uint2 o;
-    o.x = __builtin_amdgcn_perm(w1[q >> 1], w0[q >> 1], sel);  // k0 (low half), k1 (high half)
-    o.y = __builtin_amdgcn_perm(w3[q >> 1], w2[q >> 1], sel);  // k2, k3
-    *reinterpret_cast<uint2*>(tile + row * 128 + swz(row, chunk) * 16 + half * 8) = o;
+    u32x2 o;
+    o.x = __builtin_amdgcn_perm(r.v[1][q >> 1], r.v[0][q >> 1], sel);  // k0 (low half), k1 (high half)
+    o.y = __builtin_amdgcn_perm(r.v[3][q >> 1], r.v[2][q >> 1], sel);  // k2, k3
+    *reinterpret_cast<u32x2*>(tile + row * 128 + swz(row, chunk) * 16 + half * 8) = o;
   }
 }
+
+__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + expf(-g)); }
 
 template <int MODE>
 __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) {
@@ -137,14 +137,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   }
   const int n0 = nt * (MODE == GATE_UP ? BN / 2 : BN);
 
+  constexpr bool A_KS = (MODE == WGRAD);
+  constexpr bool B_KS = (MODE == WGRAD || MODE == DGRAD_H || MODE == DGRAD_X);
+
   // ---------------- operand sources -------------------------------------------
   // A tile rows <-> output rows m0 + r ; B tile rows <-> output columns.
-  const uint16_t* pa[4];   // per-thread row pointers (KC) or column pointer (KS, pa[0])
-  const uint16_t* pb[4];
-  ptrdiff_t a_phase = 0, b_phase = 0;   // element offset added for the second K phase
-  int k_lo = 0, k_hi = 0;            // WGRAD: expert's row range (the reduction)
+  // K-contiguous operands: wave w issues 4 direct-to-LDS loads per K step; load i fills LDS
+  // rows (4w+i)*8 .. +8, lane l -> row + l/8, physical piece l%8, i.e. logical piece swz(row, l%8).
+  const uint16_t* da[4];
+  const uint16_t* db[4];
+  const uint16_t* pa = nullptr;   // K-strided operands: this thread's column pointer
+  const uint16_t* pb = nullptr;
+  ptrdiff_t a_phase = 0, b_phase = 0;   // element offset of the second K phase (DGRAD_X)
+  int k_lo = 0, k_hi = 0;               // WGRAD: the expert's row range is the reduction
   int nk;
-  size_t lda, ldb;
+  size_t lda = 0, ldb = 0;
 
   if constexpr (MODE == WGRAD) {
     k_lo = a.offsets[e];
@@ -155,91 +162,94 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     const int nb = tid & 31;
     int ca = m0 + nb * 8;  if (ca > a.M - 8) ca = a.M - 8;
     int cb = n0 + nb * 8;  if (cb > a.N - 8) cb = a.N - 8;
-    pa[0] = a.A0 + ca;
-    pb[0] = a.B0 + cb;
+    pa = a.A0 + ca;
+    pb = a.B0 + cb;
   } else {
     nk = a.K / BK;
-    lda = a.K;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      int r = m0 + (tid >> 3) + 64 * i;
+      const int row = (wave * 4 + i) * 8 + (lane >> 3);
+      const int piece = swz(row, lane & 7);
+      int r = m0 + row;
       if (r > m_end - 1) r = m_end - 1;
-      pa[i] = a.A0 + static_cast<size_t>(r) * lda + (tid & 7) * 8;
+      da[i] = a.A0 + static_cast<size_t>(r) * a.K + piece * 8;
     }
     if constexpr (MODE == DGRAD_X) { a_phase = a.A1 - a.A0; nk *= 2; }
-    if constexpr (MODE == GATE_UP || MODE == DOWN) {
-      ldb = a.K;
-      const size_t wsz = static_cast<size_t>(a.N) * a.K;
+    const size_t wsz = static_cast<size_t>(a.N) * a.K;
+    if constexpr (!B_KS) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int r = (tid >> 3) + 64 * i;   // LDS row of the B tile
+        const int row = (wave * 4 + i) * 8 + (lane >> 3);   // LDS row of the B tile
+        const int piece = swz(row, lane & 7);
         const uint16_t* w = a.B0;
-        int col = n0 + r;
+        int col = n0 + row;
         if constexpr (MODE == GATE_UP) {
-          if (r >= BN / 2) { w = a.B1; col = n0 + r - BN / 2; }
+          if (row >= BN / 2) { w = a.B1; col = n0 + row - BN / 2; }
         }
         if (col > a.N - 1) col = a.N - 1;
-        pb[i] = w + static_cast<size_t>(e) * wsz + static_cast<size_t>(col) * ldb + (tid & 7) * 8;
+        db[i] = w + static_cast<size_t>(e) * wsz + static_cast<size_t>(col) * a.K + piece * 8;
       }
     } else {  // DGRAD_H / DGRAD_X: weights stored [K][N]
       ldb = a.N;
-      const size_t wsz = static_cast<size_t>(a.N) * a.K;
       int cb = n0 + (tid & 31) * 8;
       if (cb > a.N - 8) cb = a.N - 8;
-      pb[0] = a.B0 + static_cast<size_t>(e) * wsz + cb;
+      pb = a.B0 + static_cast<size_t>(e) * wsz + cb;
       if constexpr (MODE == DGRAD_X) b_phase = a.B1 - a.B0;
     }
   }
-  constexpr bool A_KS = (MODE == WGRAD);
-  constexpr bool B_KS = (MODE == WGRAD || MODE == DGRAD_H || MODE == DGRAD_X);
 
   Staged ra, rb;
 
-  auto load_tiles = [&](int kt) {
-    // K offset inside the phase, and the phase offset
+  // Starts the fetch of K step kt into LDS buffer `buf`: direct-to-LDS loads land there by
+  // themselves; K-strided operands arrive in ra / rb and are written by finish_fetch().
+  auto start_fetch = [&](int kt, int buf) {
     int kk = kt;
     ptrdiff_t offa = 0, offb = 0;
     if constexpr (MODE == DGRAD_X) {
       const int half = nk >> 1;
       if (kt >= half) { kk = kt - half; offa = a_phase; offb = b_phase; }
     }
+    char* ta = lds + buf * 2 * TILE_BYTES;
+    char* tb = ta + TILE_BYTES;
+    if constexpr (!A_KS) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(da[i] + offa + static_cast<size_t>(kk) * BK),
+                                         LDS_PTR(ta + (wave * 4 + i) * 1024), 16, 0, 0);
+    }
+    if constexpr (!B_KS) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(db[i] + static_cast<size_t>(kk) * BK),
+                                         LDS_PTR(tb + (wave * 4 + i) * 1024), 16, 0, 0);
+    }
+    const int kq = tid >> 5;
     if constexpr (A_KS) {
-      const int kq = tid >> 5;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int r = k_lo + kk * BK + kq * 4 + j;
-        ra.v[j] = r < k_hi ? *reinterpret_cast<const uint4*>(pa[0] + static_cast<size_t>(r) * lda)
-                              : make_uint4(0, 0, 0, 0);
+        ra.v[j] = r < k_hi ? *reinterpret_cast<const u32x4*>(pa + static_cast<size_t>(r) * lda) : u32x4{0, 0, 0, 0};
       }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        ra.v[i] = *reinterpret_cast<const uint4*>(pa[i] + offa + static_cast<size_t>(kk) * BK);
     }
     if constexpr (B_KS) {
-      const int kq = tid >> 5;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         if constexpr (MODE == WGRAD) {
           const int r = k_lo + kk * BK + kq * 4 + j;
-          rb.v[j] = r < k_hi ? *reinterpret_cast<const uint4*>(pb[0] + static_cast<size_t>(r) * ldb)
-                                : make_uint4(0, 0, 0, 0);
+          rb.v[j] = r < k_hi ? *reinterpret_cast<const u32x4*>(pb + static_cast<size_t>(r) * ldb) : u32x4{0, 0, 0, 0};
         } else {
           const int r = kk * BK + kq * 4 + j;
-          rb.v[j] = *reinterpret_cast<const uint4*>(pb[0] + offb + static_cast<size_t>(r) * ldb);
+          rb.v[j] = *reinterpret_cast<const u32x4*>(pb + offb + static_cast<size_t>(r) * ldb);
         }
       }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        rb.v[i] = *reinterpret_cast<const uint4*>(pb[i] + static_cast<size_t>(kk) * BK);
     }
   };
-  auto store_tiles = [&](int buf) {
+  auto finish_fetch = [&](int buf) {
     char* ta = lds + buf * 2 * TILE_BYTES;
     char* tb = ta + TILE_BYTES;
-    if constexpr (A_KS) store_ks(ra, ta, tid); else store_kc(ra, ta, tid);
-    if constexpr (B_KS) store_ks(rb, tb, tid); else store_kc(rb, tb, tid);
+    if constexpr (A_KS) store_ks(ra, ta, tid);
+    if constexpr (B_KS) store_ks(rb, tb, tid);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads have landed
   };
 
   // ---------------- main loop ----------------------------------------------------
@@ -252,11 +262,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int lrow = lane & 31, lgrp = lane >> 5;
-  if (nk > 0) {
-    load_tiles(0);
-    store_tiles(0);
-  }
-  __syncthreads();
+  int arow[4], brow[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) arow[i] = wm * 128 + i * 32 + lrow;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) brow[j] = (MODE == GATE_UP) ? j * 128 + wn * 32 + lrow : wn * 64 + j * 32 + lrow;
+
   auto compute = [&](int buf) {
     const char* ta = lds + buf * 2 * TILE_BYTES;
     const char* tb = ta + TILE_BYTES;
@@ -265,70 +276,162 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       bf16x8_t fa[4], fb[2];
       const int chunk = ks * 2 + lgrp;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = wm * 128 + i * 32 + lrow;
-        fa[i] = *reinterpret_cast<const bf16x8_t*>(ta + row * 128 + swz(row, chunk) * 16);
-      }
+      for (int i = 0; i < 4; ++i)
+        fa[i] = *reinterpret_cast<const bf16x8_t*>(ta + arow[i] * 128 + swz(arow[i], chunk) * 16);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int row = j * 128 + wn * 32 + lrow;
-        fb[j] = *reinterpret_cast<const bf16x8_t*>(tb + row * 128 + swz(row, chunk) * 16);
-      }
+      for (int j = 0; j < 2; ++j)
+        fb[j] = *reinterpret_cast<const bf16x8_t*>(tb + brow[j] * 128 + swz(brow[j], chunk) * 16);
+      // weight fragment first: the lane then holds 4 consecutive output columns of one row
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
   };
-  // steady state: the next K step is loaded while this one is multiplied
+
+  if (nk > 0) {
+    start_fetch(0, 0);
+    finish_fetch(0);
+  }
+  __syncthreads();
   for (int kt = 0; kt + 1 < nk; ++kt) {
-    load_tiles(kt + 1);
+    start_fetch(kt + 1, (kt + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);     // keep the fetch ahead of the math
     compute(kt & 1);
-    store_tiles((kt + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    finish_fetch((kt + 1) & 1);
     __syncthreads();
   }
   if (nk > 0) compute((nk - 1) & 1);
+  __syncthreads();                          // every wave is done with the operand tiles
 
   // ---------------- epilogue -----------------------------------------------------
-  // acc[i][j][r] is element (row, col) of the tile with
-  //   row = wm*128 + i*32 + (r/4)*8 + lgrp*4 + r%4,  col = j*128 + wn*32 + lrow.
+  // acc[i][j][4q+c] is the wave's element (row, col) with row = i*32 + lrow and
+  // col = j*32 + q*8 + lgrp*4 + c.  The wave stages bf16 rows of 128 bytes in its own
+  // 16 KB of LDS (16-byte pieces swizzled by row & 7) and stores 16 bytes per lane.
+  char* stage = lds + wave * WAVE_STAGE_BYTES;
+  const int grow0 = m0 + wm * 128;                                   // wave's first output row
+  const int gcol0 = n0 + wn * (MODE == GATE_UP ? 32 : 64);           // wave's first output column
+  auto quad_addr = [&](int row, int piece) -> char* {
+    return stage + row * 128 + ((piece ^ (row & 7)) << 4) + lgrp * 8;
+  };
+  auto put_quad = [&](int row, int piece, float v0, float v1, float v2, float v3) {
+    u32x2 o;
+    o.x = pack_bf16(v0, v1);
+    o.y = pack_bf16(v2, v3);
+    *reinterpret_cast<u32x2*>(quad_addr(row, piece)) = o;
+  };
+  // stores `rows` staged rows starting at staged row 0 to out (row stride ld); the first
+  // `pieces` 16-byte pieces of each row go to columns col0 + piece*8 (pieces = 4 or 8)
+  auto flush = [&](uint16_t* out, size_t ld, int first_row, int rows, int piece0, int pieces, int col0, int ncols) {
+    const int rpp = 64 / pieces;                    // rows per pass
+    for (int p = 0; p < rows / rpp; ++p) {
+      const int row = p * rpp + lane / pieces;
+      const int piece = lane % pieces;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * 128 + (((piece0 + piece) ^ (row & 7)) << 4));
+      const int gr = first_row + row, gc = col0 + piece * 8;
+      if (gr < m_end && gc < ncols) *reinterpret_cast<u32x4*>(out + static_cast<size_t>(gr) * ld + gc) = v;
+    }
+  };
+
+  if constexpr (MODE == GATE_UP) {
+    // pass 1: g in pieces 0-3, u in pieces 4-7
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = m0 + wm * 128 + i * 32 + (r >> 2) * 8 + lgrp * 4 + (r & 3);
-      if (row >= m_end) continue;
-      if constexpr (MODE == GATE_UP) {
-        const int col = n0 + wn * 32 + lrow;
-        if (col < a.N) {
-          const float gv = acc[i][0][r], uv = acc[i][1][r];
-          const float hv = gv / (1.0f + expf(-gv)) * uv;
-          const size_t o = static_cast<size_t>(row) * a.N + col;
-          a.O0[o] = f32_to_bf16(gv);
-          a.O1[o] = f32_to_bf16(uv);
-          a.O2[o] = f32_to_bf16(hv);
-        }
-      } else {
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int col = n0 + j * 128 + wn * 32 + lrow;
-          if (col >= a.N) continue;
-          const float v = acc[i][j][r];
-          if constexpr (MODE == DGRAD_H) {
-            const size_t o = static_cast<size_t>(row) * a.N + col;
-            const float gv = bf16_to_f32(a.G[o]), uv = bf16_to_f32(a.U[o]);
-            const float s = 1.0f / (1.0f + expf(-gv));
-            a.O0[o] = f32_to_bf16(v * uv * s * (1.0f + gv * (1.0f - s)));
-            a.O1[o] = f32_to_bf16(v * gv * s);
-          } else if constexpr (MODE == WGRAD) {
-            a.O0[(static_cast<size_t>(e) * a.M + row) * a.N + col] = f32_to_bf16(v);
-          } else {
-            a.O0[static_cast<size_t>(row) * a.N + col] = f32_to_bf16(v);
+        for (int q = 0; q < 4; ++q)
+          put_quad(i * 32 + lrow, j * 4 + q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+    __builtin_amdgcn_wave_barrier();
+    flush(a.O0, a.N, grow0, 128, 0, 4, gcol0, a.N);
+    flush(a.O1, a.N, grow0, 128, 4, 4, gcol0, a.N);
+    __builtin_amdgcn_wave_barrier();
+    // pass 2: h = silu(g) * u from the fp32 accumulators
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float h[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) h[c] = silu_f(acc[i][0][4 * q + c]) * acc[i][1][4 * q + c];
+        put_quad(i * 32 + lrow, q, h[0], h[1], h[2], h[3]);
+      }
+    __builtin_amdgcn_wave_barrier();
+    flush(a.O2, a.N, grow0, 128, 0, 4, gcol0, a.N);
+  } else if constexpr (MODE == DGRAD_H) {
+    // two halves of 64 rows: g rows at stage[0, 8K), u rows at stage[8K, 16K)
+    char* ustage = stage + WAVE_STAGE_BYTES / 2;
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int first = grow0 + hh * 64;
+      for (int p = 0; p < 8; ++p) {
+        const int row = p * 8 + (lane >> 3), piece = lane & 7;
+        int gr = first + row;  if (gr > m_end - 1) gr = m_end - 1;
+        int gc = gcol0 + piece * 8;  if (gc > a.N - 8) gc = a.N - 8;
+        const size_t o = static_cast<size_t>(gr) * a.N + gc;
+        const u32x4 gv = *reinterpret_cast<const u32x4*>(a.G + o);
+        const u32x4 uv = *reinterpret_cast<const u32x4*>(a.U + o);
+        const int so = row * 128 + ((piece ^ (row & 7)) << 4);
+        *reinterpret_cast<u32x4*>(stage + so) = gv;
+        *reinterpret_cast<u32x4*>(ustage + so) = uv;
+      }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int row = i2 * 32 + lrow;
+            char* ga = quad_addr(row, j * 4 + q);
+            char* ua = ga + WAVE_STAGE_BYTES / 2;
+            const u32x2 gq = *reinterpret_cast<const u32x2*>(ga);
+            const u32x2 uq = *reinterpret_cast<const u32x2*>(ua);
+            const float g4[4] = {bf16lo(gq.x), bf16hi(gq.x), bf16lo(gq.y), bf16hi(gq.y)};
+            const float u4[4] = {bf16lo(uq.x), bf16hi(uq.x), bf16lo(uq.y), bf16hi(uq.y)};
+            float dg[4], du[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const float dh = acc[hh * 2 + i2][j][4 * q + c];
+              const float sg = 1.0f / (1.0f + expf(-g4[c]));
+              dg[c] = dh * u4[c] * sg * (1.0f + g4[c] * (1.0f - sg));
+              du[c] = dh * g4[c] * sg;
+            }
+            u32x2 o;
+            o.x = pack_bf16(dg[0], dg[1]);  o.y = pack_bf16(dg[2], dg[3]);
+            *reinterpret_cast<u32x2*>(ga) = o;
+            o.x = pack_bf16(du[0], du[1]);  o.y = pack_bf16(du[2], du[3]);
+            *reinterpret_cast<u32x2*>(ua) = o;
           }
+      __builtin_amdgcn_wave_barrier();
+      for (int p = 0; p < 8; ++p) {
+        const int row = p * 8 + (lane >> 3), piece = lane & 7;
+        const int so = row * 128 + ((piece ^ (row & 7)) << 4);
+        const u32x4 dgv = *reinterpret_cast<const u32x4*>(stage + so);
+        const u32x4 duv = *reinterpret_cast<const u32x4*>(ustage + so);
+        const int gr = first + row, gc = gcol0 + piece * 8;
+        if (gr < m_end && gc < a.N) {
+          const size_t o = static_cast<size_t>(gr) * a.N + gc;
+          *reinterpret_cast<u32x4*>(a.O0 + o) = dgv;
+          *reinterpret_cast<u32x4*>(a.O1 + o) = duv;
         }
       }
+      __builtin_amdgcn_wave_barrier();
     }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          put_quad(i * 32 + lrow, j * 4 + q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+    __builtin_amdgcn_wave_barrier();
+    uint16_t* out = a.O0;
+    if constexpr (MODE == WGRAD) out += static_cast<size_t>(e) * a.M * a.N;
+    flush(out, a.N, grow0, 128, 0, 8, gcol0, a.N);
   }
 }
 
