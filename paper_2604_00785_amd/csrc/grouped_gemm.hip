@@ -68,11 +68,15 @@ struct GemmArgs {
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row ^ (row >> 3)) & 7); }
 
-// K-strided operand: a thread stages k rows (tid/32)*4 + j (j<4), columns (tid%32)*8 .. +8.
+// K-strided operand: a thread stages k rows ks_kq*4 + j (j<4), columns ks_nb*8 .. +8.  Inside a
+// group of 32 lanes nb takes 8 values and kq 4, so that one transposing LDS write spreads over
+// 16 different 8-byte bank groups, and one global load covers 256 contiguous bytes of 4 rows.
 struct Staged { u32x4 v[4]; };
+__device__ __forceinline__ int ks_nb(int tid) { return ((tid >> 5) & 3) * 8 + (tid & 7); }
+__device__ __forceinline__ int ks_kq(int tid) { return (tid >> 7) * 4 + ((tid >> 3) & 3); }
 
 __device__ __forceinline__ void store_ks(const Staged& r, char* tile, int tid) {
-  const int nb = tid & 31, kq = tid >> 5;
+  const int nb = ks_nb(tid), kq = ks_kq(tid);
   const int chunk = kq >> 1, half = kq & 1;
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
@@ -85,7 +89,12 @@ __device__ __forceinline__ void store_ks(const Staged& r, char* tile, int tid) {
   }
 }
 
-__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + expf(-g)); }
+// sigmoid through the hardware exp2 and reciprocal (each about 1 ulp): far inside bf16 rounding.
+// exp2 overflows to +inf for very negative g and the reciprocal then returns 0, as it should.
+__device__ __forceinline__ float sigmoid_f(float g) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+}
+__device__ __forceinline__ float silu_f(float g) { return g * sigmoid_f(g); }
 
 template <int MODE>
 __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) {
@@ -159,7 +168,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     nk = (k_hi - k_lo + BK - 1) / BK;
     lda = a.M;
     ldb = a.N;
-    const int nb = tid & 31;
+    const int nb = ks_nb(tid);
     int ca = m0 + nb * 8;  if (ca > a.M - 8) ca = a.M - 8;
     int cb = n0 + nb * 8;  if (cb > a.N - 8) cb = a.N - 8;
     pa = a.A0 + ca;
@@ -191,7 +200,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       }
     } else {  // DGRAD_H / DGRAD_X: weights stored [K][N]
       ldb = a.N;
-      int cb = n0 + (tid & 31) * 8;
+      int cb = n0 + ks_nb(tid) * 8;
       if (cb > a.N - 8) cb = a.N - 8;
       pb = a.B0 + static_cast<size_t>(e) * wsz + cb;
       if constexpr (MODE == DGRAD_X) b_phase = a.B1 - a.B0;
@@ -223,7 +232,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
         __builtin_amdgcn_global_load_lds(GLOBAL_PTR(db[i] + static_cast<size_t>(kk) * BK),
                                          LDS_PTR(tb + (wave * 4 + i) * 1024), 16, 0, 0);
     }
-    const int kq = tid >> 5;
+    const int kq = ks_kq(tid);
     if constexpr (A_KS) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -395,7 +404,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
               const float dh = acc[hh * 2 + i2][j][4 * q + c];
-              const float sg = 1.0f / (1.0f + expf(-g4[c]));
+              const float sg = sigmoid_f(g4[c]);
               dg[c] = dh * u4[c] * sg * (1.0f + g4[c] * (1.0f - sg));
               du[c] = dh * g4[c] * sg;
             }

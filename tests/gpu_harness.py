@@ -28,8 +28,31 @@ def to_bf16_bits(a: np.ndarray) -> np.ndarray:
     return W.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))
 
 
-def run_layer(cfg: W.MoEConfig, inp: Dict[str, np.ndarray], device="cuda:0") -> Dict[str, np.ndarray]:
-    """Whole hot path on the GPU for one generated batch; returns numpy results."""
+class DeviceResults:
+    """Results left on the device; rows are brought to the host on demand (large configs)."""
+
+    def __init__(self, tensors: Dict[str, torch.Tensor]):
+        self.t = tensors
+
+    def _sel(self, name, idx):
+        t = self.t[name]
+        if idx is None:
+            return t
+        if isinstance(idx, slice):
+            return t[idx]
+        return t[torch.from_numpy(np.asarray(idx, dtype=np.int64)).to(t.device)]
+
+    def rows(self, name, idx=None) -> np.ndarray:
+        t = self._sel(name, idx)
+        return bf16_from_dev(t) if t.dtype == torch.bfloat16 else t.cpu().numpy()
+
+    def bits(self, name, idx=None) -> np.ndarray:
+        return self._sel(name, idx).contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def run_layer(cfg: W.MoEConfig, inp: Dict[str, np.ndarray], device="cuda:0", keep_on_device=False):
+    """Whole hot path on the GPU for one generated batch; returns numpy results
+    (or a DeviceResults when keep_on_device is set)."""
     buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.e_begin, cfg.n_local, cfg.renormalize, device)
     x, dout = bf16_to_dev(inp["x"], device), bf16_to_dev(inp["dout"], device)
     Wg, Wu, Wd = (bf16_to_dev(inp[n], device) for n in ("Wg", "Wu", "Wd"))
@@ -39,6 +62,8 @@ def run_layer(cfg: W.MoEConfig, inp: Dict[str, np.ndarray], device="cuda:0") -> 
         getattr(buf, n).fill_(float("nan"))
     buf.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
     torch.cuda.synchronize()
+    if keep_on_device:
+        return DeviceResults(buf.results())
     res = {}
     for n, t in buf.results().items():
         res[n] = bf16_from_dev(t) if t.dtype == torch.bfloat16 else t.cpu().numpy()

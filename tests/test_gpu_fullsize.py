@@ -1,0 +1,83 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle cannot run a whole OLMoE-sized layer in test time, so routing and the
+permutation are compared in full (bit-exact; they are cheap on the CPU) and the
+floating-point results are compared on samples the oracle computes exactly:
+ * whole experts: the sub-batch of all tokens routed to expert e, with e as the
+   only local expert, gives that expert's rows of g, u, h, yp, dyp, dxp and its
+   weight gradients;
+ * whole tokens: a sub-batch of sampled tokens through all local experts gives
+   out, dx and dgate of those tokens (tokens are independent of each other).
+"""
+import numpy as np
+import pytest
+
+from oracle import moe_oracle as O
+from paper_2604_00785_amd import workloads as W
+
+import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def sub_batch(inp, tokens, e_lo, e_hi):
+    s = {k: inp[k][tokens] for k in ("x", "dout", "logits")}
+    for k in ("Wg", "Wu", "Wd"):
+        s[k] = inp[k][e_lo:e_hi]
+    return s
+
+
+@pytest.mark.parametrize("name", ["olmoe", "fine", "ep_share"])
+def test_full_size_config(name):
+    cfg = W.CONFIGS[name]
+    print(f"full size {name}: generating inputs", flush=True)
+    inp = W.make_inputs(cfg)
+    print("running the HIP path", flush=True)
+    res = H.run_layer(cfg, inp, keep_on_device=True)
+    T, k, nl, eb = cfg.T, cfg.k, cfg.n_local, cfg.e_begin
+
+    # ---- routing and permutation: in full, bit-exact --------------------------------
+    print("routing / permutation", flush=True)
+    ridx, rw = O.route(inp["logits"], k, cfg.renormalize)
+    assert np.array_equal(res.rows("topk_idx"), ridx)
+    gpu_w = res.rows("topk_w")
+    np.testing.assert_allclose(gpu_w, rw, rtol=H.GATE_TOL)
+    roff, rrt, rsr, _ = O.permute(np.zeros((T, 1)), ridx, eb, nl)
+    R = int(roff[-1])
+    assert np.array_equal(res.rows("expert_offsets"), roff)
+    assert np.array_equal(res.rows("slot_row"), rsr)
+    assert np.array_equal(res.rows("row_token", slice(0, R)), rrt)
+    for a in range(0, R, 16384):                       # xp is an exact gather of x
+        b = min(R, a + 16384)
+        assert np.array_equal(res.bits("xp", slice(a, b)), inp["x"][rrt[a:b]]), "xp is not an exact gather of x"
+    # properties that hold at any size
+    local = (ridx >= eb) & (ridx < eb + nl)
+    assert R == int(local.sum()) and (nl < cfg.E or R == T * k)
+    assert np.array_equal(np.sort(rsr[local]), np.arange(R))
+    np.testing.assert_allclose(gpu_w.sum(1), 1.0, atol=1e-5)
+
+    # ---- whole experts -----------------------------------------------------------------
+    rng = np.random.default_rng(1)
+    counts = np.diff(roff)
+    picks = sorted({0, nl - 1, int(np.argmax(counts)), int(np.argmin(counts)), int(rng.integers(nl))})
+    for e in picks:
+        a, b = int(roff[e]), int(roff[e + 1])
+        print(f"expert {e}: rows [{a},{b})", flush=True)
+        if a == b:
+            for n in ("dWg", "dWu", "dWd"):
+                assert np.all(res.rows(n, slice(e, e + 1)) == 0.0)
+            continue
+        tokens = rrt[a:b]
+        ref = O.layer_fwd_bwd(sub_batch(inp, tokens, e, e + 1), k, eb + e, 1, cfg.renormalize)
+        assert int(ref["expert_offsets"][-1]) == b - a
+        for n in ("g", "u", "h", "yp", "dyp", "dxp"):
+            H.assert_close(res.rows(n, slice(a, b)), ref[n], f"{n}[expert {e}]")
+        for n in ("dWg", "dWu", "dWd"):
+            H.assert_close(res.rows(n, slice(e, e + 1))[0], ref[n][0], f"{n}[{e}]")
+
+    # ---- whole tokens ---------------------------------------------------------------------
+    tokens = np.sort(rng.choice(T, size=48, replace=False))
+    print("sampled tokens through every local expert", flush=True)
+    ref = O.layer_fwd_bwd(sub_batch(inp, tokens, 0, nl), k, eb, nl, cfg.renormalize)
+    for n in ("out", "dx", "dgate"):
+        H.assert_close(res.rows(n, tokens), ref[n], f"{n}[sampled tokens]")
