@@ -61,7 +61,7 @@ struct GemmArgs {
   int K;                // reduction length of one phase (modes 0-3)
   int N;                // output columns (per half for GATE_UP)
   int n_tiles;          // column tiles
-  int m_tiles_cap;      // upper bound on row tiles (modes 0-3)
+  int m_tiles_cap;      // upper bound on row tiles (modes 0-3); row tiles of one dW (WGRAD)
   // WGRAD: out[e][M][N] = sum over the expert's rows of A[r][M] * B[r][N]
   int M;
 };
@@ -99,52 +99,73 @@ __device__ __forceinline__ float silu_f(float g) { return g * sigmoid_f(g); }
 template <int MODE>
 __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  __shared__ int s_tile[3];
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  __shared__ int s_pref[MOE_MAX_EXPERTS + 1];   // exclusive prefix of row tiles per expert (modes 0-3)
+  const int tid0 = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
   const int wm = wave >> 2, wn = wave & 3;
 
-  // ---------------- which tile ------------------------------------------------
-  int e, m0, m_end, nt;
+  // ---------------- tile list ---------------------------------------------------
+  // The launch is persistent: gridDim.x workgroups (one per compute unit) walk the tile list.
+  // Workgroups are dealt to the 8 XCDs round-robin, so workgroup b takes position
+  // (b % 8) * (gridDim.x / 8) + b / 8 of every round: each XCD then works on a run of
+  // consecutive tiles (same expert, neighbouring panels) that share its L2.
+  int total;
   if constexpr (MODE == WGRAD) {
-    e = blockIdx.y;
-    nt = blockIdx.x % a.n_tiles;
-    m0 = (blockIdx.x / a.n_tiles) * BM;   // output row of dW
-    m_end = a.M;
+    total = a.E * a.m_tiles_cap * a.n_tiles;
   } else {
-    nt = blockIdx.x % a.n_tiles;
-    const int mt = blockIdx.x / a.n_tiles;
-    if (tid == 0) s_tile[0] = -1;
-    __syncthreads();
     if (wave == 0) {
       int base = 0;
       for (int e0 = 0; e0 < a.E; e0 += 64) {
+        const int lane = tid0 & 63;
         const int ee = e0 + lane;
-        const int o0 = ee < a.E ? a.offsets[ee] : 0;
-        const int o1 = ee < a.E ? a.offsets[ee + 1] : 0;
-        const int tiles = (o1 - o0 + BM - 1) / BM;
+        const int rows = ee < a.E ? a.offsets[ee + 1] - a.offsets[ee] : 0;
+        const int tiles = (rows + BM - 1) / BM;
         int inc = tiles;
 #pragma unroll
         for (int s = 1; s < 64; s <<= 1) {
           const int v = __shfl_up(inc, s, 64);
           if (lane >= s) inc += v;
         }
-        const int exc = base + inc - tiles;
-        if (mt >= exc && mt < exc + tiles) {
-          s_tile[0] = ee;
-          s_tile[1] = o0 + (mt - exc) * BM;
-          s_tile[2] = o1;
-        }
+        if (ee < a.E) s_pref[ee] = base + inc - tiles;
         base += __shfl(inc, 63, 64);
       }
+      if ((tid0 & 63) == 0) s_pref[a.E] = base;
     }
     __syncthreads();
-    e = s_tile[0];
-    if (e < 0) return;
-    m0 = s_tile[1];
-    m_end = s_tile[2];
+    total = s_pref[a.E] * a.n_tiles;
+  }
+  const int per_xcd = gridDim.x >> 3;
+  const int first_tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+
+  for (int tile = first_tile; tile < total; tile += gridDim.x) {
+  // the thread id is laundered per tile so that lane-dependent address pieces are recomputed for
+  // every tile instead of staying live (and spilling) across the whole loop
+  int tid = tid0;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
+  int e, m0, m_end;
+  const int nt = tile % a.n_tiles;
+  if constexpr (MODE == WGRAD) {
+    const int rest = tile / a.n_tiles;
+    e = rest / a.m_tiles_cap;
+    m0 = (rest % a.m_tiles_cap) * BM;   // output row of dW
+    m_end = a.M;
+  } else {
+    const int mt = tile / a.n_tiles;
+    int lo = 0, hi = a.E;               // last expert whose first tile is <= mt
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (s_pref[mid] <= mt) lo = mid; else hi = mid;
+    }
+    e = lo;
+    m0 = a.offsets[e] + (mt - s_pref[e]) * BM;
+    m_end = a.offsets[e + 1];
   }
   const int n0 = nt * (MODE == GATE_UP ? BN / 2 : BN);
+  // 32-row fragments of this wave that hold at least one valid row (the others are skipped)
+  int nfa = (m_end - m0 - wm * 128 + 31) >> 5;
+  nfa = nfa < 0 ? 0 : (nfa > 4 ? 4 : nfa);
+  nfa = __builtin_amdgcn_readfirstlane(nfa);
 
   constexpr bool A_KS = (MODE == WGRAD);
   constexpr bool B_KS = (MODE == WGRAD || MODE == DGRAD_H || MODE == DGRAD_X);
@@ -285,17 +306,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       bf16x8_t fa[4], fb[2];
       const int chunk = ks * 2 + lgrp;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8_t*>(ta + arow[i] * 128 + swz(arow[i], chunk) * 16);
-#pragma unroll
       for (int j = 0; j < 2; ++j)
         fb[j] = *reinterpret_cast<const bf16x8_t*>(tb + brow[j] * 128 + swz(brow[j], chunk) * 16);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (i < nfa) fa[i] = *reinterpret_cast<const bf16x8_t*>(ta + arow[i] * 128 + swz(arow[i], chunk) * 16);
       // weight fragment first: the lane then holds 4 consecutive output columns of one row
 #pragma unroll
       for (int i = 0; i < 4; ++i)
+        if (i < nfa) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        }
     }
   };
 
@@ -442,10 +465,31 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     if constexpr (MODE == WGRAD) out += static_cast<size_t>(e) * a.M * a.N;
     flush(out, a.N, grow0, 128, 0, 8, gcol0, a.N);
   }
+  __syncthreads();   // the staging area becomes operand tiles again
+  }  // tile loop
+}
+
+// Workgroups of the persistent launch: one per compute unit (the 128 KB of LDS allow no more),
+// a multiple of 8 so that every XCD gets the same share, and no more than there can be tiles.
+int persistent_grid(long long max_tiles) {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) {
+      (void)hipGetLastError();
+      n = 256;
+    }
+    cus = n & ~7;
+  }
+  long long g = (max_tiles + 7) & ~7ll;
+  if (g > cus) g = cus;
+  if (g < 8) g = 8;
+  return static_cast<int>(g);
 }
 
 template <int MODE>
-int launch_gemm(const GemmArgs& a, dim3 grid, hipStream_t s, const char* name) {
+int launch_gemm(const GemmArgs& a, long long max_tiles, hipStream_t s, const char* name) {
+  const dim3 grid(persistent_grid(max_tiles));
   static bool configured = false;
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_gemm_kernel<MODE>),
@@ -496,14 +540,14 @@ extern "C" int moe_grouped_gemm_fwd(const moe_bf16* xp, const int32_t* expert_of
   // gate | up with the SwiGLU epilogue
   a.A0 = U16(xp); a.B0 = U16(Wg); a.B1 = U16(Wu); a.O0 = g; a.O1 = u; a.O2 = h;
   a.K = d; a.N = f; a.n_tiles = (f + BN / 2 - 1) / (BN / 2);
-  int rc = launch_gemm<GATE_UP>(a, dim3(a.n_tiles * m_tiles), s, "gemm_gate_up");
+  int rc = launch_gemm<GATE_UP>(a, static_cast<long long>(a.n_tiles) * m_tiles, s, "gemm_gate_up");
   if (rc != MOE_OK) return rc;
   // down
   GemmArgs b{};
   b.offsets = expert_offsets; b.E = E; b.m_tiles_cap = m_tiles;
   b.A0 = U16(h); b.B0 = U16(Wd); b.O0 = yp;
   b.K = f; b.N = d; b.n_tiles = (d + BN - 1) / BN;
-  return launch_gemm<DOWN>(b, dim3(b.n_tiles * m_tiles), s, "gemm_down");
+  return launch_gemm<DOWN>(b, static_cast<long long>(b.n_tiles) * m_tiles, s, "gemm_down");
 }
 
 extern "C" int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, const moe_bf16* g, const moe_bf16* u,
@@ -527,14 +571,14 @@ extern "C" int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, con
   a.offsets = expert_offsets; a.E = E; a.m_tiles_cap = m_tiles;
   a.A0 = U16(dyp); a.B0 = U16(Wd); a.G = U16(g); a.U = U16(u); a.O0 = dg; a.O1 = du;
   a.K = d; a.N = f; a.n_tiles = (f + BN - 1) / BN;
-  int rc = launch_gemm<DGRAD_H>(a, dim3(a.n_tiles * m_tiles), s, "gemm_dgrad_h");
+  int rc = launch_gemm<DGRAD_H>(a, static_cast<long long>(a.n_tiles) * m_tiles, s, "gemm_dgrad_h");
   if (rc != MOE_OK) return rc;
   // dxp = dg . Wg + du . Wu
   GemmArgs b{};
   b.offsets = expert_offsets; b.E = E; b.m_tiles_cap = m_tiles;
   b.A0 = dg; b.A1 = du; b.B0 = U16(Wg); b.B1 = U16(Wu); b.O0 = dxp;
   b.K = f; b.N = d; b.n_tiles = (d + BN - 1) / BN;
-  rc = launch_gemm<DGRAD_X>(b, dim3(b.n_tiles * m_tiles), s, "gemm_dgrad_x");
+  rc = launch_gemm<DGRAD_X>(b, static_cast<long long>(b.n_tiles) * m_tiles, s, "gemm_dgrad_x");
   if (rc != MOE_OK) return rc;
   // weight gradients: dWd = dyp^T h ; dWg = dg^T xp ; dWu = du^T xp
   struct W { const uint16_t* A; const uint16_t* B; uint16_t* O; int M, N; const char* name; };
@@ -546,8 +590,8 @@ extern "C" int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, con
     w.offsets = expert_offsets; w.E = E;
     w.A0 = j.A; w.B0 = j.B; w.O0 = j.O; w.M = j.M; w.N = j.N;
     w.n_tiles = (j.N + BN - 1) / BN;
-    const int mt = (j.M + BM - 1) / BM;
-    rc = launch_gemm<WGRAD>(w, dim3(w.n_tiles * mt, E), s, j.name);
+    w.m_tiles_cap = (j.M + BM - 1) / BM;   // row tiles of one expert's dW
+    rc = launch_gemm<WGRAD>(w, static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E, s, j.name);
     if (rc != MOE_OK) return rc;
   }
   return MOE_OK;
