@@ -28,6 +28,7 @@
 // expert_offsets: a workgroup turns its M-tile number into (expert, first row)
 // with a wave-wide prefix sum over ceil(rows_e / 256); experts without rows own
 // no tile; rows past an expert's end are clamped on load and masked on store.
+#include <type_traits>
 #include "common.h"
 
 namespace {
@@ -298,7 +299,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
 #pragma unroll
   for (int j = 0; j < 2; ++j) brow[j] = (MODE == GATE_UP) ? j * 128 + wn * 32 + lrow : wn * 64 + j * 32 + lrow;
 
-  auto compute = [&](int buf) {
+  // FULL: all four 32-row fragments of the wave are live (the common case, branch-free)
+  auto compute = [&](int buf, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
     const char* ta = lds + buf * 2 * TILE_BYTES;
     const char* tb = ta + TILE_BYTES;
 #pragma unroll
@@ -310,15 +313,33 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
         fb[j] = *reinterpret_cast<const bf16x8_t*>(tb + brow[j] * 128 + swz(brow[j], chunk) * 16);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        if (i < nfa) fa[i] = *reinterpret_cast<const bf16x8_t*>(ta + arow[i] * 128 + swz(arow[i], chunk) * 16);
+        if (FULL || i < nfa) fa[i] = *reinterpret_cast<const bf16x8_t*>(ta + arow[i] * 128 + swz(arow[i], chunk) * 16);
       // weight fragment first: the lane then holds 4 consecutive output columns of one row
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        if (i < nfa) {
+        if (FULL || i < nfa) {
 #pragma unroll
           for (int j = 0; j < 2; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
+    }
+  };
+
+  const int grow0 = m0 + wm * 128;                                   // wave's first output row
+  const int gcol0 = n0 + wn * (MODE == GATE_UP ? 32 : 64);           // wave's first output column
+  // DGRAD_H: saved g / u rows of one 64-row half of the wave's piece, 16 bytes per lane and pass
+  u32x4 pg[8], pu[8];
+  auto gu_load = [&](int hh) {
+    if constexpr (MODE == DGRAD_H) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const int row = p * 8 + (lane >> 3), piece = lane & 7;
+        int gr = grow0 + hh * 64 + row;  if (gr > m_end - 1) gr = m_end - 1;
+        int gc = gcol0 + piece * 8;  if (gc > a.N - 8) gc = a.N - 8;
+        const size_t o = static_cast<size_t>(gr) * a.N + gc;
+        pg[p] = *reinterpret_cast<const u32x4*>(a.G + o);
+        pu[p] = *reinterpret_cast<const u32x4*>(a.U + o);
+      }
     }
   };
 
@@ -327,15 +348,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     finish_fetch(0);
   }
   __syncthreads();
-  for (int kt = 0; kt + 1 < nk; ++kt) {
-    start_fetch(kt + 1, (kt + 1) & 1);
-    __builtin_amdgcn_sched_barrier(0);     // keep the fetch ahead of the math
-    compute(kt & 1);
-    __builtin_amdgcn_sched_barrier(0);
-    finish_fetch((kt + 1) & 1);
-    __syncthreads();
-  }
-  if (nk > 0) compute((nk - 1) & 1);
+  auto main_loop = [&](auto full_tag) {
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+      start_fetch(kt + 1, (kt + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);     // keep the fetch ahead of the math
+      compute(kt & 1, full_tag);
+      __builtin_amdgcn_sched_barrier(0);
+      finish_fetch((kt + 1) & 1);
+      __syncthreads();
+    }
+    gu_load(0);
+    if (nk > 0) compute((nk - 1) & 1, full_tag);
+  };
+  if (nfa == 4) main_loop(std::true_type{}); else main_loop(std::false_type{});
   __syncthreads();                          // every wave is done with the operand tiles
 
   // ---------------- epilogue -----------------------------------------------------
@@ -343,8 +368,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   // col = j*32 + q*8 + lgrp*4 + c.  The wave stages bf16 rows of 128 bytes in its own
   // 16 KB of LDS (16-byte pieces swizzled by row & 7) and stores 16 bytes per lane.
   char* stage = lds + wave * WAVE_STAGE_BYTES;
-  const int grow0 = m0 + wm * 128;                                   // wave's first output row
-  const int gcol0 = n0 + wn * (MODE == GATE_UP ? 32 : 64);           // wave's first output column
   auto quad_addr = [&](int row, int piece) -> char* {
     return stage + row * 128 + ((piece ^ (row & 7)) << 4) + lgrp * 8;
   };
@@ -393,22 +416,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     __builtin_amdgcn_wave_barrier();
     flush(a.O2, a.N, grow0, 128, 0, 4, gcol0, a.N);
   } else if constexpr (MODE == DGRAD_H) {
-    // two halves of 64 rows: g rows at stage[0, 8K), u rows at stage[8K, 16K)
+    // two halves of 64 rows: g rows at stage[0, 8K), u rows at stage[8K, 16K).  The g/u rows of
+    // the first half were requested before the last K step, those of the second half are
+    // requested before the first half is processed, so their latency stays hidden.
     char* ustage = stage + WAVE_STAGE_BYTES / 2;
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
       const int first = grow0 + hh * 64;
+#pragma unroll
       for (int p = 0; p < 8; ++p) {
         const int row = p * 8 + (lane >> 3), piece = lane & 7;
-        int gr = first + row;  if (gr > m_end - 1) gr = m_end - 1;
-        int gc = gcol0 + piece * 8;  if (gc > a.N - 8) gc = a.N - 8;
-        const size_t o = static_cast<size_t>(gr) * a.N + gc;
-        const u32x4 gv = *reinterpret_cast<const u32x4*>(a.G + o);
-        const u32x4 uv = *reinterpret_cast<const u32x4*>(a.U + o);
         const int so = row * 128 + ((piece ^ (row & 7)) << 4);
-        *reinterpret_cast<u32x4*>(stage + so) = gv;
-        *reinterpret_cast<u32x4*>(ustage + so) = uv;
+        *reinterpret_cast<u32x4*>(stage + so) = pg[p];
+        *reinterpret_cast<u32x4*>(ustage + so) = pu[p];
       }
+      if (hh == 0) gu_load(1);
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int i2 = 0; i2 < 2; ++i2)
