@@ -2,9 +2,10 @@
 // gather, as an atomics-free stable counting sort:
 //
 //   count   every workgroup owns PERM_CHUNK consecutive (token, slot) pairs and
-//           counts them per local expert; each wave counts its own quarter with
-//           ballots (one pass per distinct expert in a 64-pair batch) into its
-//           own LDS row, so there is no atomic anywhere.  -> block_hist[e][b]
+//           counts them per local expert; each wave finds, with one ballot per
+//           bit of the expert id, the lanes of a 64-pair batch that chose the
+//           same expert, and the lowest lane of each such group adds the group
+//           size to the wave's own LDS row: no atomic anywhere.  -> block_hist[e][b]
 //   scan    one workgroup turns block_hist, read in expert-major order, into
 //           exclusive prefix sums: the first row of every (expert, workgroup)
 //           cell, and expert_offsets.  This is the paper's
@@ -20,7 +21,7 @@ namespace {
 
 constexpr int PERM_THREADS = 256;
 constexpr int PERM_WAVES = PERM_THREADS / MOE_WAVE;
-constexpr int PERM_ITERS = 4;                                  // 64-pair batches per wave
+constexpr int PERM_ITERS = 1;                                  // 64-pair batches per wave
 constexpr int PERM_CHUNK = PERM_WAVES * PERM_ITERS * MOE_WAVE;  // pairs per workgroup
 
 __device__ __forceinline__ uint64_t lanemask_lt() {
@@ -28,10 +29,22 @@ __device__ __forceinline__ uint64_t lanemask_lt() {
   return lane == 0 ? 0ull : (~0ull >> (64 - lane));
 }
 
+// For every lane, the mask of lanes of its 64-pair batch that chose the same local expert: the
+// AND over the bits of the expert id of "lanes whose bit equals mine" (one ballot per bit, so
+// log2(e_count) steps whatever the number of distinct experts).  Lanes with e < 0 get 0.
+__device__ __forceinline__ uint64_t same_expert_mask(int e, int nbits) {
+  uint64_t m = __ballot(e >= 0);
+  for (int b = 0; b < nbits; ++b) {
+    const uint64_t set = __ballot((e >> b) & 1);
+    m &= ((e >> b) & 1) ? set : ~set;
+  }
+  return e >= 0 ? m : 0ull;
+}
+
 // Counts this wave's pairs per local expert into cnt[] (one LDS row per wave).
 // le[it] receives the local expert id of the lane's pair in batch `it`, or -1.
 __device__ __forceinline__ void count_wave(const int32_t* __restrict__ topk_idx, int n, int e_begin, int e_count,
-                                           int first, int* cnt, int le[PERM_ITERS]) {
+                                           int nbits, int first, int* cnt, int le[PERM_ITERS]) {
   const int lane = threadIdx.x % MOE_WAVE;
 #pragma unroll
   for (int it = 0; it < PERM_ITERS; ++it) {
@@ -42,26 +55,25 @@ __device__ __forceinline__ void count_wave(const int32_t* __restrict__ topk_idx,
       if (e < 0 || e >= e_count) e = -1;
     }
     le[it] = e;
-    uint64_t active = __ballot(e >= 0);
-    while (active) {
-      const int leader = __builtin_ctzll(active);
-      const int e0 = __shfl(e, leader, MOE_WAVE);
-      const uint64_t m = __ballot(e == e0);
-      if (lane == leader) cnt[e0] += __builtin_popcountll(m);
-      active &= ~m;
-    }
+    const uint64_t m = same_expert_mask(e, nbits);
+    // the lowest lane of every group adds the group's size: one writer per expert and batch
+    if (m != 0 && lane == __builtin_ctzll(m)) cnt[e] += __builtin_popcountll(m);
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
 __global__ __launch_bounds__(PERM_THREADS) void permute_count_kernel(const int32_t* __restrict__ topk_idx, int n,
-                                                                     int e_begin, int e_count, int nblocks,
+                                                                     int e_begin, int e_count, int nbits, int nblocks,
                                                                      int32_t* __restrict__ block_hist) {
   __shared__ int wcnt[PERM_WAVES][MOE_MAX_EXPERTS];
   const int tid = threadIdx.x, w = tid / MOE_WAVE;
-  for (int i = tid; i < PERM_WAVES * MOE_MAX_EXPERTS; i += PERM_THREADS) (&wcnt[0][0])[i] = 0;
+  for (int e = tid; e < e_count; e += PERM_THREADS) {
+#pragma unroll
+    for (int v = 0; v < PERM_WAVES; ++v) wcnt[v][e] = 0;
+  }
   __syncthreads();
   int le[PERM_ITERS];
-  count_wave(topk_idx, n, e_begin, e_count, blockIdx.x * PERM_CHUNK + w * PERM_ITERS * MOE_WAVE, wcnt[w], le);
+  count_wave(topk_idx, n, e_begin, e_count, nbits, blockIdx.x * PERM_CHUNK + w * PERM_ITERS * MOE_WAVE, wcnt[w], le);
   __syncthreads();
   for (int e = tid; e < e_count; e += PERM_THREADS) {
     int s = 0;
@@ -71,47 +83,71 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_count_kernel(const int32
   }
 }
 
-// In-place exclusive scan of block_hist (length e_count*nblocks) by one workgroup.
+// In-place exclusive scan of block_hist (length e_count*nblocks, padded to a multiple of 4 by the
+// workspace rounding) by one workgroup of 1024 threads: 4096 elements per sweep with 16-byte
+// accesses, a shuffle scan inside each wave, the 16 wave totals through LDS, a running carry.
 __global__ __launch_bounds__(1024) void permute_scan_kernel(int32_t* __restrict__ block_hist, int e_count, int nblocks,
                                                             int32_t* __restrict__ expert_offsets) {
-  __shared__ int sums[1024];
-  const int tid = threadIdx.x;
+  __shared__ int wsum[16];
+  const int tid = threadIdx.x, lane = tid % MOE_WAVE, w = tid / MOE_WAVE;
   const int N = e_count * nblocks;
-  const int per = (N + 1023) / 1024;
-  const int lo = tid * per, hi = min(N, lo + per);
-  int s = 0;
-  for (int i = lo; i < hi; ++i) s += block_hist[i];
-  sums[tid] = s;
-  __syncthreads();
-  // Hillis-Steele inclusive scan over the 1024 partial sums
-  for (int off = 1; off < 1024; off <<= 1) {
-    int v = tid >= off ? sums[tid - off] : 0;
+  int carry = 0;
+  for (int base = 0; base < N; base += 4096) {
+    const int i = base + tid * 4;
+    int4 v = make_int4(0, 0, 0, 0);
+    if (i < N) v = *reinterpret_cast<const int4*>(block_hist + i);
+    if (i + 1 >= N) v.y = 0;
+    if (i + 2 >= N) v.z = 0;
+    if (i + 3 >= N) v.w = 0;
+    const int s = v.x + v.y + v.z + v.w;
+    int inc = s;
+#pragma unroll
+    for (int d = 1; d < MOE_WAVE; d <<= 1) {
+      const int o = __shfl_up(inc, d, MOE_WAVE);
+      if (lane >= d) inc += o;
+    }
+    if (lane == MOE_WAVE - 1) wsum[w] = inc;
     __syncthreads();
-    sums[tid] += v;
+    int before = 0, total = 0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int t = wsum[q];
+      if (q < w) before += t;
+      total += t;
+    }
     __syncthreads();
+    int4 o;
+    o.x = carry + before + inc - s;
+    o.y = o.x + v.x;
+    o.z = o.y + v.y;
+    o.w = o.z + v.z;
+    if (i < N) {
+      *reinterpret_cast<int4*>(block_hist + i) = o;
+      const int r[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (i + j < N && (i + j) % nblocks == 0) expert_offsets[(i + j) / nblocks] = r[j];
+    }
+    carry += total;
   }
-  int run = sums[tid] - s;  // exclusive prefix of this thread's segment
-  for (int i = lo; i < hi; ++i) {
-    const int c = block_hist[i];
-    block_hist[i] = run;
-    if (i % nblocks == 0) expert_offsets[i / nblocks] = run;
-    run += c;
-  }
-  if (tid == 1023) expert_offsets[e_count] = sums[1023];
+  if (tid == 0) expert_offsets[e_count] = carry;
 }
 
 __global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32_t* __restrict__ topk_idx, int n, int k,
-                                                                     int e_begin, int e_count, int nblocks,
+                                                                     int e_begin, int e_count, int nbits, int nblocks,
                                                                      const int32_t* __restrict__ block_base,
                                                                      int32_t* __restrict__ row_token,
                                                                      int32_t* __restrict__ slot_row) {
   __shared__ int wcnt[PERM_WAVES][MOE_MAX_EXPERTS];
   const int tid = threadIdx.x, w = tid / MOE_WAVE, lane = tid % MOE_WAVE;
-  for (int i = tid; i < PERM_WAVES * MOE_MAX_EXPERTS; i += PERM_THREADS) (&wcnt[0][0])[i] = 0;
+  for (int e = tid; e < e_count; e += PERM_THREADS) {
+#pragma unroll
+    for (int v = 0; v < PERM_WAVES; ++v) wcnt[v][e] = 0;
+  }
   __syncthreads();
   int le[PERM_ITERS];
   const int first = blockIdx.x * PERM_CHUNK + w * PERM_ITERS * MOE_WAVE;
-  count_wave(topk_idx, n, e_begin, e_count, first, wcnt[w], le);
+  count_wave(topk_idx, n, e_begin, e_count, nbits, first, wcnt[w], le);
   __syncthreads();
   // counts -> first row of each wave for each expert
   for (int e = tid; e < e_count; e += PERM_THREADS) {
@@ -131,18 +167,14 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32
     const int idx = first + it * MOE_WAVE + lane;
     const int e = le[it];
     int row = -1;
-    uint64_t active = __ballot(e >= 0);
-    while (active) {
-      const int leader = __builtin_ctzll(active);
-      const int e0 = __shfl(e, leader, MOE_WAVE);
-      const uint64_t m = __ballot(e == e0);
-      const int base = next[e0];
+    const uint64_t m = same_expert_mask(e, nbits);
+    if (m != 0) {
+      const int base = next[e];                      // every lane of the group reads the same counter
+      row = base + __builtin_popcountll(m & lt);
       __builtin_amdgcn_wave_barrier();
-      if (e == e0) row = base + __builtin_popcountll(m & lt);
-      if (lane == leader) next[e0] = base + __builtin_popcountll(m);
-      __builtin_amdgcn_wave_barrier();
-      active &= ~m;
+      if (lane == __builtin_ctzll(m)) next[e] = base + __builtin_popcountll(m);
     }
+    __builtin_amdgcn_wave_barrier();
     if (idx < n) {
       slot_row[idx] = row;
       if (row >= 0) row_token[row] = idx / k;
@@ -188,7 +220,7 @@ inline int perm_blocks(int T, int k) {
 extern "C" size_t moe_permute_workspace_bytes(int T, int k, int e_count) {
   if (T <= 0 || k <= 0 || e_count <= 0) return 0;
   const size_t cells = static_cast<size_t>(e_count) * perm_blocks(T, k);
-  return (cells * sizeof(int32_t) + 255) & ~static_cast<size_t>(255);
+  return (cells * sizeof(int32_t) + 16 + 255) & ~static_cast<size_t>(255);   // + one 16-byte access of slack
 }
 
 extern "C" int moe_permute(const moe_bf16* x, const int32_t* topk_idx, int T, int d, int E_total, int k, int e_begin,
@@ -204,12 +236,14 @@ extern "C" int moe_permute(const moe_bf16* x, const int32_t* topk_idx, int T, in
   if (ws_bytes < moe_permute_workspace_bytes(T, k, e_count)) return MOE_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int n = T * k, nb = perm_blocks(T, k);
+  int nbits = 0;
+  while ((1 << nbits) < e_count) ++nbits;
   int32_t* block_hist = static_cast<int32_t*>(ws);
   MOE_LAUNCH("permute_count", permute_count_kernel, dim3(nb), dim3(PERM_THREADS), 0, s, topk_idx, n, e_begin, e_count,
-             nb, block_hist);
+             nbits, nb, block_hist);
   MOE_LAUNCH("permute_scan", permute_scan_kernel, dim3(1), dim3(1024), 0, s, block_hist, e_count, nb, expert_offsets);
   MOE_LAUNCH("permute_place", permute_place_kernel, dim3(nb), dim3(PERM_THREADS), 0, s, topk_idx, n, k, e_begin,
-             e_count, nb, static_cast<const int32_t*>(block_hist), row_token, slot_row);
+             e_count, nbits, nb, static_cast<const int32_t*>(block_hist), row_token, slot_row);
   const int chunks = d / 8;
   dim3 grid((T + 3) / 4), block(256);
   const uint4* xs = reinterpret_cast<const uint4*>(x);
