@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--workload", default="olmoe", help="olmoe (headline) | fine | ep_share | tiny | skew")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -112,6 +115,12 @@ def main():
         step()
     torch.cuda.synchronize()
     R = int(buf.expert_offsets[-1].item())
+    if args.calibrate_copy:
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region: exactly K steps ------------------------------------------
     torch.cuda.synchronize()

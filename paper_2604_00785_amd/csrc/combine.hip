@@ -29,6 +29,8 @@ __device__ __forceinline__ uint4 scale8(const uint4& v, float w) {
 }
 
 // out[t] = sum_i w[t,i] * src[slot_row[t,i]]   (WEIGHTED)  or  sum_i src[slot_row[t,i]]
+// The token's slot rows and weights are fetched once (lane i holds slot i); the row loads of two
+// slots are in flight together; the sum still runs in slot order.
 template <int VPT, bool WEIGHTED>
 __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ src, const int32_t* __restrict__ slot_row,
                                                       const float* __restrict__ topk_w, int T, int k, int chunks,
@@ -42,19 +44,36 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
     for (int j = 0; j < VPT; ++j)
 #pragma unroll
       for (int q = 0; q < 8; ++q) acc[j][q] = 0.f;
-    for (int i = 0; i < k; ++i) {
-      const int row = slot_row[static_cast<size_t>(t) * k + i];
-      if (row < 0) continue;
-      const float w = WEIGHTED ? topk_w[static_cast<size_t>(t) * k + i] : 1.0f;
-      const uint4* r = src + static_cast<size_t>(row) * chunks;
-      uint4 v[VPT];
-#pragma unroll
-      for (int j = 0; j < VPT; ++j) {
-        const int c = c0 + j * MOE_WAVE + lane;
-        v[j] = c < chunks ? r[c] : make_uint4(0, 0, 0, 0);
+    for (int i0 = 0; i0 < k; i0 += MOE_WAVE) {
+      const int kk = min(k - i0, MOE_WAVE);
+      int my_row = -1;
+      float my_w = 0.f;
+      if (lane < kk) {
+        my_row = slot_row[static_cast<size_t>(t) * k + i0 + lane];
+        if (WEIGHTED) my_w = topk_w[static_cast<size_t>(t) * k + i0 + lane];
       }
+      for (int i = 0; i < kk; i += 2) {
+        const int row0 = __shfl(my_row, i, MOE_WAVE);
+        const int row1 = i + 1 < kk ? __shfl(my_row, i + 1, MOE_WAVE) : -1;
+        const float w0 = WEIGHTED ? __shfl(my_w, i, MOE_WAVE) : 1.0f;
+        const float w1 = WEIGHTED ? __shfl(my_w, (i + 1) & (MOE_WAVE - 1), MOE_WAVE) : 1.0f;
+        uint4 v0[VPT], v1[VPT];
 #pragma unroll
-      for (int j = 0; j < VPT; ++j) fma8(acc[j], v[j], w);
+        for (int j = 0; j < VPT; ++j) {
+          const int c = c0 + j * MOE_WAVE + lane;
+          const bool ok = c < chunks;
+          v0[j] = ok && row0 >= 0 ? src[static_cast<size_t>(row0) * chunks + c] : make_uint4(0, 0, 0, 0);
+          v1[j] = ok && row1 >= 0 ? src[static_cast<size_t>(row1) * chunks + c] : make_uint4(0, 0, 0, 0);
+        }
+        if (row0 >= 0) {
+#pragma unroll
+          for (int j = 0; j < VPT; ++j) fma8(acc[j], v0[j], w0);
+        }
+        if (row1 >= 0) {
+#pragma unroll
+          for (int j = 0; j < VPT; ++j) fma8(acc[j], v1[j], w1);
+        }
+      }
     }
     uint4* o = out + static_cast<size_t>(t) * chunks;
 #pragma unroll
@@ -66,6 +85,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
 }
 
 // dyp[row(t,i)] = w[t,i] * dout[t];  dgate[t,i] = <yp[row(t,i)], dout[t]>
+// The token's dout segment is loaded once and kept in registers for all of its slots; lane i
+// collects the dot product of slot i (k <= 64 slots per pass over the lanes).
 template <int VPT>
 __global__ __launch_bounds__(256) void combine_bwd_kernel(const uint4* __restrict__ dout, const uint4* __restrict__ yp,
                                                           const int32_t* __restrict__ slot_row,
@@ -75,33 +96,47 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const uint4* __restric
   const int t = blockIdx.x * (256 / MOE_WAVE) + threadIdx.x / MOE_WAVE;
   if (t >= T) return;
   const uint4* g = dout + static_cast<size_t>(t) * chunks;
-  for (int i = 0; i < k; ++i) {
-    const int row = slot_row[static_cast<size_t>(t) * k + i];
-    float dot = 0.f;
-    if (row >= 0) {
-      const float w = topk_w[static_cast<size_t>(t) * k + i];
-      const uint4* y = yp + static_cast<size_t>(row) * chunks;
-      uint4* dy = dyp + static_cast<size_t>(row) * chunks;
-      for (int c0 = 0; c0 < chunks; c0 += MOE_WAVE * VPT) {
-        uint4 gv[VPT], yv[VPT];
+  for (int i0 = 0; i0 < k; i0 += MOE_WAVE) {
+    const int kk = min(k - i0, MOE_WAVE);
+    // this pass's slots: lane i holds row and weight of slot i0 + i
+    int my_row = -1;
+    float my_w = 0.f, my_dot = 0.f;
+    if (lane < kk) {
+      my_row = slot_row[static_cast<size_t>(t) * k + i0 + lane];
+      my_w = topk_w[static_cast<size_t>(t) * k + i0 + lane];
+    }
+    for (int c0 = 0; c0 < chunks; c0 += MOE_WAVE * VPT) {
+      uint4 gv[VPT];
+#pragma unroll
+      for (int j = 0; j < VPT; ++j) {
+        const int c = c0 + j * MOE_WAVE + lane;
+        gv[j] = c < chunks ? g[c] : make_uint4(0, 0, 0, 0);
+      }
+      for (int i = 0; i < kk; ++i) {
+        const int row = __shfl(my_row, i, MOE_WAVE);
+        if (row < 0) continue;
+        const float w = __shfl(my_w, i, MOE_WAVE);
+        const uint4* y = yp + static_cast<size_t>(row) * chunks;
+        uint4* dy = dyp + static_cast<size_t>(row) * chunks;
+        uint4 yv[VPT];
 #pragma unroll
         for (int j = 0; j < VPT; ++j) {
           const int c = c0 + j * MOE_WAVE + lane;
-          const bool ok = c < chunks;
-          gv[j] = ok ? g[c] : make_uint4(0, 0, 0, 0);
-          yv[j] = ok ? y[c] : make_uint4(0, 0, 0, 0);
+          yv[j] = c < chunks ? y[c] : make_uint4(0, 0, 0, 0);
         }
+        float dot = 0.f;
 #pragma unroll
         for (int j = 0; j < VPT; ++j) {
           const int c = c0 + j * MOE_WAVE + lane;
           dot += dot8(yv[j], gv[j]);
           if (c < chunks) dy[c] = scale8(gv[j], w);
         }
-      }
 #pragma unroll
-      for (int m = 1; m < MOE_WAVE; m <<= 1) dot += __shfl_xor(dot, m, MOE_WAVE);
+        for (int m = 1; m < MOE_WAVE; m <<= 1) dot += __shfl_xor(dot, m, MOE_WAVE);
+        if (lane == i) my_dot += dot;
+      }
     }
-    if (lane == 0) dgate[static_cast<size_t>(t) * k + i] = dot;
+    if (lane < kk) dgate[static_cast<size_t>(t) * k + i0 + lane] = my_dot;
   }
 }
 

@@ -595,18 +595,11 @@ extern "C" int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, con
   a.K = d; a.N = f; a.n_tiles = (f + BN - 1) / BN;
   int rc = launch_gemm<DGRAD_H>(a, static_cast<long long>(a.n_tiles) * m_tiles, s, "gemm_dgrad_h");
   if (rc != MOE_OK) return rc;
-  // dxp = dg . Wg + du . Wu
-  GemmArgs b{};
-  b.offsets = expert_offsets; b.E = E; b.m_tiles_cap = m_tiles;
-  b.A0 = dg; b.A1 = du; b.B0 = U16(Wg); b.B1 = U16(Wu); b.O0 = dxp;
-  b.K = f; b.N = d; b.n_tiles = (d + BN - 1) / BN;
-  rc = launch_gemm<DGRAD_X>(b, static_cast<long long>(b.n_tiles) * m_tiles, s, "gemm_dgrad_x");
-  if (rc != MOE_OK) return rc;
-  // weight gradients: dWd = dyp^T h ; dWg = dg^T xp ; dWu = du^T xp
+  // weight gradients: dWg = dg^T xp ; dWu = du^T xp (dg, du still warm) ; dWd = dyp^T h
   struct W { const uint16_t* A; const uint16_t* B; uint16_t* O; int M, N; const char* name; };
-  const W jobs[3] = {{U16(dyp), U16(h), dWd, d, f, "gemm_wgrad_down"},
-                     {dg, U16(xp), dWg, f, d, "gemm_wgrad_gate"},
-                     {du, U16(xp), dWu, f, d, "gemm_wgrad_up"}};
+  const W jobs[3] = {{dg, U16(xp), dWg, f, d, "gemm_wgrad_gate"},
+                     {du, U16(xp), dWu, f, d, "gemm_wgrad_up"},
+                     {U16(dyp), U16(h), dWd, d, f, "gemm_wgrad_down"}};
   for (const W& j : jobs) {
     GemmArgs w{};
     w.offsets = expert_offsets; w.E = E;
@@ -616,5 +609,10 @@ extern "C" int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, con
     rc = launch_gemm<WGRAD>(w, static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E, s, j.name);
     if (rc != MOE_OK) return rc;
   }
-  return MOE_OK;
+  // dxp = dg . Wg + du . Wu  (last, so that the dx reduction that follows finds dxp in the last-level cache)
+  GemmArgs b{};
+  b.offsets = expert_offsets; b.E = E; b.m_tiles_cap = m_tiles;
+  b.A0 = dg; b.A1 = du; b.B0 = U16(Wg); b.B1 = U16(Wu); b.O0 = dxp;
+  b.K = f; b.N = d; b.n_tiles = (d + BN - 1) / BN;
+  return launch_gemm<DGRAD_X>(b, static_cast<long long>(b.n_tiles) * m_tiles, s, "gemm_dgrad_x");
 }
