@@ -53,6 +53,21 @@ def kernel_work(cfg, R):
     }
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` (fetch + write) from the committed rocprofv3 counter summary,
+    or None when there is none for this workload."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    key = "gemm_wgrad" if kernel.startswith("gemm_wgrad") else kernel
+    try:
+        for line in open(path):
+            p = line.split()
+            if len(p) == 3 and p[0] == key:
+                return float(p[1]) + float(p[2])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg, inp, sample_tokens):
     """The oracle, as it stands (NumPy fp64), on the first `sample_tokens` tokens of the batch."""
     import numpy as np
@@ -77,7 +92,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="olmoe", help="olmoe (headline) | fine | ep_share | tiny | skew")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096,
+                    help="tokens of the batch the CPU oracle is timed on (about 10-30 s of host work)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 "
@@ -161,6 +177,7 @@ def main():
     else:
         roofline = {"kernel": dom, "bound": "hbm", "achieved": dk["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": dk["frac"], "traffic": None}
+    roofline["traffic"] = measured_traffic(cfg.name, dom)
     gemm_us = sum(v["avg_us"] * v["launches_per_step"] for n, v in kernels.items() if n.startswith("gemm_"))
     gemm_tflops = 18.0 * R * cfg.d * cfg.f / (gemm_us * 1e-6) / 1e12 if gemm_us > 0 else 0.0
 
