@@ -191,6 +191,8 @@ def test_layer_small_configs(name):
     (700, 192, 6, 3, 320, 0, 6, 1),       # ragged in every dimension
     (2048, 256, 16, 4, 128, 4, 8, 0),     # expert-parallel share, gates not renormalised
     (1500, 128, 4, 2, 64, 0, 4, 1),       # several row tiles per expert
+    (200, 128, 128, 70, 64, 0, 128, 1),   # more than 64 slots per token, many experts with few rows
+    (64, 64, 300, 9, 64, 100, 150, 1),    # wide expert range, most experts empty
 ])
 def test_layer_ragged_shapes(T, d, E, k, f, eb, ec, renorm):
     print(f"layer T={T} d={d} E={E} k={k} f={f} local=[{eb},{eb+ec}) renorm={renorm}", flush=True)
