@@ -1,22 +1,32 @@
 // Stage 4 of Algorithm 1 (the three Grouped_mm calls around Silu(gate)*up) and
 // its derivative, as grouped bf16 MFMA GEMMs: one launch covers every expert.
 //
-// One workgroup (8 waves) computes one 256x256 output tile with a 64-deep
-// K step.  Both operand tiles live in LDS as [256 rows][64 k] bf16 (128 bytes
-// per row, 16-byte pieces XOR-swizzled by the row so that the MFMA fragment
-// reads and the fill writes spread over the banks), double-buffered: while the
-// MFMAs consume one buffer, the next K step is fetched into the other one.
-// The waves form a 2 (M) x 4 (N) grid; each owns a 128x64 piece = 4x2
-// v_mfma_f32_32x32x16_bf16 accumulators (128 fp32 registers per lane).
+// One workgroup (8 waves) computes one 256x256 output tile with a 64-deep K step.  Both
+// operand tiles of a step live in LDS (32 KB each), double-buffered (128 KB): all operand
+// traffic is direct-to-LDS (global_load_lds_dwordx4, eight per wave and step), issued one
+// whole step ahead of its use.  The waves form a 2 (M) x 4 (N) grid; each owns a 128x64
+// piece = 4x2 v_mfma_f32_32x32x16_bf16 accumulators (128 fp32 registers per lane).
 //
-// An operand that is contiguous along K in memory (activations [rows, K],
-// forward weights [N, K]) is fetched with direct-to-LDS loads
-// (global_load_lds_dwordx4): a wave instruction fills eight 128-byte LDS rows, and
-// the swizzle is applied on the global side (which 16-byte piece a lane reads).
-// An operand that is contiguous along the other dimension (weights in dgrad,
-// both operands in wgrad) is transposed in registers on its way to LDS: a thread
-// loads a 4 (k) x 8 (n) block with four 16-byte loads and writes eight 8-byte
-// K-runs.
+// What the main loop is built around: while the matrix pipe of a SIMD is saturated, vector-ALU
+// instructions of either wave on that SIMD (address arithmetic for loads and LDS reads) are
+// served very slowly, and everything queued behind them stalls.  So the loop contains no
+// vector-ALU instruction at all: global loads use the scalar-base form (SGPR base that is
+// advanced by scalar adds + a 32-bit per-lane offset computed once per tile), LDS fragment
+// reads use per-lane addresses computed once per tile + immediate offsets (the K loop is
+// unrolled by two so that the buffer is a compile-time constant).  MFMA fragments are
+// double-buffered in registers: the LDS reads of the next 16-deep sub-step are issued before
+// the MFMAs of the current one.  One s_barrier per step, placed before the last MFMA group,
+// publishes the tile that was awaited and frees the buffer that was just read, so the next
+// loads start a full step before they are needed.
+//
+// Tile layouts.  An operand that is contiguous along K in memory (activations [rows, K],
+// forward weights [N, K]) is kept as [256 rows][64 k] with 128-byte rows whose eight 16-byte
+// pieces are XOR-swizzled by the row, so that fragment reads (one ds_read_b128 per lane) spread
+// over all banks; the swizzle is applied on the global side of the fill (which piece a lane
+// fetches), since a direct-to-LDS load writes LDS linearly.  An operand that is contiguous
+// along its other dimension (weights in dgrad, both operands in wgrad) is kept as it lies in
+// memory, [64 k][256 n] with 512-byte rows, and read with the transposing LDS load
+// ds_read_b64_tr_b16, two per fragment.
 //
 // The MFMAs are issued as (weight fragment) x (activation fragment), so a lane
 // ends up with four consecutive output COLUMNS of one row.  The epilogue rounds
@@ -31,16 +41,19 @@
 #include <type_traits>
 #include "common.h"
 
+
 namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int GEMM_THREADS = 512;
-constexpr int TILE_BYTES = BM * BK * 2;              // one operand tile
-constexpr int LDS_BYTES = 2 * 2 * TILE_BYTES;        // A and B, double-buffered
-constexpr int WAVE_STAGE_BYTES = LDS_BYTES / 8;      // epilogue staging per wave (16 KB)
+constexpr int TILE_BYTES = BM * BK * 2;               // one operand tile (32 KB)
+constexpr int B_TILES = 2 * TILE_BYTES;               // LDS: A buffer 0, A buffer 1, B buffer 0, B buffer 1
+constexpr int LDS_BYTES = 4 * TILE_BYTES;             // 128 KB
+constexpr int WAVE_STAGE_BYTES = LDS_BYTES / 8;       // epilogue staging per wave (16 KB)
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
@@ -67,27 +80,60 @@ struct GemmArgs {
   int M;
 };
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row ^ (row >> 3)) & 7); }
+// 512 bytes of zeros: what the reduction rows past an expert's end read in the weight-gradient products.
+__device__ __attribute__((aligned(512))) uint32_t g_zero_block[128];
 
-// K-strided operand: a thread stages k rows ks_kq*4 + j (j<4), columns ks_nb*8 .. +8.  Inside a
-// group of 32 lanes nb takes 8 values and kq 4, so that one transposing LDS write spreads over
-// 16 different 8-byte bank groups, and one global load covers 256 contiguous bytes of 4 rows.
-struct Staged { u32x4 v[4]; };
-__device__ __forceinline__ int ks_nb(int tid) { return ((tid >> 5) & 3) * 8 + (tid & 7); }
-__device__ __forceinline__ int ks_kq(int tid) { return (tid >> 7) * 4 + ((tid >> 3) & 3); }
+// [256 rows][64 k] tile: byte offset of the 16-byte piece `chunk` (0..7) of `row`.
+__device__ __forceinline__ int kc_off(int row, int chunk) {
+  return row * 128 + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 4);
+}
+// [64 k][256 n] tile: 16-byte pieces of a k row are XOR-swizzled with 4*(k & 3), which spreads the
+// four k rows that 16 lanes of a transposing read touch over four different 64-byte bank groups.
+__device__ __forceinline__ int kn_piece(int krow, int piece) { return piece ^ ((krow & 3) << 2); }
 
-__device__ __forceinline__ void store_ks(const Staged& r, char* tile, int tid) {
-  const int nb = ks_nb(tid), kq = ks_kq(tid);
-  const int chunk = kq >> 1, half = kq & 1;
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int row = nb * 8 + q;
-    const uint32_t sel = (q & 1) ? 0x07060302u : 0x05040100u;
-    u32x2 o;
-    o.x = __builtin_amdgcn_perm(r.v[1][q >> 1], r.v[0][q >> 1], sel);  // k0 (low half), k1 (high half)
-    o.y = __builtin_amdgcn_perm(r.v[3][q >> 1], r.v[2][q >> 1], sel);  // k2, k3
-    *reinterpret_cast<u32x2*>(tile + row * 128 + swz(row, chunk) * 16 + half * 8) = o;
-  }
+// LDS fragment reads are written as inline assembly with immediate offsets and awaited by hand
+// (lds_wait): the fragments are read one sub-step ahead, across the loop back edge, and the
+// compiler's own wait insertion would drain the LDS queue completely at the first use.
+template <int OFF> __device__ __forceinline__ bf16x8_t lds_read_b128(uint32_t addr) {
+  bf16x8_t v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int OFF> __device__ __forceinline__ s16x4 lds_read_tr_b64(uint32_t addr) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+// Direct-to-LDS loads (16 bytes per lane, lane l lands at lds_addr + 16 l) are written as inline
+// assembly too, so that the (scalar base) + (32-bit lane offset) form is certain: with 64-bit lane
+// addresses every load needs vector-ALU work.  M0 carries the LDS address; nothing else in this
+// file uses M0.
+__device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const char* sbase) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ void dma16_lane(uint32_t lds_addr, const char* p) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :: "s"(lds_addr), "v"(p) : "memory");
+}
+template <int N> __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
+
+// Per-lane address of a fragment (32 tile columns starting at col0) of a [64 k][256 n] tile at
+// LDS address `tile`, K sub-step 0, first half.  Within 16 lanes, lane i supplies the address of
+// four consecutive n of k row i/4, n block i%4, and lane l receives k rows 0..3 of column l; two
+// such loads (the second 4 k rows = 2048 bytes further) give the eight consecutive k of a column,
+// and sub-step ks lies ks * 8192 bytes further.
+__device__ __forceinline__ uint32_t kn_frag_addr(uint32_t tile, int col0, int lane) {
+  const int i = lane & 15, kg = lane >> 5;
+  const int n = col0 + ((lane >> 4) & 1) * 16 + 4 * (i & 3);
+  const int krow = kg * 8 + (i >> 2);
+  return tile + krow * 512 + kn_piece(krow, n >> 3) * 16 + (n & 7) * 2;
+}
+template <int OFF> __device__ __forceinline__ bf16x8_t lds_read_kn(uint32_t addr) {
+  union { s16x4 h[2]; bf16x8_t v; } u;
+  u.h[0] = lds_read_tr_b64<OFF>(addr);
+  u.h[1] = lds_read_tr_b64<OFF + 2048>(addr);
+  return u.v;
 }
 
 // sigmoid through the hardware exp2 and reciprocal (each about 1 ulp): far inside bf16 rounding.
@@ -96,6 +142,13 @@ __device__ __forceinline__ float sigmoid_f(float g) {
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
 }
 __device__ __forceinline__ float silu_f(float g) { return g * sigmoid_f(g); }
+
+template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ void wg_barrier() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+}
 
 template <int MODE>
 __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) {
@@ -162,125 +215,160 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     m0 = a.offsets[e] + (mt - s_pref[e]) * BM;
     m_end = a.offsets[e + 1];
   }
+  // tile coordinates are wave-uniform: keep them in scalar registers, so that everything derived
+  // from them (operand base addresses in particular) is scalar too
+  e = __builtin_amdgcn_readfirstlane(e);
+  m0 = __builtin_amdgcn_readfirstlane(m0);
+  m_end = __builtin_amdgcn_readfirstlane(m_end);
   const int n0 = nt * (MODE == GATE_UP ? BN / 2 : BN);
   // 32-row fragments of this wave that hold at least one valid row (the others are skipped)
   int nfa = (m_end - m0 - wm * 128 + 31) >> 5;
   nfa = nfa < 0 ? 0 : (nfa > 4 ? 4 : nfa);
   nfa = __builtin_amdgcn_readfirstlane(nfa);
 
-  constexpr bool A_KS = (MODE == WGRAD);
-  constexpr bool B_KS = (MODE == WGRAD || MODE == DGRAD_H || MODE == DGRAD_X);
+  constexpr bool A_KN = (MODE == WGRAD);                                        // stored [k][m]
+  constexpr bool B_KN = (MODE == WGRAD || MODE == DGRAD_H || MODE == DGRAD_X);  // stored [k][n]
 
   // ---------------- operand sources -------------------------------------------
-  // A tile rows <-> output rows m0 + r ; B tile rows <-> output columns.
-  // K-contiguous operands: wave w issues 4 direct-to-LDS loads per K step; load i fills LDS
-  // rows (4w+i)*8 .. +8, lane l -> row + l/8, physical piece l%8, i.e. logical piece swz(row, l%8).
-  const uint16_t* da[4];
-  const uint16_t* db[4];
-  const uint16_t* pa = nullptr;   // K-strided operands: this thread's column pointer
-  const uint16_t* pb = nullptr;
-  ptrdiff_t a_phase = 0, b_phase = 0;   // element offset of the second K phase (DGRAD_X)
+  // A tile <-> output rows m0 + r ; B tile <-> output columns.  Per step and operand a wave issues
+  // four direct-to-LDS loads of 1 KB each, as (scalar base) + (32-bit lane offset):
+  //  K-contiguous source ([row][k]): load i of wave w fills LDS rows (4w+i)*8 .. +8 of the tile;
+  //    lane l -> row + l/8, physical piece l%8, i.e. the logical piece that kc_off maps there.
+  //    The base advances by 64 elements per step.
+  //  n-contiguous source ([k][n]): load i of wave w fills k rows (4w+i)*2, +1 of the tile;
+  //    lane l -> k row + l/32, physical piece l%32 = logical piece kn_piece(k row, l%32).
+  //    The base advances by 64 rows per step.
+  uint32_t voa[4], vob[4];              // lane offsets in bytes
+  const char* abase;                    // step 0 of phase 0
+  const char* bbase;
+  ptrdiff_t a_phase = 0, b_phase = 0;   // byte offset of the second K phase (DGRAD_X)
+  size_t a_step, b_step;                // bytes per step
   int k_lo = 0, k_hi = 0;               // WGRAD: the expert's row range is the reduction
-  int nk;
-  size_t lda = 0, ldb = 0;
+  int nk, nk_phase;                     // steps in total / in the first K phase
 
   if constexpr (MODE == WGRAD) {
-    k_lo = a.offsets[e];
-    k_hi = a.offsets[e + 1];
+    k_lo = __builtin_amdgcn_readfirstlane(a.offsets[e]);
+    k_hi = __builtin_amdgcn_readfirstlane(a.offsets[e + 1]);
     nk = (k_hi - k_lo + BK - 1) / BK;
-    lda = a.M;
-    ldb = a.N;
-    const int nb = ks_nb(tid);
-    int ca = m0 + nb * 8;  if (ca > a.M - 8) ca = a.M - 8;
-    int cb = n0 + nb * 8;  if (cb > a.N - 8) cb = a.N - 8;
-    pa = a.A0 + ca;
-    pb = a.B0 + cb;
+    nk_phase = nk;
+    abase = reinterpret_cast<const char*>(a.A0 + static_cast<size_t>(k_lo) * a.M + m0);
+    bbase = reinterpret_cast<const char*>(a.B0 + static_cast<size_t>(k_lo) * a.N + n0);
+    a_step = static_cast<size_t>(BK) * a.M * 2;
+    b_step = static_cast<size_t>(BK) * a.N * 2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int krow = (wave * 4 + i) * 2 + (lane >> 5);
+      const int piece = kn_piece(krow, lane & 31);
+      int ca = piece * 8;  if (m0 + ca > a.M - 8) ca = a.M - 8 - m0;
+      int cb = piece * 8;  if (n0 + cb > a.N - 8) cb = a.N - 8 - n0;
+      voa[i] = static_cast<uint32_t>((krow * a.M + ca) * 2);
+      vob[i] = static_cast<uint32_t>((krow * a.N + cb) * 2);
+    }
   } else {
     nk = a.K / BK;
+    nk_phase = nk;
+    abase = reinterpret_cast<const char*>(a.A0 + static_cast<size_t>(m0) * a.K);
+    a_step = BK * 2;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = (wave * 4 + i) * 8 + (lane >> 3);
-      const int piece = swz(row, lane & 7);
-      int r = m0 + row;
-      if (r > m_end - 1) r = m_end - 1;
-      da[i] = a.A0 + static_cast<size_t>(r) * a.K + piece * 8;
+      const int chunk = (kc_off(row, lane & 7) >> 4) & 7;   // the swizzle is its own inverse
+      int r = row;
+      if (m0 + r > m_end - 1) r = m_end - 1 - m0;
+      voa[i] = static_cast<uint32_t>((r * a.K + chunk * 8) * 2);
     }
-    if constexpr (MODE == DGRAD_X) { a_phase = a.A1 - a.A0; nk *= 2; }
+    if constexpr (MODE == DGRAD_X) { a_phase = (a.A1 - a.A0) * 2; nk *= 2; }
     const size_t wsz = static_cast<size_t>(a.N) * a.K;
-    if constexpr (!B_KS) {
+    if constexpr (!B_KN) {
+      // GATE_UP: LDS rows 0..127 hold Wg rows n0.., rows 128..255 hold Wu rows n0.. (waves 4-7 fill those)
+      const uint16_t* w = a.B0;
+      int rsub = 0;
+      if constexpr (MODE == GATE_UP) {
+        if (wave >= 4) { w = a.B1; rsub = BN / 2; }
+      }
+      bbase = reinterpret_cast<const char*>(w + static_cast<size_t>(e) * wsz + static_cast<size_t>(n0) * a.K);
+      b_step = BK * 2;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = (wave * 4 + i) * 8 + (lane >> 3);   // LDS row of the B tile
-        const int piece = swz(row, lane & 7);
-        const uint16_t* w = a.B0;
-        int col = n0 + row;
-        if constexpr (MODE == GATE_UP) {
-          if (row >= BN / 2) { w = a.B1; col = n0 + row - BN / 2; }
-        }
-        if (col > a.N - 1) col = a.N - 1;
-        db[i] = w + static_cast<size_t>(e) * wsz + static_cast<size_t>(col) * a.K + piece * 8;
+        const int chunk = (kc_off(row, lane & 7) >> 4) & 7;
+        int col = row - rsub;
+        if (n0 + col > a.N - 1) col = a.N - 1 - n0;
+        vob[i] = static_cast<uint32_t>((col * a.K + chunk * 8) * 2);
       }
     } else {  // DGRAD_H / DGRAD_X: weights stored [K][N]
-      ldb = a.N;
-      int cb = n0 + ks_nb(tid) * 8;
-      if (cb > a.N - 8) cb = a.N - 8;
-      pb = a.B0 + static_cast<size_t>(e) * wsz + cb;
-      if constexpr (MODE == DGRAD_X) b_phase = a.B1 - a.B0;
+      bbase = reinterpret_cast<const char*>(a.B0 + static_cast<size_t>(e) * wsz + n0);
+      b_step = static_cast<size_t>(BK) * a.N * 2;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int krow = (wave * 4 + i) * 2 + (lane >> 5);
+        int cb = kn_piece(krow, lane & 31) * 8;
+        if (n0 + cb > a.N - 8) cb = a.N - 8 - n0;
+        vob[i] = static_cast<uint32_t>((krow * a.N + cb) * 2);
+      }
+      if constexpr (MODE == DGRAD_X) b_phase = (a.B1 - a.B0) * 2;
     }
   }
 
-  Staged ra, rb;
+  // Both bases live in scalar registers and are advanced by scalar adds: steps are loaded in order.
+  auto scalarize = [](const char* p) __attribute__((always_inline)) {
+    const uint64_t u = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32));
+    return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+  };
+  const uint32_t lds_fill = __builtin_amdgcn_readfirstlane(
+      static_cast<uint32_t>(reinterpret_cast<size_t>(LDS_PTR(lds))) + wave * 4096);   // this wave's share of a tile
+  const char* sa_next = scalarize(abase);
+  const char* sb_next = scalarize(bbase);
+  const char* sa_phase1 = nullptr;
+  const char* sb_phase1 = nullptr;
+  if constexpr (MODE == DGRAD_X) { sa_phase1 = scalarize(abase + a_phase); sb_phase1 = scalarize(bbase + b_phase); }
 
-  // Starts the fetch of K step kt into LDS buffer `buf`: direct-to-LDS loads land there by
-  // themselves; K-strided operands arrive in ra / rb and are written by finish_fetch().
-  auto start_fetch = [&](int kt, int buf) {
-    int kk = kt;
-    ptrdiff_t offa = 0, offb = 0;
+  // The loads of the next reduction step (kt, in order) into buffer BUF: load_begin fixes the
+  // step's bases and advances the running ones, load_part(i) issues the i-th A and B load.
+  int kk_cur = 0;                       // WGRAD only: the step being loaded, and whether it is the partial last one
+  bool tail_cur = false;
+  auto load_begin = [&](int kt) __attribute__((always_inline)) {
+    if constexpr (MODE == WGRAD) { kk_cur = kt; tail_cur = k_lo + (kt + 1) * BK > k_hi; }
+  };
+  auto load_end = [&](int kt) __attribute__((always_inline)) {
+    sa_next += a_step;
+    sb_next += b_step;
     if constexpr (MODE == DGRAD_X) {
-      const int half = nk >> 1;
-      if (kt >= half) { kk = kt - half; offa = a_phase; offb = b_phase; }
-    }
-    char* ta = lds + buf * 2 * TILE_BYTES;
-    char* tb = ta + TILE_BYTES;
-    if constexpr (!A_KS) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(da[i] + offa + static_cast<size_t>(kk) * BK),
-                                         LDS_PTR(ta + (wave * 4 + i) * 1024), 16, 0, 0);
-    }
-    if constexpr (!B_KS) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(db[i] + static_cast<size_t>(kk) * BK),
-                                         LDS_PTR(tb + (wave * 4 + i) * 1024), 16, 0, 0);
-    }
-    const int kq = ks_kq(tid);
-    if constexpr (A_KS) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int r = k_lo + kk * BK + kq * 4 + j;
-        ra.v[j] = r < k_hi ? *reinterpret_cast<const u32x4*>(pa + static_cast<size_t>(r) * lda) : u32x4{0, 0, 0, 0};
-      }
-    }
-    if constexpr (B_KS) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if constexpr (MODE == WGRAD) {
-          const int r = k_lo + kk * BK + kq * 4 + j;
-          rb.v[j] = r < k_hi ? *reinterpret_cast<const u32x4*>(pb + static_cast<size_t>(r) * ldb) : u32x4{0, 0, 0, 0};
-        } else {
-          const int r = kk * BK + kq * 4 + j;
-          rb.v[j] = *reinterpret_cast<const u32x4*>(pb + offb + static_cast<size_t>(r) * ldb);
-        }
-      }
+      if (kt + 1 == nk_phase) { sa_next = sa_phase1; sb_next = sb_phase1; }
     }
   };
-  auto finish_fetch = [&](int buf) {
-    char* ta = lds + buf * 2 * TILE_BYTES;
-    char* tb = ta + TILE_BYTES;
-    if constexpr (A_KS) store_ks(ra, ta, tid);
-    if constexpr (B_KS) store_ks(rb, tb, tid);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct-to-LDS loads have landed
+  auto load_part = [&](auto buf_tag, auto i_tag) __attribute__((always_inline)) {
+    constexpr int BUF = decltype(buf_tag)::value, i = decltype(i_tag)::value;
+    const uint32_t la = lds_fill + BUF * TILE_BYTES + i * 1024;
+    const uint32_t lb = la + B_TILES;
+    if constexpr (MODE == WGRAD) {
+      if (tail_cur) {
+        // last, partial step of the expert: reduction rows at or past its end read zeros in A and
+        // a valid row in B (per-lane 64-bit addresses; once per tile)
+        const int krow = k_lo + kk_cur * BK + (wave * 4 + i) * 2 + (lane >> 5);
+        const char* pa = krow < k_hi ? sa_next + voa[i]
+                                     : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16;
+        const char* pb = sb_next + vob[i] - (krow < k_hi ? 0 : static_cast<size_t>(krow - (k_hi - 1)) * a.N * 2);
+        dma16_lane(la, pa);
+        dma16_lane(lb, pb);
+      } else {
+        dma16(la, voa[i], sa_next);
+        dma16(lb, vob[i], sb_next);
+      }
+    } else {
+      dma16(la, voa[i], sa_next);
+      dma16(lb, vob[i], sb_next);
+    }
+  };
+  auto load_tile = [&](int kt, auto buf_tag) __attribute__((always_inline)) {
+    load_begin(kt);
+    load_part(buf_tag, std::integral_constant<int, 0>{});
+    load_part(buf_tag, std::integral_constant<int, 1>{});
+    load_part(buf_tag, std::integral_constant<int, 2>{});
+    load_part(buf_tag, std::integral_constant<int, 3>{});
+    load_end(kt);
   };
 
   // ---------------- main loop ----------------------------------------------------
@@ -293,43 +381,88 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int lrow = lane & 31, lgrp = lane >> 5;
-  int arow[4], brow[2];
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<size_t>(LDS_PTR(lds)));
+  // Per-lane fragment addresses for buffer 0; buffer, sub-step (and half, for the transposing
+  // reads) are immediate offsets.  A swizzled [row][k] tile needs one address per sub-step.
+  uint32_t fa_addr[4][A_KN ? 1 : 4], fb_addr[2][B_KN ? 1 : 4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) arow[i] = wm * 128 + i * 32 + lrow;
+  for (int i = 0; i < 4; ++i) {
+    const int row0 = wm * 128 + i * 32;
+    if constexpr (A_KN) fa_addr[i][0] = kn_frag_addr(lds0, row0, lane);
+    else {
 #pragma unroll
-  for (int j = 0; j < 2; ++j) brow[j] = (MODE == GATE_UP) ? j * 128 + wn * 32 + lrow : wn * 64 + j * 32 + lrow;
-
-  // FULL: all four 32-row fragments of the wave are live (the common case, branch-free)
-  auto compute = [&](int buf, auto full_tag) {
-    constexpr bool FULL = decltype(full_tag)::value;
-    const char* ta = lds + buf * 2 * TILE_BYTES;
-    const char* tb = ta + TILE_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8_t fa[4], fb[2];
-      const int chunk = ks * 2 + lgrp;
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        fb[j] = *reinterpret_cast<const bf16x8_t*>(tb + brow[j] * 128 + swz(brow[j], chunk) * 16);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (FULL || i < nfa) fa[i] = *reinterpret_cast<const bf16x8_t*>(ta + arow[i] * 128 + swz(arow[i], chunk) * 16);
-      // weight fragment first: the lane then holds 4 consecutive output columns of one row
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (FULL || i < nfa) {
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-        }
+      for (int ks = 0; ks < 4; ++ks) fa_addr[i][ks] = lds0 + kc_off(row0 + lrow, ks * 2 + lgrp);
     }
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int row0 = (MODE == GATE_UP) ? j * 128 + wn * 32 : wn * 64 + j * 32;
+    if constexpr (B_KN) fb_addr[j][0] = kn_frag_addr(lds0 + B_TILES, row0, lane);
+    else {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) fb_addr[j][ks] = lds0 + B_TILES + kc_off(row0 + lrow, ks * 2 + lgrp);
+    }
+  }
+
+  bf16x8_t fa[2][4], fb[2][2];   // two fragment sets: one feeds the MFMAs while the other is being read
+  constexpr int NREADS = (A_KN ? 8 : 4) + (B_KN ? 4 : 2);   // LDS read instructions per fragment set
+  // All six fragments are read even when some hold no valid row (the counts of outstanding reads
+  // stay fixed); only the MFMAs of such fragments are skipped.
+  auto read_frags = [&](auto buf_tag, auto ks_tag, auto set_tag) __attribute__((always_inline)) {
+    constexpr int BUF = decltype(buf_tag)::value, KS = decltype(ks_tag)::value, SET = decltype(set_tag)::value;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if constexpr (B_KN) fb[SET][j] = lds_read_kn<BUF * TILE_BYTES + KS * 8192>(fb_addr[j][0]);
+      else fb[SET][j] = lds_read_b128<BUF * TILE_BYTES>(fb_addr[j][KS]);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (A_KN) fa[SET][i] = lds_read_kn<BUF * TILE_BYTES + KS * 8192>(fa_addr[i][0]);
+      else fa[SET][i] = lds_read_b128<BUF * TILE_BYTES>(fa_addr[i][KS]);
+    }
+  };
+  // weight fragment first: the lane then holds 4 consecutive output columns of one row.
+  // FULL = false: the wave owns no valid row and issues no MFMA at all
+  auto mma = [&](auto set_tag, auto full_tag) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    constexpr int set = decltype(set_tag)::value;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if constexpr (FULL) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+      }
+  };
+
+  // the same MFMA group with the loads of step kt_load in between (if do_load): one A and one B
+  // load after every second MFMA, so that neither wave of a SIMD holds the matrix pipe up with a
+  // burst of loads.  The MFMAs are not duplicated across the branch on purpose.
+  auto mma_loading = [&](auto set_tag, auto full_tag, auto buf_tag, bool do_load, int kt_load) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    constexpr int set = decltype(set_tag)::value;
+    if (do_load) load_begin(kt_load);
+#define MMA_PART(i)                                                                                          \
+    if constexpr (FULL) {                                                                                    \
+      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][0], fa[set][i], acc[i][0], 0, 0, 0);       \
+      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][1], fa[set][i], acc[i][1], 0, 0, 0);       \
+    }                                                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                                       \
+    if (do_load) load_part(buf_tag, std::integral_constant<int, i>{});                                       \
+    __builtin_amdgcn_sched_barrier(0);
+    MMA_PART(0)
+    MMA_PART(1)
+    MMA_PART(2)
+    MMA_PART(3)
+#undef MMA_PART
+    if (do_load) load_end(kt_load);
   };
 
   const int grow0 = m0 + wm * 128;                                   // wave's first output row
   const int gcol0 = n0 + wn * (MODE == GATE_UP ? 32 : 64);           // wave's first output column
   // DGRAD_H: saved g / u rows of one 64-row half of the wave's piece, 16 bytes per lane and pass
   u32x4 pg[8], pu[8];
-  auto gu_load = [&](int hh) {
+  auto gu_load = [&](int hh) __attribute__((always_inline)) {
     if constexpr (MODE == DGRAD_H) {
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
@@ -343,35 +476,66 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     }
   };
 
-  if (nk > 0) {
-    start_fetch(0, 0);
-    finish_fetch(0);
-  }
-  __syncthreads();
-  auto main_loop = [&](auto full_tag) {
-    for (int kt = 0; kt + 1 < nk; ++kt) {
-      start_fetch(kt + 1, (kt + 1) & 1);
-      __builtin_amdgcn_sched_barrier(0);     // keep the fetch ahead of the math
-      compute(kt & 1, full_tag);
-      __builtin_amdgcn_sched_barrier(0);
-      finish_fetch((kt + 1) & 1);
-      __syncthreads();
+  // Step kt reads buffer kt&1.  Its barrier comes before its last MFMA group, after every wave
+  // has (a) seen its own loads of step kt+1 land and (b) received its last fragments of step kt.
+  // Behind it the other buffer is complete, and this buffer is free for step kt+2, whose loads
+  // then have a whole step to land.
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+  auto step = [&](int kt, auto buf_tag, auto full_tag) __attribute__((always_inline)) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    using THIS = std::integral_constant<int, BUF>;
+    using OTHER = std::integral_constant<int, 1 - BUF>;
+    read_frags(THIS{}, I1{}, I1{});
+    lds_wait<NREADS>();  fence();  mma(I0{}, full_tag);  fence();
+    read_frags(THIS{}, I2{}, I0{});
+    lds_wait<NREADS>();  fence();  mma(I1{}, full_tag);  fence();
+    read_frags(THIS{}, I3{}, I1{});
+    lds_wait<NREADS>();  fence();  mma(I0{}, full_tag);  fence();
+    if (kt + 1 < nk) {
+      wait_vm<0>();
+      lds_wait<0>();
+      wg_barrier();
+      read_frags(OTHER{}, I0{}, I0{});
+    } else {
+      lds_wait<0>();
     }
-    gu_load(0);
-    if (nk > 0) compute((nk - 1) & 1, full_tag);
+    fence();
+    mma_loading(I1{}, full_tag, THIS{}, kt + 2 < nk, kt + 2);
+    fence();
   };
-  if (nfa == 4) main_loop(std::true_type{}); else main_loop(std::false_type{});
-  __syncthreads();                          // every wave is done with the operand tiles
+  auto main_loop = [&](auto full_tag) __attribute__((always_inline)) {
+    if (nk > 0) {
+      load_tile(0, I0{});
+      wait_vm<0>();
+      wg_barrier();
+      if (nk > 1) load_tile(1, I1{});
+      read_frags(I0{}, I0{}, I0{});
+    }
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+      step(kt, I0{}, full_tag);
+      step(kt + 1, I1{}, full_tag);
+    }
+    if (kt < nk) step(kt, I0{}, full_tag);
+  };
+  // a wave whose 128 rows all lie past the expert's end only keeps the loads and barriers going
+  if (nfa > 0) main_loop(std::true_type{}); else main_loop(std::false_type{});
+  gu_load(0);
+  wg_barrier();                             // every wave is done with the operand stages
 
   // ---------------- epilogue -----------------------------------------------------
   // acc[i][j][4q+c] is the wave's element (row, col) with row = i*32 + lrow and
   // col = j*32 + q*8 + lgrp*4 + c.  The wave stages bf16 rows of 128 bytes in its own
   // 16 KB of LDS (16-byte pieces swizzled by row & 7) and stores 16 bytes per lane.
   char* stage = lds + wave * WAVE_STAGE_BYTES;
-  auto quad_addr = [&](int row, int piece) -> char* {
+  auto quad_addr = [&](int row, int piece) __attribute__((always_inline)) -> char* {
     return stage + row * 128 + ((piece ^ (row & 7)) << 4) + lgrp * 8;
   };
-  auto put_quad = [&](int row, int piece, float v0, float v1, float v2, float v3) {
+  auto put_quad = [&](int row, int piece, float v0, float v1, float v2, float v3) __attribute__((always_inline)) {
     u32x2 o;
     o.x = pack_bf16(v0, v1);
     o.y = pack_bf16(v2, v3);
@@ -379,7 +543,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   };
   // stores `rows` staged rows starting at staged row 0 to out (row stride ld); the first
   // `pieces` 16-byte pieces of each row go to columns col0 + piece*8 (pieces = 4 or 8)
-  auto flush = [&](uint16_t* out, size_t ld, int first_row, int rows, int piece0, int pieces, int col0, int ncols) {
+  auto flush = [&](uint16_t* out, size_t ld, int first_row, int rows, int piece0, int pieces, int col0, int ncols) __attribute__((always_inline)) {
     const int rpp = 64 / pieces;                    // rows per pass
     for (int p = 0; p < rows / rpp; ++p) {
       const int row = p * rpp + lane / pieces;
@@ -487,7 +651,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     if constexpr (MODE == WGRAD) out += static_cast<size_t>(e) * a.M * a.N;
     flush(out, a.N, grow0, 128, 0, 8, gcol0, a.N);
   }
-  __syncthreads();   // the staging area becomes operand tiles again
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's staging reads are done
+  wg_barrier();      // the staging area becomes operand stages again
   }  // tile loop
 }
 
