@@ -1,10 +1,14 @@
 // Stage 4 of Algorithm 1 (the three Grouped_mm calls around Silu(gate)*up) and
 // its derivative, as grouped bf16 MFMA GEMMs: one launch covers every expert.
 //
-// One workgroup (8 waves) computes one 256x256 output tile with a 64-deep K step.  Both
-// operand tiles of a step live in LDS (32 KB each), double-buffered (128 KB): all operand
-// traffic is direct-to-LDS (global_load_lds_dwordx4, eight per wave and step), issued one
-// whole step ahead of its use.  The waves form a 2 (M) x 4 (N) grid; each owns a 128x64
+// One workgroup (8 waves) computes one 256x256 output tile with a 64-deep K step.  The two
+// operand tiles of a step (32 KB each) live in LDS, in a ring of five tile slots (160 KB, all
+// there is): A(t) sits in slot 2t mod 5, B(t) in slot (2t+1) mod 5.  All operand traffic is
+// direct-to-LDS (global_load_lds_dwordx4, eight per wave and step).  Two and a half steps fit,
+// so after the barrier of step t the loads of B(t+2) go out first (they are needed one step
+// later) and those of A(t+3) follow between the MFMAs (needed two steps later): the urgent
+// half of a step's loads is then small enough for the texture path to deliver within the step.
+// The waves form a 2 (M) x 4 (N) grid; each owns a 128x64
 // piece = 4x2 v_mfma_f32_32x32x16_bf16 accumulators (128 fp32 registers per lane).
 //
 // What the main loop is built around: while the matrix pipe of a SIMD is saturated, vector-ALU
@@ -13,11 +17,10 @@
 // vector-ALU instruction at all: global loads use the scalar-base form (SGPR base that is
 // advanced by scalar adds + a 32-bit per-lane offset computed once per tile), LDS fragment
 // reads use per-lane addresses computed once per tile + immediate offsets (the K loop is
-// unrolled by two so that the buffer is a compile-time constant).  MFMA fragments are
+// unrolled by five, the period of the slot pattern, so that slots are compile-time constants).  MFMA fragments are
 // double-buffered in registers: the LDS reads of the next 16-deep sub-step are issued before
 // the MFMAs of the current one.  One s_barrier per step, placed before the last MFMA group,
-// publishes the tile that was awaited and frees the buffer that was just read, so the next
-// loads start a full step before they are needed.
+// publishes the tiles that were awaited and frees the two slots that were just read.
 //
 // Tile layouts.  An operand that is contiguous along K in memory (activations [rows, K],
 // forward weights [N, K]) is kept as [256 rows][64 k] with 128-byte rows whose eight 16-byte
@@ -35,11 +38,12 @@
 // formulas are applied on the way, on the fp32 accumulators.
 //
 // Tiles of the row-grouped products are found on the device from
-// expert_offsets: a workgroup turns its M-tile number into (expert, first row)
-// with a wave-wide prefix sum over ceil(rows_e / 256); experts without rows own
-// no tile; rows past an expert's end are clamped on load and masked on store.
+// expert_offsets: every wave turns the M-tile number into (expert, first row)
+// with a wave-wide prefix sum over ceil(rows_e / 256) (no LDS is left for a table); experts
+// without rows own no tile; rows past an expert's end are clamped on load and masked on store.
 #include <type_traits>
 #include "common.h"
+
 
 
 namespace {
@@ -47,9 +51,11 @@ namespace {
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int GEMM_THREADS = 512;
 constexpr int TILE_BYTES = BM * BK * 2;               // one operand tile (32 KB)
-constexpr int B_TILES = 2 * TILE_BYTES;               // LDS: A buffer 0, A buffer 1, B buffer 0, B buffer 1
-constexpr int LDS_BYTES = 4 * TILE_BYTES;             // 128 KB
-constexpr int WAVE_STAGE_BYTES = LDS_BYTES / 8;       // epilogue staging per wave (16 KB)
+constexpr int NSLOT = 5;                              // ring of operand tile slots
+constexpr int LDS_BYTES = NSLOT * TILE_BYTES;         // 160 KB: everything a workgroup can have
+constexpr int WAVE_STAGE_BYTES = 16384;               // epilogue staging per wave
+constexpr int slot_of_a(int p) { return (2 * p) % NSLOT; }       // p = step mod 5
+constexpr int slot_of_b(int p) { return (2 * p + 1) % NSLOT; }
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
@@ -108,13 +114,13 @@ template <int OFF> __device__ __forceinline__ s16x4 lds_read_tr_b64(uint32_t add
 // assembly too, so that the (scalar base) + (32-bit lane offset) form is certain: with 64-bit lane
 // addresses every load needs vector-ALU work.  M0 carries the LDS address; nothing else in this
 // file uses M0.
-__device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const char* sbase) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+template <int OFF> __device__ __forceinline__ void dma16(uint32_t lds_base, uint32_t voff, const char* sbase) {
+  asm volatile("s_add_i32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_base), "v"(voff), "s"(sbase), "n"(OFF) : "memory", "scc");
 }
-__device__ __forceinline__ void dma16_lane(uint32_t lds_addr, const char* p) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-               :: "s"(lds_addr), "v"(p) : "memory");
+template <int OFF> __device__ __forceinline__ void dma16_lane(uint32_t lds_base, const char* p) {
+  asm volatile("s_add_i32 m0, %0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :: "s"(lds_base), "v"(p), "n"(OFF) : "memory", "scc");
 }
 template <int N> __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
 
@@ -150,10 +156,60 @@ __device__ __forceinline__ void wg_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// Row tiles of the grouped products: expert e owns ceil(rows_e / 256) consecutive tile numbers.
+// Both functions are evaluated by a whole wave (64 experts per pass) and return wave-uniform values.
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+  for (int s = 1; s < 64; s <<= 1) {
+    const int u = __shfl_up(v, s, 64);
+    if (lane >= s) v += u;
+  }
+  return v;
+}
+__device__ __forceinline__ int count_row_tiles(const int32_t* offsets, int E, int lane) {
+  int total = 0;
+  for (int e0 = 0; e0 < E; e0 += 64) {
+    const int ee = e0 + lane;
+    const int rows = ee < E ? offsets[ee + 1] - offsets[ee] : 0;
+    total += __shfl(wave_incl_scan((rows + BM - 1) / BM, lane), 63, 64);
+  }
+  return __builtin_amdgcn_readfirstlane(total);
+}
+__device__ __forceinline__ void find_row_tile(const int32_t* offsets, int E, int mt, int lane, int& e, int& m0, int& m_end) {
+  int base = 0;
+  e = 0; m0 = 0; m_end = 0;
+  for (int e0 = 0; e0 < E; e0 += 64) {
+    const int ee = e0 + lane;
+    const int lo = ee < E ? offsets[ee] : 0;
+    const int hi = ee < E ? offsets[ee + 1] : 0;
+    const int tiles = (hi - lo + BM - 1) / BM;
+    const int inc = wave_incl_scan(tiles, lane);
+    const int excl = base + inc - tiles;
+    const unsigned long long hit = __ballot(tiles > 0 && excl <= mt && mt < excl + tiles);
+    if (hit) {
+      const int l = __ffsll(hit) - 1;
+      e = e0 + l;
+      m0 = __shfl(lo, l, 64) + (mt - __shfl(excl, l, 64)) * BM;
+      m_end = __shfl(hi, l, 64);
+      return;
+    }
+    base += __shfl(inc, 63, 64);
+  }
+}
+
+// The kernel arguments again, through a pointer the compiler cannot see through: what is read from
+// it is loaded afresh (scalar loads from the argument segment) instead of being kept in scalar
+// registers across the main loop, which needs them for itself.
+typedef const __attribute__((address_space(4))) GemmArgs* ArgPtr;
+__device__ __forceinline__ ArgPtr reload_args() {
+  ArgPtr p = (ArgPtr)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(p));
+  return p;
+}
+
 template <int MODE>
 __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  __shared__ int s_pref[MOE_MAX_EXPERTS + 1];   // exclusive prefix of row tiles per expert (modes 0-3)
   const int tid0 = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
   const int wm = wave >> 2, wn = wave & 3;
@@ -164,30 +220,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   // (b % 8) * (gridDim.x / 8) + b / 8 of every round: each XCD then works on a run of
   // consecutive tiles (same expert, neighbouring panels) that share its L2.
   int total;
-  if constexpr (MODE == WGRAD) {
-    total = a.E * a.m_tiles_cap * a.n_tiles;
-  } else {
-    if (wave == 0) {
-      int base = 0;
-      for (int e0 = 0; e0 < a.E; e0 += 64) {
-        const int lane = tid0 & 63;
-        const int ee = e0 + lane;
-        const int rows = ee < a.E ? a.offsets[ee + 1] - a.offsets[ee] : 0;
-        const int tiles = (rows + BM - 1) / BM;
-        int inc = tiles;
-#pragma unroll
-        for (int s = 1; s < 64; s <<= 1) {
-          const int v = __shfl_up(inc, s, 64);
-          if (lane >= s) inc += v;
-        }
-        if (ee < a.E) s_pref[ee] = base + inc - tiles;
-        base += __shfl(inc, 63, 64);
-      }
-      if ((tid0 & 63) == 0) s_pref[a.E] = base;
-    }
-    __syncthreads();
-    total = s_pref[a.E] * a.n_tiles;
-  }
+  if constexpr (MODE == WGRAD) total = a.E * a.m_tiles_cap * a.n_tiles;
+  else total = count_row_tiles(a.offsets, a.E, tid0 & 63) * a.n_tiles;
   const int per_xcd = gridDim.x >> 3;
   const int first_tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
 
@@ -205,15 +239,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     m0 = (rest % a.m_tiles_cap) * BM;   // output row of dW
     m_end = a.M;
   } else {
-    const int mt = tile / a.n_tiles;
-    int lo = 0, hi = a.E;               // last expert whose first tile is <= mt
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (s_pref[mid] <= mt) lo = mid; else hi = mid;
-    }
-    e = lo;
-    m0 = a.offsets[e] + (mt - s_pref[e]) * BM;
-    m_end = a.offsets[e + 1];
+    find_row_tile(a.offsets, a.E, tile / a.n_tiles, lane, e, m0, m_end);
   }
   // tile coordinates are wave-uniform: keep them in scalar registers, so that everything derived
   // from them (operand base addresses in particular) is scalar too
@@ -325,50 +351,63 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   const char* sb_phase1 = nullptr;
   if constexpr (MODE == DGRAD_X) { sa_phase1 = scalarize(abase + a_phase); sb_phase1 = scalarize(bbase + b_phase); }
 
-  // The loads of the next reduction step (kt, in order) into buffer BUF: load_begin fixes the
-  // step's bases and advances the running ones, load_part(i) issues the i-th A and B load.
-  int kk_cur = 0;                       // WGRAD only: the step being loaded, and whether it is the partial last one
-  bool tail_cur = false;
-  auto load_begin = [&](int kt) __attribute__((always_inline)) {
-    if constexpr (MODE == WGRAD) { kk_cur = kt; tail_cur = k_lo + (kt + 1) * BK > k_hi; }
-  };
-  auto load_end = [&](int kt) __attribute__((always_inline)) {
-    sa_next += a_step;
-    sb_next += b_step;
-    if constexpr (MODE == DGRAD_X) {
-      if (kt + 1 == nk_phase) { sa_next = sa_phase1; sb_next = sb_phase1; }
-    }
-  };
-  auto load_part = [&](auto buf_tag, auto i_tag) __attribute__((always_inline)) {
-    constexpr int BUF = decltype(buf_tag)::value, i = decltype(i_tag)::value;
-    const uint32_t la = lds_fill + BUF * TILE_BYTES + i * 1024;
-    const uint32_t lb = la + B_TILES;
+  // Loads come per operand tile ("unit"), in order of the steps: part i of a unit is this wave's
+  // i-th load of it, unit_end advances the operand's running base.
+  using J0 = std::integral_constant<int, 0>;
+  using J1 = std::integral_constant<int, 1>;
+  using J2 = std::integral_constant<int, 2>;
+  using J3 = std::integral_constant<int, 3>;
+  auto a_part = [&](int kt, auto slot_tag, auto i_tag) __attribute__((always_inline)) {
+    constexpr int SLOT = decltype(slot_tag)::value, i = decltype(i_tag)::value;
+    constexpr int OFF = SLOT * TILE_BYTES + i * 1024;
     if constexpr (MODE == WGRAD) {
-      if (tail_cur) {
-        // last, partial step of the expert: reduction rows at or past its end read zeros in A and
-        // a valid row in B (per-lane 64-bit addresses; once per tile)
-        const int krow = k_lo + kk_cur * BK + (wave * 4 + i) * 2 + (lane >> 5);
-        const char* pa = krow < k_hi ? sa_next + voa[i]
-                                     : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16;
-        const char* pb = sb_next + vob[i] - (krow < k_hi ? 0 : static_cast<size_t>(krow - (k_hi - 1)) * a.N * 2);
-        dma16_lane(la, pa);
-        dma16_lane(lb, pb);
+      if (k_lo + (kt + 1) * BK > k_hi) {
+        // last, partial step of the expert: reduction rows at or past its end read zeros
+        // (per-lane 64-bit addresses; once per tile)
+        const int krow = k_lo + kt * BK + (wave * 4 + i) * 2 + (lane >> 5);
+        dma16_lane<OFF>(lds_fill, krow < k_hi ? sa_next + voa[i]
+                                   : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16);
       } else {
-        dma16(la, voa[i], sa_next);
-        dma16(lb, vob[i], sb_next);
+        dma16<OFF>(lds_fill, voa[i], sa_next);
       }
     } else {
-      dma16(la, voa[i], sa_next);
-      dma16(lb, vob[i], sb_next);
+      dma16<OFF>(lds_fill, voa[i], sa_next);
     }
   };
-  auto load_tile = [&](int kt, auto buf_tag) __attribute__((always_inline)) {
-    load_begin(kt);
-    load_part(buf_tag, std::integral_constant<int, 0>{});
-    load_part(buf_tag, std::integral_constant<int, 1>{});
-    load_part(buf_tag, std::integral_constant<int, 2>{});
-    load_part(buf_tag, std::integral_constant<int, 3>{});
-    load_end(kt);
+  auto b_part = [&](int kt, auto slot_tag, auto i_tag) __attribute__((always_inline)) {
+    constexpr int SLOT = decltype(slot_tag)::value, i = decltype(i_tag)::value;
+    constexpr int OFF = SLOT * TILE_BYTES + i * 1024;
+    if constexpr (MODE == WGRAD) {
+      if (k_lo + (kt + 1) * BK > k_hi) {
+        // ... and the other operand reads its last valid row there, so that zero times it is zero
+        const int krow = k_lo + kt * BK + (wave * 4 + i) * 2 + (lane >> 5);
+        dma16_lane<OFF>(lds_fill, sb_next + vob[i] - (krow < k_hi ? 0 : static_cast<size_t>(krow - (k_hi - 1)) * a.N * 2));
+      } else {
+        dma16<OFF>(lds_fill, vob[i], sb_next);
+      }
+    } else {
+      dma16<OFF>(lds_fill, vob[i], sb_next);
+    }
+  };
+  auto a_end = [&](int kt) __attribute__((always_inline)) {
+    sa_next += a_step;
+    if constexpr (MODE == DGRAD_X) {
+      if (kt + 1 == nk_phase) sa_next = sa_phase1;
+    }
+  };
+  auto b_end = [&](int kt) __attribute__((always_inline)) {
+    sb_next += b_step;
+    if constexpr (MODE == DGRAD_X) {
+      if (kt + 1 == nk_phase) sb_next = sb_phase1;
+    }
+  };
+  auto a_unit = [&](int kt, auto slot_tag) __attribute__((always_inline)) {
+    a_part(kt, slot_tag, J0{}); a_part(kt, slot_tag, J1{}); a_part(kt, slot_tag, J2{}); a_part(kt, slot_tag, J3{});
+    a_end(kt);
+  };
+  auto b_unit = [&](int kt, auto slot_tag) __attribute__((always_inline)) {
+    b_part(kt, slot_tag, J0{}); b_part(kt, slot_tag, J1{}); b_part(kt, slot_tag, J2{}); b_part(kt, slot_tag, J3{});
+    b_end(kt);
   };
 
   // ---------------- main loop ----------------------------------------------------
@@ -382,43 +421,60 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
 
   const int lrow = lane & 31, lgrp = lane >> 5;
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<size_t>(LDS_PTR(lds)));
-  // Per-lane fragment addresses for buffer 0; buffer, sub-step (and half, for the transposing
-  // reads) are immediate offsets.  A swizzled [row][k] tile needs one address per sub-step.
-  uint32_t fa_addr[4][A_KN ? 1 : 4], fb_addr[2][B_KN ? 1 : 4];
+  // Per-lane fragment addresses.  Slot, fragment and sub-step are immediate offsets of the LDS
+  // reads, which reach 64 KB: one set of addresses serves slots 0-1, one slots 2-3, one slot 4.
+  //  [row][k] tile: an address per sub-step, for the wave's first fragment.  Fragment i lies
+  //    32 i rows = 4096 i bytes further, and an odd i flips bit 2 of the row swizzle, which is the
+  //    same as taking sub-step ks ^ 2.
+  //  [k][n] tile: an address per fragment (its swizzle depends on the column block); sub-step and
+  //    half are immediates.
+  const int b_row0 = (MODE == GATE_UP) ? wn * 32 : wn * 64;
+  uint32_t fa_base[3][4], fb_base[3][B_KN ? 2 : 4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row0 = wm * 128 + i * 32;
-    if constexpr (A_KN) fa_addr[i][0] = kn_frag_addr(lds0, row0, lane);
-    else {
+  for (int st = 0; st < 3; ++st) {
+    const uint32_t org = lds0 + st * 2 * TILE_BYTES;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) fa_addr[i][ks] = lds0 + kc_off(row0 + lrow, ks * 2 + lgrp);
+    for (int q = 0; q < 4; ++q) {
+      if constexpr (A_KN) fa_base[st][q] = kn_frag_addr(org, wm * 128 + q * 32, lane);
+      else fa_base[st][q] = org + kc_off(wm * 128 + lrow, q * 2 + lgrp);
     }
-  }
+    if constexpr (B_KN) {
+      fb_base[st][0] = kn_frag_addr(org, b_row0, lane);
+      fb_base[st][1] = kn_frag_addr(org, b_row0 + 32, lane);
+    } else {
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int row0 = (MODE == GATE_UP) ? j * 128 + wn * 32 : wn * 64 + j * 32;
-    if constexpr (B_KN) fb_addr[j][0] = kn_frag_addr(lds0 + B_TILES, row0, lane);
-    else {
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) fb_addr[j][ks] = lds0 + B_TILES + kc_off(row0 + lrow, ks * 2 + lgrp);
+      for (int q = 0; q < 4; ++q) fb_base[st][q] = org + kc_off(b_row0 + lrow, q * 2 + lgrp);
     }
   }
 
   bf16x8_t fa[2][4], fb[2][2];   // two fragment sets: one feeds the MFMAs while the other is being read
   constexpr int NREADS = (A_KN ? 8 : 4) + (B_KN ? 4 : 2);   // LDS read instructions per fragment set
-  // All six fragments are read even when some hold no valid row (the counts of outstanding reads
-  // stay fixed); only the MFMAs of such fragments are skipped.
-  auto read_frags = [&](auto buf_tag, auto ks_tag, auto set_tag) __attribute__((always_inline)) {
-    constexpr int BUF = decltype(buf_tag)::value, KS = decltype(ks_tag)::value, SET = decltype(set_tag)::value;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      if constexpr (B_KN) fb[SET][j] = lds_read_kn<BUF * TILE_BYTES + KS * 8192>(fb_addr[j][0]);
-      else fb[SET][j] = lds_read_b128<BUF * TILE_BYTES>(fb_addr[j][KS]);
+  // Reads sub-step KS of the tiles in slots SA (A) and SB (B) into fragment set SET.  All six
+  // fragments are read even when the wave owns no valid row: the counts of outstanding reads stay fixed.
+  auto read_frags = [&](auto sa_tag, auto sb_tag, auto ks_tag, auto set_tag) __attribute__((always_inline)) {
+    constexpr int SA = decltype(sa_tag)::value, SB = decltype(sb_tag)::value;
+    constexpr int KS = decltype(ks_tag)::value, SET = decltype(set_tag)::value;
+    constexpr int OA = (SA & 1) * TILE_BYTES, OB = (SB & 1) * TILE_BYTES;
+    if constexpr (B_KN) {
+      fb[SET][0] = lds_read_kn<OB + KS * 8192>(fb_base[SB >> 1][0]);
+      fb[SET][1] = lds_read_kn<OB + KS * 8192>(fb_base[SB >> 1][1]);
+    } else if constexpr (MODE == GATE_UP) {   // second fragment: the up half, 128 tile rows further
+      fb[SET][0] = lds_read_b128<OB>(fb_base[SB >> 1][KS]);
+      fb[SET][1] = lds_read_b128<OB + 128 * 128>(fb_base[SB >> 1][KS]);
+    } else {
+      fb[SET][0] = lds_read_b128<OB>(fb_base[SB >> 1][KS]);
+      fb[SET][1] = lds_read_b128<OB + 4096>(fb_base[SB >> 1][KS ^ 2]);
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if constexpr (A_KN) fa[SET][i] = lds_read_kn<BUF * TILE_BYTES + KS * 8192>(fa_addr[i][0]);
-      else fa[SET][i] = lds_read_b128<BUF * TILE_BYTES>(fa_addr[i][KS]);
+    if constexpr (A_KN) {
+      fa[SET][0] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][0]);
+      fa[SET][1] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][1]);
+      fa[SET][2] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][2]);
+      fa[SET][3] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][3]);
+    } else {
+      fa[SET][0] = lds_read_b128<OA>(fa_base[SA >> 1][KS]);
+      fa[SET][1] = lds_read_b128<OA + 4096>(fa_base[SA >> 1][KS ^ 2]);
+      fa[SET][2] = lds_read_b128<OA + 8192>(fa_base[SA >> 1][KS]);
+      fa[SET][3] = lds_read_b128<OA + 12288>(fa_base[SA >> 1][KS ^ 2]);
     }
   };
   // weight fragment first: the lane then holds 4 consecutive output columns of one row.
@@ -435,97 +491,126 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       }
   };
 
-  // the same MFMA group with the loads of step kt_load in between (if do_load): one A and one B
-  // load after every second MFMA, so that neither wave of a SIMD holds the matrix pipe up with a
-  // burst of loads.  The MFMAs are not duplicated across the branch on purpose.
-  auto mma_loading = [&](auto set_tag, auto full_tag, auto buf_tag, bool do_load, int kt_load) __attribute__((always_inline)) {
+  // One quarter of an MFMA group: the two MFMAs that share activation fragment i.  The loads of a
+  // step are issued between such pairs, never in a burst: a wave whose load has to queue for the
+  // texture path issues nothing else meanwhile, its MFMAs included.
+  auto mma_pair = [&](auto set_tag, auto i_tag, auto full_tag) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_tag)::value;
-    constexpr int set = decltype(set_tag)::value;
-    if (do_load) load_begin(kt_load);
-#define MMA_PART(i)                                                                                          \
-    if constexpr (FULL) {                                                                                    \
-      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][0], fa[set][i], acc[i][0], 0, 0, 0);       \
-      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][1], fa[set][i], acc[i][1], 0, 0, 0);       \
-    }                                                                                                        \
-    __builtin_amdgcn_sched_barrier(0);                                                                       \
-    if (do_load) load_part(buf_tag, std::integral_constant<int, i>{});                                       \
+    constexpr int set = decltype(set_tag)::value, i = decltype(i_tag)::value;
+    if constexpr (FULL) {
+      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][0], fa[set][i], acc[i][0], 0, 0, 0);
+      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][1], fa[set][i], acc[i][1], 0, 0, 0);
+    }
     __builtin_amdgcn_sched_barrier(0);
-    MMA_PART(0)
-    MMA_PART(1)
-    MMA_PART(2)
-    MMA_PART(3)
-#undef MMA_PART
-    if (do_load) load_end(kt_load);
   };
 
   const int grow0 = m0 + wm * 128;                                   // wave's first output row
   const int gcol0 = n0 + wn * (MODE == GATE_UP ? 32 : 64);           // wave's first output column
   // DGRAD_H: saved g / u rows of one 64-row half of the wave's piece, 16 bytes per lane and pass
   u32x4 pg[8], pu[8];
-  auto gu_load = [&](int hh) __attribute__((always_inline)) {
+  auto gu_load = [&](int hh, ArgPtr ap) __attribute__((always_inline)) {
     if constexpr (MODE == DGRAD_H) {
+      const int ncol = ap->N;
+      const uint16_t* gsrc = ap->G;
+      const uint16_t* usrc = ap->U;
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
         const int row = p * 8 + (lane >> 3), piece = lane & 7;
         int gr = grow0 + hh * 64 + row;  if (gr > m_end - 1) gr = m_end - 1;
-        int gc = gcol0 + piece * 8;  if (gc > a.N - 8) gc = a.N - 8;
-        const size_t o = static_cast<size_t>(gr) * a.N + gc;
-        pg[p] = *reinterpret_cast<const u32x4*>(a.G + o);
-        pu[p] = *reinterpret_cast<const u32x4*>(a.U + o);
+        int gc = gcol0 + piece * 8;  if (gc > ncol - 8) gc = ncol - 8;
+        const size_t o = static_cast<size_t>(gr) * ncol + gc;
+        pg[p] = *reinterpret_cast<const u32x4*>(gsrc + o);
+        pu[p] = *reinterpret_cast<const u32x4*>(usrc + o);
       }
     }
   };
 
-  // Step kt reads buffer kt&1.  Its barrier comes before its last MFMA group, after every wave
-  // has (a) seen its own loads of step kt+1 land and (b) received its last fragments of step kt.
-  // Behind it the other buffer is complete, and this buffer is free for step kt+2, whose loads
-  // then have a whole step to land.
+  // Step kt (phase P = kt mod 5) reads A from slot 2P mod 5 and B from slot (2P+1) mod 5.  Its
+  // barrier comes before its last MFMA group, after every wave has (a) seen its own loads of
+  // A(kt+1) and B(kt+1) land (the four loads of A(kt+2), issued last, may still be in flight) and
+  // (b) received its last fragments of step kt.  Behind it the tiles of step kt+1 are complete and
+  // the two slots of step kt are free: B(kt+2) goes into A's slot at once, A(kt+3) into B's slot
+  // between the MFMAs.
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
   using I2 = std::integral_constant<int, 2>;
   using I3 = std::integral_constant<int, 3>;
   auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
-  auto step = [&](int kt, auto buf_tag, auto full_tag) __attribute__((always_inline)) {
-    constexpr int BUF = decltype(buf_tag)::value;
-    using THIS = std::integral_constant<int, BUF>;
-    using OTHER = std::integral_constant<int, 1 - BUF>;
-    read_frags(THIS{}, I1{}, I1{});
-    lds_wait<NREADS>();  fence();  mma(I0{}, full_tag);  fence();
-    read_frags(THIS{}, I2{}, I0{});
-    lds_wait<NREADS>();  fence();  mma(I1{}, full_tag);  fence();
-    read_frags(THIS{}, I3{}, I1{});
-    lds_wait<NREADS>();  fence();  mma(I0{}, full_tag);  fence();
+  auto step = [&](int kt, auto phase_tag, auto full_tag) __attribute__((always_inline)) {
+    constexpr int P = decltype(phase_tag)::value;
+    using SA = std::integral_constant<int, slot_of_a(P)>;
+    using SB = std::integral_constant<int, slot_of_b(P)>;
+    using NA = std::integral_constant<int, slot_of_a((P + 1) % NSLOT)>;
+    using NB = std::integral_constant<int, slot_of_b((P + 1) % NSLOT)>;
+    using LA = std::integral_constant<int, slot_of_a((P + 2) % NSLOT)>;   // where A(kt+2) goes: B(kt-1)'s slot
+    const bool more = kt + 2 < nk;
+    read_frags(SA{}, SB{}, I1{}, I1{});
+    lds_wait<NREADS>();  fence();
+    mma_pair(I0{}, J0{}, full_tag);  mma_pair(I0{}, J1{}, full_tag);
+    if (more) a_part(kt + 2, LA{}, J0{});
+    fence();
+    mma_pair(I0{}, J2{}, full_tag);  mma_pair(I0{}, J3{}, full_tag);
+    if (more) a_part(kt + 2, LA{}, J1{});
+    fence();
+    read_frags(SA{}, SB{}, I2{}, I0{});
+    lds_wait<NREADS>();  fence();
+    mma_pair(I1{}, J0{}, full_tag);  mma_pair(I1{}, J1{}, full_tag);
+    if (more) a_part(kt + 2, LA{}, J2{});
+    fence();
+    mma_pair(I1{}, J2{}, full_tag);  mma_pair(I1{}, J3{}, full_tag);
+    if (more) { a_part(kt + 2, LA{}, J3{}); a_end(kt + 2); }
+    fence();
+    read_frags(SA{}, SB{}, I3{}, I1{});
+    lds_wait<NREADS>();  fence();
+    mma(I0{}, full_tag);  fence();
     if (kt + 1 < nk) {
-      wait_vm<0>();
+      if (more) wait_vm<4>(); else wait_vm<0>();
       lds_wait<0>();
       wg_barrier();
-      read_frags(OTHER{}, I0{}, I0{});
+      read_frags(NA{}, NB{}, I0{}, I0{});
     } else {
       lds_wait<0>();
     }
     fence();
-    mma_loading(I1{}, full_tag, THIS{}, kt + 2 < nk, kt + 2);
+    // B(kt+2) goes into A(kt)'s slot, one load after each MFMA pair
+    mma_pair(I1{}, J0{}, full_tag);
+    if (more) b_part(kt + 2, SA{}, J0{});
+    fence();
+    mma_pair(I1{}, J1{}, full_tag);
+    if (more) b_part(kt + 2, SA{}, J1{});
+    fence();
+    mma_pair(I1{}, J2{}, full_tag);
+    if (more) b_part(kt + 2, SA{}, J2{});
+    fence();
+    mma_pair(I1{}, J3{}, full_tag);
+    if (more) { b_part(kt + 2, SA{}, J3{}); b_end(kt + 2); }
     fence();
   };
   auto main_loop = [&](auto full_tag) __attribute__((always_inline)) {
     if (nk > 0) {
-      load_tile(0, I0{});
-      wait_vm<0>();
+      a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
+      b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
+      if (nk > 1) {
+        a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
+        b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
+      }
+      if (nk > 1) wait_vm<8>(); else wait_vm<0>();
       wg_barrier();
-      if (nk > 1) load_tile(1, I1{});
-      read_frags(I0{}, I0{}, I0{});
+      read_frags(std::integral_constant<int, slot_of_a(0)>{}, std::integral_constant<int, slot_of_b(0)>{}, I0{}, I0{});
     }
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
+    for (int kt = 0; kt < nk; kt += NSLOT) {
       step(kt, I0{}, full_tag);
-      step(kt + 1, I1{}, full_tag);
+      if (kt + 1 < nk) step(kt + 1, I1{}, full_tag);
+      if (kt + 2 < nk) step(kt + 2, I2{}, full_tag);
+      if (kt + 3 < nk) step(kt + 3, I3{}, full_tag);
+      if (kt + 4 < nk) step(kt + 4, std::integral_constant<int, 4>{}, full_tag);
     }
-    if (kt < nk) step(kt, I0{}, full_tag);
   };
   // a wave whose 128 rows all lie past the expert's end only keeps the loads and barriers going
   if (nfa > 0) main_loop(std::true_type{}); else main_loop(std::false_type{});
-  gu_load(0);
-  wg_barrier();                             // every wave is done with the operand stages
+  const ArgPtr ae = reload_args();          // the epilogue reads its arguments afresh
+  gu_load(0, ae);
+  wg_barrier();                             // every wave is done with the operand tiles
 
   // ---------------- epilogue -----------------------------------------------------
   // acc[i][j][4q+c] is the wave's element (row, col) with row = i*32 + lrow and
@@ -564,8 +649,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
         for (int q = 0; q < 4; ++q)
           put_quad(i * 32 + lrow, j * 4 + q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
     __builtin_amdgcn_wave_barrier();
-    flush(a.O0, a.N, grow0, 128, 0, 4, gcol0, a.N);
-    flush(a.O1, a.N, grow0, 128, 4, 4, gcol0, a.N);
+    flush(ae->O0, ae->N, grow0, 128, 0, 4, gcol0, ae->N);
+    flush(ae->O1, ae->N, grow0, 128, 4, 4, gcol0, ae->N);
     __builtin_amdgcn_wave_barrier();
     // pass 2: h = silu(g) * u from the fp32 accumulators
 #pragma unroll
@@ -578,7 +663,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
         put_quad(i * 32 + lrow, q, h[0], h[1], h[2], h[3]);
       }
     __builtin_amdgcn_wave_barrier();
-    flush(a.O2, a.N, grow0, 128, 0, 4, gcol0, a.N);
+    flush(ae->O2, ae->N, grow0, 128, 0, 4, gcol0, ae->N);
   } else if constexpr (MODE == DGRAD_H) {
     // two halves of 64 rows: g rows at stage[0, 8K), u rows at stage[8K, 16K).  The g/u rows of
     // the first half were requested before the last K step, those of the second half are
@@ -594,7 +679,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
         *reinterpret_cast<u32x4*>(stage + so) = pg[p];
         *reinterpret_cast<u32x4*>(ustage + so) = pu[p];
       }
-      if (hh == 0) gu_load(1);
+      if (hh == 0) gu_load(1, ae);
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int i2 = 0; i2 < 2; ++i2)
@@ -630,10 +715,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
         const u32x4 dgv = *reinterpret_cast<const u32x4*>(stage + so);
         const u32x4 duv = *reinterpret_cast<const u32x4*>(ustage + so);
         const int gr = first + row, gc = gcol0 + piece * 8;
-        if (gr < m_end && gc < a.N) {
-          const size_t o = static_cast<size_t>(gr) * a.N + gc;
-          *reinterpret_cast<u32x4*>(a.O0 + o) = dgv;
-          *reinterpret_cast<u32x4*>(a.O1 + o) = duv;
+        if (gr < m_end && gc < ae->N) {
+          const size_t o = static_cast<size_t>(gr) * ae->N + gc;
+          *reinterpret_cast<u32x4*>(ae->O0 + o) = dgv;
+          *reinterpret_cast<u32x4*>(ae->O1 + o) = duv;
         }
       }
       __builtin_amdgcn_wave_barrier();
@@ -647,9 +732,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
         for (int q = 0; q < 4; ++q)
           put_quad(i * 32 + lrow, j * 4 + q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
     __builtin_amdgcn_wave_barrier();
-    uint16_t* out = a.O0;
-    if constexpr (MODE == WGRAD) out += static_cast<size_t>(e) * a.M * a.N;
-    flush(out, a.N, grow0, 128, 0, 8, gcol0, a.N);
+    uint16_t* out = ae->O0;
+    if constexpr (MODE == WGRAD) out += static_cast<size_t>(e) * ae->M * ae->N;
+    flush(out, ae->N, grow0, 128, 0, 8, gcol0, ae->N);
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's staging reads are done
   wg_barrier();      // the staging area becomes operand stages again
