@@ -448,10 +448,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   }
 
   bf16x8_t fa[2][4], fb[2][2];   // two fragment sets: one feeds the MFMAs while the other is being read
-  constexpr int NREADS = (A_KN ? 8 : 4) + (B_KN ? 4 : 2);   // LDS read instructions per fragment set
-  // Reads sub-step KS of the tiles in slots SA (A) and SB (B) into fragment set SET.  All six
-  // fragments are read even when the wave owns no valid row: the counts of outstanding reads stay fixed.
-  auto read_frags = [&](auto sa_tag, auto sb_tag, auto ks_tag, auto set_tag) __attribute__((always_inline)) {
+  // LDS read instructions per fragment set when NFA activation fragments are live (none at all for NFA = 0)
+  constexpr auto nreads = [](int nfa) { return nfa == 0 ? 0 : (A_KN ? 2 : 1) * nfa + (B_KN ? 4 : 2); };
+  // Reads sub-step KS of the tiles in slots SA (A) and SB (B) into fragment set SET.  Activation
+  // fragments without a valid row are not read: nothing would keep their registers reserved until
+  // the data lands.
+  auto read_frags = [&](auto sa_tag, auto sb_tag, auto ks_tag, auto set_tag, auto full_tag) __attribute__((always_inline)) {
+    constexpr int NFA = decltype(full_tag)::value;
+    if constexpr (NFA == 0) return;
     constexpr int SA = decltype(sa_tag)::value, SB = decltype(sb_tag)::value;
     constexpr int KS = decltype(ks_tag)::value, SET = decltype(set_tag)::value;
     constexpr int OA = (SA & 1) * TILE_BYTES, OB = (SB & 1) * TILE_BYTES;
@@ -466,25 +470,25 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       fb[SET][1] = lds_read_b128<OB + 4096>(fb_base[SB >> 1][KS ^ 2]);
     }
     if constexpr (A_KN) {
-      fa[SET][0] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][0]);
-      fa[SET][1] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][1]);
-      fa[SET][2] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][2]);
-      fa[SET][3] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][3]);
+      if constexpr (NFA > 0) fa[SET][0] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][0]);
+      if constexpr (NFA > 1) fa[SET][1] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][1]);
+      if constexpr (NFA > 2) fa[SET][2] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][2]);
+      if constexpr (NFA > 3) fa[SET][3] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][3]);
     } else {
-      fa[SET][0] = lds_read_b128<OA>(fa_base[SA >> 1][KS]);
-      fa[SET][1] = lds_read_b128<OA + 4096>(fa_base[SA >> 1][KS ^ 2]);
-      fa[SET][2] = lds_read_b128<OA + 8192>(fa_base[SA >> 1][KS]);
-      fa[SET][3] = lds_read_b128<OA + 12288>(fa_base[SA >> 1][KS ^ 2]);
+      if constexpr (NFA > 0) fa[SET][0] = lds_read_b128<OA>(fa_base[SA >> 1][KS]);
+      if constexpr (NFA > 1) fa[SET][1] = lds_read_b128<OA + 4096>(fa_base[SA >> 1][KS ^ 2]);
+      if constexpr (NFA > 2) fa[SET][2] = lds_read_b128<OA + 8192>(fa_base[SA >> 1][KS]);
+      if constexpr (NFA > 3) fa[SET][3] = lds_read_b128<OA + 12288>(fa_base[SA >> 1][KS ^ 2]);
     }
   };
   // weight fragment first: the lane then holds 4 consecutive output columns of one row.
-  // FULL = false: the wave owns no valid row and issues no MFMA at all
+  // the tag is the number of 32-row fragments of the wave that hold a valid row; the others issue no MFMA
   auto mma = [&](auto set_tag, auto full_tag) __attribute__((always_inline)) {
-    constexpr bool FULL = decltype(full_tag)::value;
+    constexpr int NFA = decltype(full_tag)::value;
     constexpr int set = decltype(set_tag)::value;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      if constexpr (FULL) {
+      if (i < NFA) {
 #pragma unroll
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
@@ -495,9 +499,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   // step are issued between such pairs, never in a burst: a wave whose load has to queue for the
   // texture path issues nothing else meanwhile, its MFMAs included.
   auto mma_pair = [&](auto set_tag, auto i_tag, auto full_tag) __attribute__((always_inline)) {
-    constexpr bool FULL = decltype(full_tag)::value;
+    constexpr int NFA = decltype(full_tag)::value;
     constexpr int set = decltype(set_tag)::value, i = decltype(i_tag)::value;
-    if constexpr (FULL) {
+    if constexpr (i < NFA) {
       acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][0], fa[set][i], acc[i][0], 0, 0, 0);
       acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][1], fa[set][i], acc[i][1], 0, 0, 0);
     }
@@ -544,30 +548,30 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     using NB = std::integral_constant<int, slot_of_b((P + 1) % NSLOT)>;
     using LA = std::integral_constant<int, slot_of_a((P + 2) % NSLOT)>;   // where A(kt+2) goes: B(kt-1)'s slot
     const bool more = kt + 2 < nk;
-    read_frags(SA{}, SB{}, I1{}, I1{});
-    lds_wait<NREADS>();  fence();
+    read_frags(SA{}, SB{}, I1{}, I1{}, full_tag);
+    lds_wait<nreads(decltype(full_tag)::value)>();  fence();
     mma_pair(I0{}, J0{}, full_tag);  mma_pair(I0{}, J1{}, full_tag);
     if (more) a_part(kt + 2, LA{}, J0{});
     fence();
     mma_pair(I0{}, J2{}, full_tag);  mma_pair(I0{}, J3{}, full_tag);
     if (more) a_part(kt + 2, LA{}, J1{});
     fence();
-    read_frags(SA{}, SB{}, I2{}, I0{});
-    lds_wait<NREADS>();  fence();
+    read_frags(SA{}, SB{}, I2{}, I0{}, full_tag);
+    lds_wait<nreads(decltype(full_tag)::value)>();  fence();
     mma_pair(I1{}, J0{}, full_tag);  mma_pair(I1{}, J1{}, full_tag);
     if (more) a_part(kt + 2, LA{}, J2{});
     fence();
     mma_pair(I1{}, J2{}, full_tag);  mma_pair(I1{}, J3{}, full_tag);
     if (more) { a_part(kt + 2, LA{}, J3{}); a_end(kt + 2); }
     fence();
-    read_frags(SA{}, SB{}, I3{}, I1{});
-    lds_wait<NREADS>();  fence();
+    read_frags(SA{}, SB{}, I3{}, I1{}, full_tag);
+    lds_wait<nreads(decltype(full_tag)::value)>();  fence();
     mma(I0{}, full_tag);  fence();
     if (kt + 1 < nk) {
       if (more) wait_vm<4>(); else wait_vm<0>();
       lds_wait<0>();
       wg_barrier();
-      read_frags(NA{}, NB{}, I0{}, I0{});
+      read_frags(NA{}, NB{}, I0{}, I0{}, full_tag);
     } else {
       lds_wait<0>();
     }
@@ -596,7 +600,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       }
       if (nk > 1) wait_vm<8>(); else wait_vm<0>();
       wg_barrier();
-      read_frags(std::integral_constant<int, slot_of_a(0)>{}, std::integral_constant<int, slot_of_b(0)>{}, I0{}, I0{});
+      read_frags(std::integral_constant<int, slot_of_a(0)>{}, std::integral_constant<int, slot_of_b(0)>{}, I0{}, I0{}, full_tag);
     }
     for (int kt = 0; kt < nk; kt += NSLOT) {
       step(kt, I0{}, full_tag);
@@ -606,8 +610,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       if (kt + 4 < nk) step(kt + 4, std::integral_constant<int, 4>{}, full_tag);
     }
   };
-  // a wave whose 128 rows all lie past the expert's end only keeps the loads and barriers going
-  if (nfa > 0) main_loop(std::true_type{}); else main_loop(std::false_type{});
+  // one copy of the loop per number of live fragments: a wave whose 128 rows all lie past the
+  // expert's end only keeps the loads and barriers going
+  switch (nfa) {
+    case 4: main_loop(std::integral_constant<int, 4>{}); break;
+    case 3: main_loop(std::integral_constant<int, 3>{}); break;
+    case 2: main_loop(std::integral_constant<int, 2>{}); break;
+    case 1: main_loop(std::integral_constant<int, 1>{}); break;
+    default: main_loop(std::integral_constant<int, 0>{}); break;
+  }
   const ArgPtr ae = reload_args();          // the epilogue reads its arguments afresh
   gu_load(0, ae);
   wg_barrier();                             // every wave is done with the operand tiles
