@@ -131,6 +131,10 @@ def test_permute_then_combine_is_identity():
     ([300, 0, 5, 257, 256, 1, 0, 700], 192, 320),  # ragged rows and columns, empty experts
     ([1100, 900], 512, 128),                      # several row tiles per expert
     ([0, 0, 40], 64, 64),                         # leading empty experts, minimum sizes
+    ([70, 1, 63, 64, 65, 128, 320, 330, 449], 64, 64),   # one reduction step forward; 1..8 steps in the weight gradients
+    ([130, 130, 130], 320, 448),                  # 5 and 7 reduction steps: one and more rounds of the tile ring
+    ([257, 511], 384, 704),                       # 6 and 11 steps, rows just past a tile boundary
+    ([3] * 130, 64, 128),                         # more experts than one wave scans in a pass
 ])
 def test_grouped_gemm_fwd_bwd_isolated(counts, d, f):
     print(f"gemm counts={counts} d={d} f={f}", flush=True)
