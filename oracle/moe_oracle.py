@@ -15,6 +15,11 @@ What is defined here (paper: Section 3.1 "FastSparseMoE" and Algorithm 1):
 * ``combine_bwd``      Stage 5, ExpertOutputReductionBackward.
 * ``expert_mlp_bwd``   derivative of Stage 4 (the paper leaves it to autograd).
 * ``permute_bwd``      derivative of the Stage-4 gather (likewise).
+* ``router_logits``    Stage 1, ``logits = Router(input)`` (the router is a Linear layer without bias).
+* ``route_bwd``        derivative of Stage 1's Softmax / TopK / renormalisation with respect to the
+                       logits, for a given gradient of the k gate weights (autograd in the paper).
+* ``router_bwd``       derivative of the router's Linear layer: its weight gradient and its share of
+                       the gradient of the layer input.
 
 The paper's method is a re-organisation of the dropless top-k SwiGLU MoE layer,
 not an approximation of it, so every function is the plain definition written
@@ -75,6 +80,48 @@ def route(logits: np.ndarray, k: int, renormalize: int = 1,
     if renormalize:
         topk_w = topk_w / topk_w.sum(axis=1, keepdims=True)
     return topk_idx, topk_w
+
+
+def router_logits(x: np.ndarray, Wr: np.ndarray) -> np.ndarray:
+    """Stage 1, first line: logits[t, e] = sum_j x[t, j] * Wr[e, j] (a Linear layer, no bias)."""
+    return np.asarray(x) @ np.asarray(Wr, dtype=np.asarray(x).dtype).T
+
+
+def route_bwd(logits: np.ndarray, topk_idx: np.ndarray, dgate: np.ndarray, renormalize: int = 1,
+              dtype=np.float64) -> np.ndarray:
+    """Gradient with respect to the logits, given dgate[t, i] = dL/d topk_w[t, i].
+
+    The chosen experts are held fixed (TopK passes the gradient to the chosen
+    entries and nothing to the others).  With p = Softmax(logits), s_i = p[idx_i]
+    and S = sum_i s_i:  topk_w_i = s_i / S when renormalising, else s_i.
+      renormalised:   dL/ds_i = (dgate_i - sum_j dgate_j * topk_w_j) / S
+      otherwise:      dL/ds_i = dgate_i
+    dL/dp_e = dL/ds_i where e = idx_i, else 0, and through the softmax
+      dlogits_e = p_e * (dL/dp_e - sum_e' dL/dp_e' * p_e').
+    """
+    l = np.asarray(logits, dtype=np.float32).astype(dtype)
+    idx = np.asarray(topk_idx).astype(np.int64)
+    dgate = np.asarray(dgate, dtype=dtype)
+    z = np.exp(l - l.max(axis=1, keepdims=True))
+    p = z / z.sum(axis=1, keepdims=True)
+    s = np.take_along_axis(p, idx, axis=1)
+    if renormalize:
+        S = s.sum(axis=1, keepdims=True)
+        w = s / S
+        ds = (dgate - (dgate * w).sum(axis=1, keepdims=True)) / S
+    else:
+        ds = dgate
+    dp = np.zeros_like(p)
+    np.put_along_axis(dp, idx, ds, axis=1)
+    return p * (dp - (dp * p).sum(axis=1, keepdims=True))
+
+
+def router_bwd(x: np.ndarray, Wr: np.ndarray, dlogits: np.ndarray):
+    """Derivative of ``logits = x @ Wr.T``: dWr = dlogits.T @ x, dx = dlogits @ Wr."""
+    x = np.asarray(x)
+    Wr = np.asarray(Wr, dtype=x.dtype)
+    dl = np.asarray(dlogits, dtype=x.dtype)
+    return dl.T @ x, dl @ Wr
 
 
 # --------------------------------------------------------------------------
