@@ -193,6 +193,32 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    # ---- the router and the Stage-1 backward (rows "next" of the scope table): timed apart, not in `value`
+    if "Wr" in inp:
+        Wr = torch.from_numpy(inp["Wr"]).to(dev)
+        lg = torch.empty_like(logits)
+        dl = torch.empty_like(logits)
+        dWr = torch.empty_like(Wr)
+        rws = torch.zeros(max(B.moe_router_bwd_workspace_bytes(cfg.T, cfg.d, cfg.E), 256), dtype=torch.uint8, device=dev)
+
+        def router_pass():
+            B.moe_router_fwd(x, Wr, lg)
+            B.moe_route_bwd(lg, buf.topk_idx, buf.dgate, cfg.renormalize, dl)
+            B.moe_router_bwd(x, Wr, dl, buf.dx, dWr, rws)
+
+        for _ in range(3):
+            router_pass()
+        torch.cuda.synchronize()
+        B.moe_prof_enable(True)
+        for _ in range(args.steps):
+            router_pass()
+        torch.cuda.synchronize()
+        rp = {n: round(ms / max(c, 1) * 1e3, 2) for n, ms, c in B.moe_prof_read()}
+        B.moe_prof_enable(False)
+        line["router_path"] = {"kernels_us": rp, "us_per_step": round(sum(rp.values()), 1),
+                               "flop_per_step": 6.0 * cfg.T * cfg.E * cfg.d,
+                               "note": "router Linear layer, gradient of softmax/top-k/renormalisation, router weight "
+                                       "and input gradients; not part of `value`"}
     if not args.no_cpu:
         n = min(args.cpu_sample_tokens, cfg.T)
         cb, _ = cpu_baseline(cfg, inp, n)

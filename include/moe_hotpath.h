@@ -162,6 +162,43 @@ int moe_unpermute_combine_bwd(const moe_bf16* dout, const moe_bf16* yp,
                               int T, int k, int d, moe_bf16* dyp, float* dgate, void* stream);
 
 /*
+ * The router itself and the derivative of Stage 1 (Algorithm 1: logits = Router(input), a Linear
+ * layer; the paper leaves the backward pass to autograd).  These calls complete the layer as a
+ * drop-in block: moe_router_fwd feeds moe_route, and dgate from moe_unpermute_combine_bwd goes
+ * back through moe_route_bwd and moe_router_bwd.
+ *
+ * moe_router_fwd:  logits[t, e] = sum_j x[t, j] * Wr[e, j]   (no bias)
+ *   x [T, d] bf16, Wr [E, d] fp32, logits [T, E] fp32 out.  d % 16 == 0, E <= MOE_MAX_EXPERTS.
+ *   The products are formed exactly and summed in fp32 (the summation order differs from a host
+ *   matrix product, so logits agree to fp32 rounding, not bit for bit).
+ */
+int moe_router_fwd(const moe_bf16* x, const float* Wr, int T, int d, int E, float* logits, void* stream);
+
+/*
+ * moe_route_bwd:  gradient with respect to the logits for given dgate[t, i] = dL/d topk_w[t, i],
+ * the chosen experts held fixed.  With p = Softmax(logits), s_i = p[topk_idx[t, i]], S = sum_i s_i:
+ *   renormalize != 0:  dL/ds_i = (dgate_i - sum_j dgate_j * s_j / S) / S ;  otherwise dL/ds_i = dgate_i
+ *   dlogits[t, e] = p_e * (dL/dp_e - sum_i dL/ds_i * s_i),  dL/dp_e = dL/ds_i if e = topk_idx[t, i], else 0.
+ *   logits [T, E] fp32, topk_idx [T, k] int32 (distinct per token), dgate [T, k] fp32,
+ *   dlogits [T, E] fp32 out.
+ */
+int moe_route_bwd(const float* logits, const int32_t* topk_idx, const float* dgate, int T, int E, int k,
+                  int renormalize, float* dlogits, void* stream);
+
+/*
+ * moe_router_bwd:  derivative of the Linear layer.
+ *   dWr[e, j] = sum_t dlogits[t, e] * x[t, j]                  fp32 [E, d] out (overwritten)
+ *   dx[t, j] += sum_e dlogits[t, e] * Wr[e, j]                 bf16 [T, d] IN-OUT: the router's share
+ *     is ADDED to what dx holds (the expert path's gradient from moe_permute_bwd), in fp32, and the
+ *     sum is rounded once.  This is the one argument of the library that is accumulated into.
+ *   ws at least moe_router_bwd_workspace_bytes(T, d, E): partial sums of dWr over chunks of 128
+ *   tokens, reduced in a fixed order (no atomics: results are reproducible).
+ */
+size_t moe_router_bwd_workspace_bytes(int T, int d, int E);
+int moe_router_bwd(const moe_bf16* x, const float* Wr, const float* dlogits, int T, int d, int E,
+                   moe_bf16* dx, float* dWr, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Per-kernel timing for benchmarks (not part of the paper's method).  While
  * enabled, every kernel the library launches is bracketed by two HIP events
  * recorded on the launch stream.  moe_prof_read synchronises on the recorded

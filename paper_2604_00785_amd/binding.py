@@ -20,6 +20,7 @@ EXPORTS = [
     "moe_version", "moe_permute_workspace_bytes", "moe_grouped_gemm_bwd_workspace_bytes", "moe_workspace_bytes",
     "moe_route", "moe_permute", "moe_permute_bwd", "moe_grouped_gemm_fwd", "moe_grouped_gemm_bwd",
     "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_prof_enable", "moe_prof_count", "moe_prof_read",
+    "moe_router_fwd", "moe_route_bwd", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
 ]
 
 _ERR = {-1: "MOE_ERR_INVALID (bad pointer, alignment or size)", -2: "MOE_ERR_WORKSPACE (workspace too small)",
@@ -52,6 +53,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.moe_grouped_gemm_bwd_workspace_bytes.argtypes = [c_int] * 2
     lib.moe_workspace_bytes.restype = c_sz
     lib.moe_workspace_bytes.argtypes = [c_int] * 5
+    lib.moe_router_bwd_workspace_bytes.restype = c_sz
+    lib.moe_router_bwd_workspace_bytes.argtypes = [c_int] * 3
     sigs = {
         "moe_route": [vp, c_int, c_int, c_int, c_int, vp, vp, vp],
         "moe_permute": [vp, vp, c_int, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, c_sz, vp],
@@ -60,6 +63,9 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "moe_grouped_gemm_bwd": [vp] * 9 + [c_int] * 4 + [vp] * 4 + [vp, c_sz, vp],
         "moe_unpermute_combine": [vp, vp, vp, c_int, c_int, c_int, vp, vp],
         "moe_unpermute_combine_bwd": [vp, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp],
+        "moe_router_fwd": [vp, vp, c_int, c_int, c_int, vp, vp],
+        "moe_route_bwd": [vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp],
+        "moe_router_bwd": [vp, vp, vp, c_int, c_int, c_int, vp, vp, vp, c_sz, vp],
         "moe_prof_enable": [c_int],
         "moe_prof_count": [],
         "moe_prof_read": [c_int, ctypes.c_char_p, c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(c_int)],
@@ -194,6 +200,43 @@ def moe_unpermute_combine_bwd(dout, yp, slot_row, topk_w, dyp, dgate) -> None:
     _want(dgate, torch.float32, (T, k), "dgate")
     _check(load().moe_unpermute_combine_bwd(_p(dout), _p(yp), _p(slot_row), _p(topk_w), T, k, d, _p(dyp), _p(dgate),
                                             _stream()), "moe_unpermute_combine_bwd")
+
+
+def moe_router_bwd_workspace_bytes(T: int, d: int, E: int) -> int:
+    return int(load().moe_router_bwd_workspace_bytes(T, d, E))
+
+
+def moe_router_fwd(x, Wr, logits) -> None:
+    T, d = x.shape
+    E = Wr.shape[0]
+    _want(x, BF16, name="x")
+    _want(Wr, torch.float32, (E, d), "Wr")
+    _want(logits, torch.float32, (T, E), "logits")
+    _check(load().moe_router_fwd(_p(x), _p(Wr), T, d, E, _p(logits), _stream()), "moe_router_fwd")
+
+
+def moe_route_bwd(logits, topk_idx, dgate, renormalize: int, dlogits) -> None:
+    T, E = logits.shape
+    k = topk_idx.shape[1]
+    _want(logits, torch.float32, name="logits")
+    _want(topk_idx, torch.int32, (T, k), "topk_idx")
+    _want(dgate, torch.float32, (T, k), "dgate")
+    _want(dlogits, torch.float32, (T, E), "dlogits")
+    _check(load().moe_route_bwd(_p(logits), _p(topk_idx), _p(dgate), T, E, k, renormalize, _p(dlogits), _stream()),
+           "moe_route_bwd")
+
+
+def moe_router_bwd(x, Wr, dlogits, dx, dWr, ws) -> None:
+    """dWr is overwritten; the router's share of the input gradient is ADDED to dx."""
+    T, d = x.shape
+    E = Wr.shape[0]
+    _want(x, BF16, name="x")
+    _want(Wr, torch.float32, (E, d), "Wr")
+    _want(dlogits, torch.float32, (T, E), "dlogits")
+    _want(dx, BF16, (T, d), "dx")
+    _want(dWr, torch.float32, (E, d), "dWr")
+    _check(load().moe_router_bwd(_p(x), _p(Wr), _p(dlogits), T, d, E, _p(dx), _p(dWr), _p(ws),
+                                 ws.numel() * ws.element_size(), _stream()), "moe_router_bwd")
 
 
 def moe_prof_enable(on: bool) -> None:

@@ -1,0 +1,401 @@
+// The router of Stage 1 of Algorithm 1 (logits = Router(input), a Linear layer without bias) and
+// the derivative of Stage 1: through the renormalisation, TopK and Softmax back to the logits,
+// and through the Linear layer to its weight and to the layer input.  The paper leaves the
+// derivative to autograd; the formulas are the chain rule written out (see moe_route_bwd).
+//
+// moe_router_fwd   logits[T,E] = x[T,d] . Wr[E,d]^T with fp32 router weights and bf16 activations.
+//   A wave owns a 32-token x 32-expert block and feeds v_mfma_f32_32x32x16_bf16 straight from global
+//   memory (both operands are contiguous along d, the reduction).  The fp32 weights are split in
+//   registers into three bf16 terms (w = hi + mid + lo exactly to 24 bits); x * hi, x * mid and
+//   x * lo are exact in fp32, so the result has fp32 accuracy at bf16 matrix-core speed.
+// moe_route_bwd    one group of G lanes per token, like moe_route: recomputes the softmax, forms the
+//   gradient of the k chosen probabilities, scatters it by expert through LDS.
+// moe_router_bwd   dx[T,d] += dlogits[T,E] . Wr[E,d]   (vector ALU, fp32; a workgroup owns 8 tokens)
+//                  dWr[E,d] = dlogits^T . x            (vector ALU, fp32; token chunks -> partial
+//                  sums in the workspace -> one deterministic reduction; no atomics)
+#include "common.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// ------------------------------------------------------------------ router forward
+// three bf16 terms of eight fp32 values; each residual is exact in fp32
+__device__ __forceinline__ void split3(const float (&w)[8], bf16x8_t& hi, bf16x8_t& mid, bf16x8_t& lo) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const __bf16 h = static_cast<__bf16>(w[i]);
+    const float r1 = w[i] - static_cast<float>(h);
+    const __bf16 m = static_cast<__bf16>(r1);
+    const float r2 = r1 - static_cast<float>(m);
+    hi[i] = h;
+    mid[i] = m;
+    lo[i] = static_cast<__bf16>(r2);
+  }
+}
+
+constexpr int RF_WAVES = 4;   // waves per workgroup: they share one 32x32 block and split the reduction
+
+__global__ __launch_bounds__(64 * RF_WAVES) void router_fwd_kernel(const uint16_t* __restrict__ x,
+                                                                   const float* __restrict__ Wr, int T, int d,
+                                                                   int E, float* __restrict__ logits) {
+  __shared__ float s_part[RF_WAVES - 1][16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int e_blocks = (E + 31) / 32;
+  const int t0 = (blockIdx.x / e_blocks) * 32, e0 = (blockIdx.x % e_blocks) * 32;
+  const int lrow = lane & 31, lgrp = lane >> 5;
+  int tr = t0 + lrow;  if (tr > T - 1) tr = T - 1;     // rows past the end shadow the last one
+  int er = e0 + lrow;  if (er > E - 1) er = E - 1;
+  const uint16_t* xa = x + static_cast<size_t>(tr) * d + lgrp * 8;
+  const float* wb = Wr + static_cast<size_t>(er) * d + lgrp * 8;
+  // three independent accumulation chains (one per weight term), so that consecutive MFMAs do not
+  // wait for each other; wave w takes the 16-wide reduction steps w, w+4, w+8, ...
+  f32x16_t acc_hi, acc_mid, acc_lo;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { acc_hi[r] = 0.f; acc_mid[r] = 0.f; acc_lo[r] = 0.f; }
+  const int nsteps = d / 16;
+  int st = wave;
+  for (; st + RF_WAVES < nsteps; st += 2 * RF_WAVES) {   // two steps per trip: four loads in flight per operand
+    const int k0 = st * 16, k1 = (st + RF_WAVES) * 16;
+    const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(xa + k0);
+    const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(xa + k1);
+    const f32x4 w00 = *reinterpret_cast<const f32x4*>(wb + k0), w01 = *reinterpret_cast<const f32x4*>(wb + k0 + 4);
+    const f32x4 w10 = *reinterpret_cast<const f32x4*>(wb + k1), w11 = *reinterpret_cast<const f32x4*>(wb + k1 + 4);
+    const float wa[8] = {w00[0], w00[1], w00[2], w00[3], w01[0], w01[1], w01[2], w01[3]};
+    const float wc[8] = {w10[0], w10[1], w10[2], w10[3], w11[0], w11[1], w11[2], w11[3]};
+    bf16x8_t hi, mid, lo;
+    split3(wa, hi, mid, lo);
+    // operand order (weights, activations) gives a lane 4 consecutive experts of one token
+    acc_lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, a0, acc_lo, 0, 0, 0);
+    acc_mid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mid, a0, acc_mid, 0, 0, 0);
+    acc_hi = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, a0, acc_hi, 0, 0, 0);
+    split3(wc, hi, mid, lo);
+    acc_lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, a1, acc_lo, 0, 0, 0);
+    acc_mid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mid, a1, acc_mid, 0, 0, 0);
+    acc_hi = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, a1, acc_hi, 0, 0, 0);
+  }
+  for (; st < nsteps; st += RF_WAVES) {
+    const int k0 = st * 16;
+    const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(xa + k0);
+    const f32x4 w00 = *reinterpret_cast<const f32x4*>(wb + k0), w01 = *reinterpret_cast<const f32x4*>(wb + k0 + 4);
+    const float wa[8] = {w00[0], w00[1], w00[2], w00[3], w01[0], w01[1], w01[2], w01[3]};
+    bf16x8_t hi, mid, lo;
+    split3(wa, hi, mid, lo);
+    acc_lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, a0, acc_lo, 0, 0, 0);
+    acc_mid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mid, a0, acc_mid, 0, 0, 0);
+    acc_hi = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, a0, acc_hi, 0, 0, 0);
+  }
+  f32x16_t acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = (acc_lo[r] + acc_mid[r]) + acc_hi[r];   // smallest terms first
+  // the four partial sums are added in wave order
+  if (wave > 0) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_part[wave - 1][r][lane] = acc[r];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+#pragma unroll
+  for (int w = 0; w < RF_WAVES - 1; ++w)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] += s_part[w][r][lane];
+  // acc[4q+c] = (token t0 + lrow, expert e0 + q*8 + lgrp*4 + c)
+  const int t = t0 + lrow;
+  if (t < T) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int e = e0 + q * 8 + lgrp * 4;
+      float* o = logits + static_cast<size_t>(t) * E + e;
+      if (e + 3 < E && (E & 3) == 0) {
+        *reinterpret_cast<f32x4*>(o) = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (e + c < E) o[c] = acc[4 * q + c];
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ softmax / top-k backward
+template <int G, int VPL>
+__global__ __launch_bounds__(256) void route_bwd_kernel(const float* __restrict__ logits,
+                                                        const int32_t* __restrict__ topk_idx,
+                                                        const float* __restrict__ dgate, int T, int E, int k,
+                                                        int renormalize, float* __restrict__ dlogits) {
+  constexpr int GROUPS = 256 / G;
+  extern __shared__ float s_dp[];   // [GROUPS][E]: gradient of the probabilities, by expert
+  const int tid = threadIdx.x;
+  const int gl = tid % G, grp = tid / G;
+  const int t = blockIdx.x * GROUPS + grp;
+  const bool live = t < T;
+  const int tt = live ? t : T - 1;
+  float* dp = s_dp + grp * E;
+
+  float val[VPL];
+  float m = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    const int e = gl + j * G;
+    val[j] = e < E ? logits[static_cast<size_t>(tt) * E + e] : -INFINITY;
+    m = fmaxf(m, val[j]);
+    if (e < E) dp[e] = 0.f;
+  }
+#pragma unroll
+  for (int s = 1; s < G; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, MOE_WAVE));
+  float p[VPL], sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    p[j] = gl + j * G < E ? expf(val[j] - m) : 0.f;
+    sum += p[j];
+  }
+#pragma unroll
+  for (int s = 1; s < G; s <<= 1) sum += __shfl_xor(sum, s, MOE_WAVE);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) p[j] *= inv;
+
+  // the chosen probabilities s_i and the gradient of the gates, slot i on lane i % G
+  float S = 0.f, dot = 0.f;
+  for (int i = gl; i < k; i += G) {
+    const int e = topk_idx[static_cast<size_t>(tt) * k + i];
+    const float s_i = expf(logits[static_cast<size_t>(tt) * E + e] - m) * inv;
+    S += s_i;
+    dot += dgate[static_cast<size_t>(tt) * k + i] * s_i;
+  }
+#pragma unroll
+  for (int s = 1; s < G; s <<= 1) { S += __shfl_xor(S, s, MOE_WAVE); dot += __shfl_xor(dot, s, MOE_WAVE); }
+  // renormalised: w_i = s_i / S, dL/ds_i = (dgate_i - sum_j dgate_j w_j) / S ; otherwise dL/ds_i = dgate_i
+  const float invS = renormalize ? 1.0f / S : 1.0f;
+  const float shift = renormalize ? dot * invS : 0.f;
+  __syncthreads();                       // dp is zeroed
+  float c = 0.f;                         // sum_i dL/ds_i * s_i
+  for (int i = gl; i < k; i += G) {
+    const int e = topk_idx[static_cast<size_t>(tt) * k + i];
+    const float s_i = expf(logits[static_cast<size_t>(tt) * E + e] - m) * inv;
+    const float ds = (dgate[static_cast<size_t>(tt) * k + i] - shift) * invS;
+    dp[e] = ds;                          // a token's experts are distinct
+    c += ds * s_i;
+  }
+#pragma unroll
+  for (int s = 1; s < G; s <<= 1) c += __shfl_xor(c, s, MOE_WAVE);
+  __syncthreads();
+  if (live) {
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) {
+      const int e = gl + j * G;
+      if (e < E) dlogits[static_cast<size_t>(t) * E + e] = p[j] * (dp[e] - c);
+    }
+  }
+}
+
+template <int G, int VPL>
+void launch_route_bwd(const float* logits, const int32_t* idx, const float* dgate, int T, int E, int k, int renorm,
+                      float* dlogits, hipStream_t s) {
+  const int groups = 256 / G;
+  dim3 grid((T + groups - 1) / groups), block(256);
+  MOE_LAUNCH("route_bwd", (route_bwd_kernel<G, VPL>), grid, block, groups * E * sizeof(float), s, logits, idx, dgate,
+             T, E, k, renorm, dlogits);
+}
+
+// ------------------------------------------------------------------ router backward
+constexpr int DX_TOKENS = 8;   // tokens per workgroup; a thread owns 8 consecutive columns of each
+
+__global__ __launch_bounds__(256) void router_bwd_dx_kernel(const float* __restrict__ dlogits,
+                                                            const float* __restrict__ Wr, int T, int d, int E,
+                                                            uint16_t* __restrict__ dx) {
+  extern __shared__ float s_dl[];   // [DX_TOKENS][E]
+  const int t0 = blockIdx.x * DX_TOKENS;
+  for (int i = threadIdx.x; i < DX_TOKENS * E; i += 256) {
+    const int t = t0 + i / E;
+    s_dl[i] = t < T ? dlogits[static_cast<size_t>(t) * E + i % E] : 0.f;
+  }
+  __syncthreads();
+  for (int c0 = threadIdx.x * 8; c0 < d; c0 += 256 * 8) {
+    float acc[DX_TOKENS][8];
+#pragma unroll
+    for (int r = 0; r < DX_TOKENS; ++r)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[r][j] = 0.f;
+    for (int eb = 0; eb < E; eb += 4) {   // four weight rows in flight
+      f32x4 w0[4], w1[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = eb + u < E ? eb + u : E - 1;
+        w0[u] = *reinterpret_cast<const f32x4*>(Wr + static_cast<size_t>(e) * d + c0);
+        w1[u] = *reinterpret_cast<const f32x4*>(Wr + static_cast<size_t>(e) * d + c0 + 4);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (eb + u < E) {
+#pragma unroll
+          for (int r = 0; r < DX_TOKENS; ++r) {
+            const float g = s_dl[r * E + eb + u];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { acc[r][j] += g * w0[u][j]; acc[r][4 + j] += g * w1[u][j]; }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < DX_TOKENS; ++r) {
+      const int t = t0 + r;
+      if (t < T) {
+        u32x4* p = reinterpret_cast<u32x4*>(dx + static_cast<size_t>(t) * d + c0);
+        const u32x4 old = *p;
+        u32x4 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          o[j] = pack_bf16(bf16lo(old[j]) + acc[r][2 * j], bf16hi(old[j]) + acc[r][2 * j + 1]);
+        *p = o;
+      }
+    }
+  }
+}
+
+constexpr int DW_CHUNK = 128;   // tokens per partial sum
+constexpr int DW_COLS = 512;    // columns per workgroup: 64 threads x 8 columns, 4 expert groups
+
+__global__ __launch_bounds__(256) void router_bwd_dw_partial_kernel(const float* __restrict__ dlogits,
+                                                                    const uint16_t* __restrict__ x, int T, int d,
+                                                                    int E, int e_per, float* __restrict__ part) {
+  // grid: (column blocks, token chunks, expert blocks of 4 * e_per).  Thread: expert group tid / 64
+  // (e_per experts, at most 16), columns (tid % 64) * 8 .. +8 of the block.
+  extern __shared__ float s_dl[];   // [32 tokens][4 * e_per]
+  const int cb = blockIdx.x, chunk = blockIdx.y, eb = blockIdx.z;
+  const int eg = threadIdx.x >> 6, cl = threadIdx.x & 63;
+  const int c0 = cb * DW_COLS + cl * 8;
+  const int ew = 4 * e_per, e_base = eb * ew;
+  const int t_lo = chunk * DW_CHUNK, t_hi = min(T, t_lo + DW_CHUNK);
+  float acc[16][8];
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[r][j] = 0.f;
+  for (int tb = t_lo; tb < t_hi; tb += 32) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < 32 * ew; i += 256) {
+      const int t = tb + i / ew, e = e_base + i % ew;
+      s_dl[i] = (t < t_hi && e < E) ? dlogits[static_cast<size_t>(t) * E + e] : 0.f;
+    }
+    __syncthreads();
+    const int nt = min(32, t_hi - tb);
+    if (c0 < d) {
+      for (int rb = 0; rb < nt; rb += 4) {   // four token rows in flight
+        u32x4 xv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int r = rb + u < nt ? rb + u : nt - 1;
+          xv[u] = *reinterpret_cast<const u32x4*>(x + static_cast<size_t>(tb + r) * d + c0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (rb + u < nt) {
+            const float xf[8] = {bf16lo(xv[u][0]), bf16hi(xv[u][0]), bf16lo(xv[u][1]), bf16hi(xv[u][1]),
+                                 bf16lo(xv[u][2]), bf16hi(xv[u][2]), bf16lo(xv[u][3]), bf16hi(xv[u][3])};
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+              if (q < e_per) {
+                const float g = s_dl[(rb + u) * ew + eg * e_per + q];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[q][j] += g * xf[j];
+              }
+            }
+          }
+        }
+      }
+    }
+  }
+  if (c0 < d) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int e = e_base + eg * e_per + q;
+      if (q < e_per && e < E) {
+        float* o = part + (static_cast<size_t>(chunk) * E + e) * d + c0;
+        *reinterpret_cast<f32x4*>(o) = f32x4{acc[q][0], acc[q][1], acc[q][2], acc[q][3]};
+        *reinterpret_cast<f32x4*>(o + 4) = f32x4{acc[q][4], acc[q][5], acc[q][6], acc[q][7]};
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void router_bwd_dw_reduce_kernel(const float* __restrict__ part, int chunks,
+                                                                   size_t n, float* __restrict__ dWr) {
+  const size_t i = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
+  if (i >= n) return;
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+  for (int c = 0; c < chunks; ++c) s += *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(c) * n + i);
+  *reinterpret_cast<f32x4*>(dWr + i) = s;
+}
+
+bool bad_router_dims(int T, int d, int E) { return T <= 0 || d <= 0 || E <= 0 || E > MOE_MAX_EXPERTS || d % 16 != 0; }
+
+}  // namespace
+
+extern "C" int moe_router_fwd(const moe_bf16* x, const float* Wr, int T, int d, int E, float* logits, void* stream) {
+  if (!x || !Wr || !logits) return MOE_ERR_INVALID;
+  if (bad_router_dims(T, d, E)) return MOE_ERR_INVALID;
+  if (!moe_aligned16(x) || !moe_aligned16(Wr) || !moe_aligned16(logits)) return MOE_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const long long blocks = static_cast<long long>((T + 31) / 32) * ((E + 31) / 32);
+  dim3 grid(static_cast<unsigned>(blocks)), block(64 * RF_WAVES);
+  MOE_LAUNCH("router_fwd", router_fwd_kernel, grid, block, 0, s, x, Wr, T, d, E, logits);
+  return moe_check_launch();
+}
+
+extern "C" int moe_route_bwd(const float* logits, const int32_t* topk_idx, const float* dgate, int T, int E, int k,
+                             int renormalize, float* dlogits, void* stream) {
+  if (!logits || !topk_idx || !dgate || !dlogits) return MOE_ERR_INVALID;
+  if (T <= 0 || E <= 0 || k <= 0 || k > E || E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
+  if (!moe_aligned16(logits) || !moe_aligned16(topk_idx) || !moe_aligned16(dgate) || !moe_aligned16(dlogits))
+    return MOE_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int r = renormalize != 0;
+  if (E <= 8) launch_route_bwd<8, 1>(logits, topk_idx, dgate, T, E, k, r, dlogits, s);
+  else if (E <= 16) launch_route_bwd<16, 1>(logits, topk_idx, dgate, T, E, k, r, dlogits, s);
+  else if (E <= 32) launch_route_bwd<32, 1>(logits, topk_idx, dgate, T, E, k, r, dlogits, s);
+  else if (E <= 64) launch_route_bwd<64, 1>(logits, topk_idx, dgate, T, E, k, r, dlogits, s);
+  else if (E <= 128) launch_route_bwd<64, 2>(logits, topk_idx, dgate, T, E, k, r, dlogits, s);
+  else if (E <= 256) launch_route_bwd<64, 4>(logits, topk_idx, dgate, T, E, k, r, dlogits, s);
+  else launch_route_bwd<64, 8>(logits, topk_idx, dgate, T, E, k, r, dlogits, s);
+  return moe_check_launch();
+}
+
+extern "C" size_t moe_router_bwd_workspace_bytes(int T, int d, int E) {
+  if (T <= 0 || d <= 0 || E <= 0) return 0;
+  const size_t chunks = (static_cast<size_t>(T) + DW_CHUNK - 1) / DW_CHUNK;
+  return chunks * E * d * sizeof(float);
+}
+
+extern "C" int moe_router_bwd(const moe_bf16* x, const float* Wr, const float* dlogits, int T, int d, int E,
+                              moe_bf16* dx, float* dWr, void* ws, size_t ws_bytes, void* stream) {
+  if (!x || !Wr || !dlogits || !dx || !dWr || !ws) return MOE_ERR_INVALID;
+  if (bad_router_dims(T, d, E)) return MOE_ERR_INVALID;
+  const void* ptrs[] = {x, Wr, dlogits, dx, dWr, ws};
+  for (const void* p : ptrs) if (!moe_aligned16(p)) return MOE_ERR_INVALID;
+  if (ws_bytes < moe_router_bwd_workspace_bytes(T, d, E)) return MOE_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  {
+    dim3 grid((T + DX_TOKENS - 1) / DX_TOKENS), block(256);
+    MOE_LAUNCH("router_bwd_dx", router_bwd_dx_kernel, grid, block, DX_TOKENS * E * sizeof(float), s, dlogits, Wr, T, d,
+               E, dx);
+  }
+  const int chunks = (T + DW_CHUNK - 1) / DW_CHUNK;
+  {
+    // a thread keeps e_per <= 16 experts; a workgroup covers 4 * e_per of them
+    int e_per = (E + 3) / 4;
+    if (e_per > 16) e_per = 16;
+    const int ew = 4 * e_per;
+    dim3 grid((d + DW_COLS - 1) / DW_COLS, chunks, (E + ew - 1) / ew), block(256);
+    MOE_LAUNCH("router_bwd_dw_partial", router_bwd_dw_partial_kernel, grid, block, 32 * ew * sizeof(float), s, dlogits,
+               x, T, d, E, e_per, static_cast<float*>(ws));
+  }
+  {
+    const size_t n = static_cast<size_t>(E) * d;
+    dim3 grid(static_cast<unsigned>((n / 4 + 255) / 256)), block(256);
+    MOE_LAUNCH("router_bwd_dw_reduce", router_bwd_dw_reduce_kernel, grid, block, 0, s, static_cast<const float*>(ws),
+               chunks, n, dWr);
+  }
+  return moe_check_launch();
+}

@@ -125,6 +125,7 @@ def make_inputs(cfg: MoEConfig, with_weights: bool = True) -> Dict[str, np.ndarr
       dout   uint16 [T, d]      upstream gradient, N(0,1) as bf16 bits
       logits float32 [T, E]     router logits (input of the routing step)
       Wg,Wu  uint16 [n_local, f, d], Wd uint16 [n_local, d, f]   N(0,0.02) as bf16 bits
+      Wr     float32 [E, d]     the router weight the logits were made with (not for "iid")
     Router logits are ``x @ Wr.T`` with ``Wr ~ N(0,0.02)`` fp32 ("router"),
     the same plus a Zipf bias ("zipf"), or i.i.d. N(0,1) ("iid": every
     k-subset of experts is equally likely, as for already-dispatched tokens).
@@ -142,6 +143,7 @@ def make_inputs(cfg: MoEConfig, with_weights: bool = True) -> Dict[str, np.ndarr
         if cfg.logits == "zipf":
             logits = logits + zipf_bias(E, float(logits.std()))[None, :]
         out["logits"] = np.ascontiguousarray(logits, dtype=np.float32)
+        out["Wr"] = Wr
     if with_weights:
         out["Wg"] = _normal_bf16(rng, (nl, f, d), 0.02)
         out["Wu"] = _normal_bf16(rng, (nl, f, d), 0.02)

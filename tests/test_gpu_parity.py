@@ -207,6 +207,95 @@ def test_layer_ragged_shapes(T, d, E, k, f, eb, ec, renorm):
     H.compare_layer(res, ref, ec)
 
 
+# ----------------------------------------------------------------------------- router and Stage-1 backward
+@pytest.mark.parametrize("T,d,E", [(256, 128, 8), (1000, 2048, 64), (77, 64, 100), (33, 48, 5), (4096, 256, 300)])
+def test_router_fwd(T, d, E):
+    print(f"router_fwd T={T} d={d} E={E}", flush=True)
+    rng = np.random.default_rng(T + d + E)
+    xb = W.f32_to_bf16_bits(rng.standard_normal((T, d)).astype(np.float32))
+    Wr = (rng.standard_normal((E, d)) * 0.05).astype(np.float32)
+    logits = torch.full((T, E), float("nan"), dtype=torch.float32, device=DEV)
+    B.moe_router_fwd(H.bf16_to_dev(xb), torch.from_numpy(Wr).to(DEV), logits)
+    torch.cuda.synchronize()
+    ref = O.router_logits(O.decode_bf16(xb), Wr)
+    got = logits.cpu().numpy().astype(np.float64)
+    # exact products, fp32 accumulation over d terms: error ~ sqrt(d) * 2^-24 * |terms|
+    scale = np.abs(ref).max()
+    assert np.abs(got - ref).max() <= 2e-6 * scale * max(1.0, np.sqrt(d) / 8)
+
+
+@pytest.mark.parametrize("T,E,k", [(256, 8, 2), (1000, 64, 8), (130, 100, 7), (64, 300, 70), (5, 1, 1), (33, 512, 9)])
+@pytest.mark.parametrize("renorm", [0, 1])
+def test_route_bwd(T, E, k, renorm):
+    print(f"route_bwd T={T} E={E} k={k} renorm={renorm}", flush=True)
+    rng = np.random.default_rng(T * 7 + E + k)
+    logits = (rng.standard_normal((T, E)) * 2).astype(np.float32)
+    idx, _ = O.route(logits, k, renorm)
+    dgate = rng.standard_normal((T, k)).astype(np.float32)
+    dl = torch.full((T, E), float("nan"), dtype=torch.float32, device=DEV)
+    B.moe_route_bwd(torch.from_numpy(logits).to(DEV), dev_i32(idx), torch.from_numpy(dgate).to(DEV), renorm, dl)
+    torch.cuda.synchronize()
+    ref = O.route_bwd(logits, idx, dgate, renorm)
+    got = dl.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert np.abs(got - ref).max() <= 2e-5 * max(np.abs(ref).max(), 1e-30)
+
+
+@pytest.mark.parametrize("T,d,E", [(256, 128, 8), (1000, 2048, 64), (300, 64, 100), (33, 48, 5), (2100, 256, 130)])
+def test_router_bwd(T, d, E):
+    print(f"router_bwd T={T} d={d} E={E}", flush=True)
+    rng = np.random.default_rng(T + 3 * d + E)
+    xb = W.f32_to_bf16_bits(rng.standard_normal((T, d)).astype(np.float32))
+    dx0b = W.f32_to_bf16_bits(rng.standard_normal((T, d)).astype(np.float32))
+    Wr = (rng.standard_normal((E, d)) * 0.05).astype(np.float32)
+    dl = (rng.standard_normal((T, E)) * 0.1).astype(np.float32)
+    dx = H.bf16_to_dev(dx0b).clone()
+    dWr = torch.full((E, d), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.zeros(B.moe_router_bwd_workspace_bytes(T, d, E), dtype=torch.uint8, device=DEV)
+    B.moe_router_bwd(H.bf16_to_dev(xb), torch.from_numpy(Wr).to(DEV), torch.from_numpy(dl).to(DEV), dx, dWr, ws)
+    torch.cuda.synchronize()
+    rdWr, rdx = O.router_bwd(O.decode_bf16(xb), Wr, dl.astype(np.float64))
+    got = dWr.cpu().numpy().astype(np.float64)
+    assert np.abs(got - rdWr).max() <= 1e-5 * np.abs(rdWr).max()
+    H.assert_close(H.bf16_from_dev(dx), O.decode_bf16(dx0b) + rdx, "dx", 1e-2)
+    # the same call again gives the same dWr bits (fixed reduction order, no atomics)
+    dWr2 = torch.zeros_like(dWr)
+    B.moe_router_bwd(H.bf16_to_dev(xb), torch.from_numpy(Wr).to(DEV), torch.from_numpy(dl).to(DEV), dx, dWr2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dWr, dWr2)
+
+
+def test_drop_in_block_router_to_gradients():
+    """Router -> route on the device's own logits -> ... -> dgate -> dlogits -> dWr, dx: the chain a
+    training step runs, against the oracle fed with the same (device) logits."""
+    cfg = W.MoEConfig("custom", T=512, d=128, E=16, k=4, f=64, seed=5)
+    inp = W.make_inputs(cfg)
+    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f)
+    x, dout = H.bf16_to_dev(inp["x"]), H.bf16_to_dev(inp["dout"])
+    Wg, Wu, Wd = (H.bf16_to_dev(inp[n]) for n in ("Wg", "Wu", "Wd"))
+    Wr = torch.from_numpy(inp["Wr"]).to(DEV)
+    logits = torch.zeros(cfg.T, cfg.E, dtype=torch.float32, device=DEV)
+    B.moe_router_fwd(x, Wr, logits)
+    buf.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
+    dl = torch.zeros_like(logits)
+    dWr = torch.zeros_like(Wr)
+    ws = torch.zeros(B.moe_router_bwd_workspace_bytes(cfg.T, cfg.d, cfg.E), dtype=torch.uint8, device=DEV)
+    dx_expert = H.bf16_from_dev(buf.dx)
+    B.moe_route_bwd(logits, buf.topk_idx, buf.dgate, cfg.renormalize, dl)
+    B.moe_router_bwd(x, Wr, dl, buf.dx, dWr, ws)
+    torch.cuda.synchronize()
+    inp2 = dict(inp)
+    inp2["logits"] = logits.cpu().numpy()
+    ref = O.layer_fwd_bwd(inp2, cfg.k, 0, cfg.E, cfg.renormalize)
+    assert np.array_equal(buf.topk_idx.cpu().numpy(), ref["topk_idx"])
+    rdl = O.route_bwd(inp2["logits"], ref["topk_idx"], ref["dgate"], cfg.renormalize)
+    rdWr, rdx = O.router_bwd(O.decode_bf16(inp["x"]), inp["Wr"], rdl)
+    H.assert_close(dl.cpu().numpy().astype(np.float64), rdl, "dlogits")
+    H.assert_close(dWr.cpu().numpy().astype(np.float64), rdWr, "dWr")
+    H.assert_close(H.bf16_from_dev(buf.dx), ref["dx"] + rdx, "dx (expert path + router path)")
+    assert np.abs(H.bf16_from_dev(buf.dx) - dx_expert).max() > 0
+
+
 def test_argument_checks():
     t = torch.zeros(64, 64, dtype=torch.float32, device=DEV)
     idx = torch.zeros(64, 2, dtype=torch.int32, device=DEV)
