@@ -191,7 +191,7 @@ int moe_route_bwd(const float* logits, const int32_t* topk_idx, const float* dga
  *   dx[t, j] += sum_e dlogits[t, e] * Wr[e, j]                 bf16 [T, d] IN-OUT: the router's share
  *     is ADDED to what dx holds (the expert path's gradient from moe_permute_bwd), in fp32, and the
  *     sum is rounded once.  This is the one argument of the library that is accumulated into.
- *   ws at least moe_router_bwd_workspace_bytes(T, d, E): partial sums of dWr over chunks of 128
+ *   ws at least moe_router_bwd_workspace_bytes(T, d, E): partial sums of dWr over chunks of 256
  *   tokens, reduced in a fixed order (no atomics: results are reproducible).
  */
 size_t moe_router_bwd_workspace_bytes(int T, int d, int E);

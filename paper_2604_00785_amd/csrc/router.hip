@@ -11,8 +11,9 @@
 // moe_route_bwd    one group of G lanes per token, like moe_route: recomputes the softmax, forms the
 //   gradient of the k chosen probabilities, scatters it by expert through LDS.
 // moe_router_bwd   dx[T,d] += dlogits[T,E] . Wr[E,d]   (vector ALU, fp32; a workgroup owns 8 tokens)
-//                  dWr[E,d] = dlogits^T . x            (vector ALU, fp32; token chunks -> partial
-//                  sums in the workspace -> one deterministic reduction; no atomics)
+//                  dWr[E,d] = dlogits^T . x            (matrix cores, dlogits split into three bf16
+//                  terms; token chunks -> partial sums in the workspace -> one deterministic
+//                  reduction; no atomics)
 #include "common.h"
 
 namespace {
@@ -254,69 +255,125 @@ __global__ __launch_bounds__(256) void router_bwd_dx_kernel(const float* __restr
   }
 }
 
-constexpr int DW_CHUNK = 128;   // tokens per partial sum
-constexpr int DW_COLS = 512;    // columns per workgroup: 64 threads x 8 columns, 4 expert groups
+// dWr = dlogits^T . x on the matrix cores.  Both operands have the reduction (the tokens) as their
+// slow dimension, so both pass through LDS: a stage of 32 tokens of x is kept as it lies in memory
+// and read with the transposing LDS load; the same tokens of dlogits are split into three bf16 terms
+// (as the weights are in the forward kernel) and stored expert-major, so that a lane reads the eight
+// consecutive tokens of its expert with one 16-byte load per term.  The next stage is fetched into
+// registers while the current one is multiplied.
+constexpr int DW_CHUNK = 256;   // tokens per partial sum
+constexpr int DW_COLS = 128;    // columns of x per workgroup: 4 waves x 32
+constexpr int DW_EXP = 64;      // experts per workgroup: 2 MFMA row blocks
+constexpr int DW_TOK = 32;      // tokens per stage
+constexpr int DW_XROW = DW_COLS * 2;        // bytes of a token row of the x stage
+constexpr int DW_GROW = DW_TOK * 2 + 16;    // bytes of an expert row of a dlogits term (padded)
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// 16-byte pieces of a token row are XOR-swizzled with 4 * (row & 3): the four rows that 16 lanes of a
+// transposing read touch then fall into different bank groups
+__device__ __forceinline__ int dw_piece(int row, int piece) { return piece ^ ((row & 3) << 2); }
 
 __global__ __launch_bounds__(256) void router_bwd_dw_partial_kernel(const float* __restrict__ dlogits,
                                                                     const uint16_t* __restrict__ x, int T, int d,
-                                                                    int E, int e_per, float* __restrict__ part) {
-  // grid: (column blocks, token chunks, expert blocks of 4 * e_per).  Thread: expert group tid / 64
-  // (e_per experts, at most 16), columns (tid % 64) * 8 .. +8 of the block.
-  extern __shared__ float s_dl[];   // [32 tokens][4 * e_per]
-  const int cb = blockIdx.x, chunk = blockIdx.y, eb = blockIdx.z;
-  const int eg = threadIdx.x >> 6, cl = threadIdx.x & 63;
-  const int c0 = cb * DW_COLS + cl * 8;
-  const int ew = 4 * e_per, e_base = eb * ew;
+                                                                    int E, float* __restrict__ part) {
+  // grid: (column blocks of 128, token chunks of 256, expert blocks of 64)
+  __shared__ __attribute__((aligned(16))) unsigned char s_x[DW_TOK * DW_XROW];
+  __shared__ __attribute__((aligned(16))) unsigned char s_g[3][DW_EXP * DW_GROW];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c_base = blockIdx.x * DW_COLS, chunk = blockIdx.y, e_base = blockIdx.z * DW_EXP;
   const int t_lo = chunk * DW_CHUNK, t_hi = min(T, t_lo + DW_CHUNK);
-  float acc[16][8];
+
+  // loader roles: x -- token row tid / 8, pieces 2 * (tid % 8), +1; dlogits -- token tid / 8, experts 8 * (tid % 8) .. +8
+  const int ld_row = tid >> 3, ld_sub = tid & 7;
+  u32x4 rx[2];
+  float rg[8];
+  auto fetch = [&](int tb) __attribute__((always_inline)) {
+    const int t = tb + ld_row;
+    const int tc = t < T ? t : T - 1;   // rows past the end meet zero gradients below
 #pragma unroll
-  for (int r = 0; r < 16; ++r)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[r][j] = 0.f;
-  for (int tb = t_lo; tb < t_hi; tb += 32) {
-    __syncthreads();
-    for (int i = threadIdx.x; i < 32 * ew; i += 256) {
-      const int t = tb + i / ew, e = e_base + i % ew;
-      s_dl[i] = (t < t_hi && e < E) ? dlogits[static_cast<size_t>(t) * E + e] : 0.f;
+    for (int h = 0; h < 2; ++h) {
+      const int c = c_base + (2 * ld_sub + h) * 8;
+      rx[h] = c < d ? *reinterpret_cast<const u32x4*>(x + static_cast<size_t>(tc) * d + c) : u32x4{0u, 0u, 0u, 0u};
     }
+    const int e = e_base + ld_sub * 8;
+    const float* g = dlogits + static_cast<size_t>(tc) * E + e;
+    if (t < t_hi && e + 7 < E && (E & 3) == 0) {
+      const f32x4 g0 = *reinterpret_cast<const f32x4*>(g), g1 = *reinterpret_cast<const f32x4*>(g + 4);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { rg[j] = g0[j]; rg[4 + j] = g1[j]; }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) rg[j] = (t < t_hi && e + j < E) ? g[j] : 0.f;
+    }
+  };
+  auto stage = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      *reinterpret_cast<u32x4*>(s_x + ld_row * DW_XROW + dw_piece(ld_row, 2 * ld_sub + h) * 16) = rx[h];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const __bf16 hi = static_cast<__bf16>(rg[j]);
+      const float r1 = rg[j] - static_cast<float>(hi);
+      const __bf16 mid = static_cast<__bf16>(r1);
+      const __bf16 lo = static_cast<__bf16>(r1 - static_cast<float>(mid));
+      const int off = (ld_sub * 8 + j) * DW_GROW + ld_row * 2;
+      *reinterpret_cast<__bf16*>(s_g[0] + off) = hi;
+      *reinterpret_cast<__bf16*>(s_g[1] + off) = mid;
+      *reinterpret_cast<__bf16*>(s_g[2] + off) = lo;
+    }
+  };
+
+  // fragment addresses.  x: within 16 lanes, lane i names token row i / 4 and four columns 4 * (i % 4) of the
+  // wave's 32; lane l of the 16 receives rows 0..3 of column l.  The second read lies 4 rows further, the second
+  // 16-token sub-step 16 rows further (the swizzle only depends on row % 4).
+  const int fi = lane & 15, kg = lane >> 5;
+  const int fcol = wave * 32 + ((lane >> 4) & 1) * 16 + 4 * (fi & 3);
+  const int frow = kg * 8 + (fi >> 2);
+  const unsigned char* xfrag = s_x + frow * DW_XROW + dw_piece(frow, fcol >> 3) * 16 + (fcol & 7) * 2;
+  const int gfrag = (lane & 31) * DW_GROW + kg * 16;   // expert lane % 32 of a block, tokens 8 * kg .. +8
+
+  f32x16_t acc[2][3];   // [expert block][term]: independent chains
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int m = 0; m < 3; ++m)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[b][m][r] = 0.f;
+
+  fetch(t_lo);
+  for (int tb = t_lo; tb < t_hi; tb += DW_TOK) {
+    __syncthreads();   // the previous stage has been read
+    stage();
     __syncthreads();
-    const int nt = min(32, t_hi - tb);
-    if (c0 < d) {
-      for (int rb = 0; rb < nt; rb += 4) {   // four token rows in flight
-        u32x4 xv[4];
+    if (tb + DW_TOK < t_hi) fetch(tb + DW_TOK);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int r = rb + u < nt ? rb + u : nt - 1;
-          xv[u] = *reinterpret_cast<const u32x4*>(x + static_cast<size_t>(tb + r) * d + c0);
+    for (int ss = 0; ss < 2; ++ss) {
+      union { s16x4 h[2]; bf16x8_t v; } xb;
+      xb.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(xfrag + ss * 16 * DW_XROW));
+      xb.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(xfrag + ss * 16 * DW_XROW + 4 * DW_XROW));
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int m = 2; m >= 0; --m) {
+          const bf16x8_t ga = *reinterpret_cast<const bf16x8_t*>(s_g[m] + b * 32 * DW_GROW + gfrag + ss * 32);
+          // (gradient, activation): a lane ends up with one column and 16 experts
+          acc[b][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, xb.v, acc[b][m], 0, 0, 0);
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (rb + u < nt) {
-            const float xf[8] = {bf16lo(xv[u][0]), bf16hi(xv[u][0]), bf16lo(xv[u][1]), bf16hi(xv[u][1]),
-                                 bf16lo(xv[u][2]), bf16hi(xv[u][2]), bf16lo(xv[u][3]), bf16hi(xv[u][3])};
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-              if (q < e_per) {
-                const float g = s_dl[(rb + u) * ew + eg * e_per + q];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[q][j] += g * xf[j];
-              }
-            }
-          }
-        }
-      }
     }
   }
-  if (c0 < d) {
+  // acc[b][.][4q+c] = (expert e_base + 32 b + 8 q + 4 (lane / 32) + c, column c_base + 32 wave + lane % 32)
+  const int col = c_base + wave * 32 + (lane & 31);
+  if (col < d) {
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int e = e_base + eg * e_per + q;
-      if (q < e_per && e < E) {
-        float* o = part + (static_cast<size_t>(chunk) * E + e) * d + c0;
-        *reinterpret_cast<f32x4*>(o) = f32x4{acc[q][0], acc[q][1], acc[q][2], acc[q][3]};
-        *reinterpret_cast<f32x4*>(o + 4) = f32x4{acc[q][4], acc[q][5], acc[q][6], acc[q][7]};
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int e = e_base + 32 * b + 8 * (r >> 2) + 4 * kg + (r & 3);
+        if (e < E)
+          part[(static_cast<size_t>(chunk) * E + e) * d + col] = (acc[b][2][r] + acc[b][1][r]) + acc[b][0][r];
       }
-    }
   }
 }
 
@@ -383,13 +440,9 @@ extern "C" int moe_router_bwd(const moe_bf16* x, const float* Wr, const float* d
   }
   const int chunks = (T + DW_CHUNK - 1) / DW_CHUNK;
   {
-    // a thread keeps e_per <= 16 experts; a workgroup covers 4 * e_per of them
-    int e_per = (E + 3) / 4;
-    if (e_per > 16) e_per = 16;
-    const int ew = 4 * e_per;
-    dim3 grid((d + DW_COLS - 1) / DW_COLS, chunks, (E + ew - 1) / ew), block(256);
-    MOE_LAUNCH("router_bwd_dw_partial", router_bwd_dw_partial_kernel, grid, block, 32 * ew * sizeof(float), s, dlogits,
-               x, T, d, E, e_per, static_cast<float*>(ws));
+    dim3 grid((d + DW_COLS - 1) / DW_COLS, chunks, (E + DW_EXP - 1) / DW_EXP), block(256);
+    MOE_LAUNCH("router_bwd_dw_partial", router_bwd_dw_partial_kernel, grid, block, 0, s, dlogits, x, T, d, E,
+               static_cast<float*>(ws));
   }
   {
     const size_t n = static_cast<size_t>(E) * d;
