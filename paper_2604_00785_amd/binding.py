@@ -302,6 +302,21 @@ class MoELayerBuffers:
         self.run_fwd(x, logits, Wg, Wu, Wd)
         self.run_bwd(dout, Wg, Wu, Wd)
 
+    def capture_fwd_bwd(self, x, logits, dout, Wg, Wu, Wd) -> "torch.cuda.CUDAGraph":
+        """Record ``run_fwd_bwd`` on these buffers and arguments into a HIP graph.
+
+        The entry points only launch kernels (no allocation, no memset, no host
+        synchronisation), so the whole step can be captured; ``replay()`` then
+        runs it again with one submission instead of fifteen launches.  Profiling
+        (``moe_prof_enable``) must be off while capturing.
+        """
+        self.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)   # loads every kernel before the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
+        return graph
+
     def results(self) -> Dict[str, torch.Tensor]:
         names = ("topk_idx", "topk_w", "expert_offsets", "row_token", "slot_row", "xp", "g", "u", "h", "yp", "out",
                  "dyp", "dgate", "dxp", "dWg", "dWu", "dWd", "dx")

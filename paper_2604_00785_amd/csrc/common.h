@@ -21,8 +21,12 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
 // two packed bf16 (low half = element 0) <-> two floats
 __device__ __forceinline__ float bf16lo(uint32_t p) { return __uint_as_float(p << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t p) { return __uint_as_float(p & 0xFFFF0000u); }
+// one v_cvt_pk_bf16_f32 (round to nearest even, as the scalar conversion)
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 static inline bool moe_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

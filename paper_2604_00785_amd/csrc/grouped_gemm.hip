@@ -710,8 +710,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
             for (int c = 0; c < 4; ++c) {
               const float dh = acc[hh * 2 + i2][j][4 * q + c];
               const float sg = sigmoid_f(g4[c]);
-              dg[c] = dh * u4[c] * sg * (1.0f + g4[c] * (1.0f - sg));
-              du[c] = dh * g4[c] * sg;
+              const float a = dh * sg;                       // shared by both derivatives
+              du[c] = a * g4[c];
+              dg[c] = (a * u4[c]) * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f);
             }
             u32x2 o;
             o.x = pack_bf16(dg[0], dg[1]);  o.y = pack_bf16(dg[2], dg[3]);

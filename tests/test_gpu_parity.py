@@ -311,3 +311,34 @@ def test_argument_checks():
     assert lib.moe_grouped_gemm_fwd(B._p(x), B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 60, 64,
                                     B._p(x), B._p(x), B._p(x), B._p(x), None) == -1
     torch.cuda.synchronize()
+
+
+def test_graph_replay_matches_eager():
+    """The whole step recorded into a HIP graph: every replay, with eager work and
+    synchronisations in between, leaves exactly the bits the eager step leaves."""
+    cfg = W.MoEConfig("custom", T=700, d=256, E=16, k=4, f=128, seed=11)
+    inp = W.make_inputs(cfg)
+    x, dout = H.bf16_to_dev(inp["x"]), H.bf16_to_dev(inp["dout"])
+    Wg, Wu, Wd = (H.bf16_to_dev(inp[n]) for n in ("Wg", "Wu", "Wd"))
+    logits = torch.from_numpy(inp["logits"]).to(DEV)
+    ref = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f)
+    ref.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
+    torch.cuda.synchronize()
+    want = {n: t.clone() for n, t in ref.results().items()}
+    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f)
+    graph = buf.capture_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
+    for rep in range(3):
+        print(f"graph replay {rep}", flush=True)
+        for t in buf.results().values():
+            t.fill_(1)                      # eager work between replays; stale results cannot pass
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, t in buf.results().items():
+            R = int(want["expert_offsets"][-1])
+            if n in ("xp", "g", "u", "h", "yp", "dyp", "dxp"):
+                assert torch.equal(t[:R], want[n][:R]), n
+            elif n == "row_token":
+                assert torch.equal(t[:R], want[n][:R]), n
+            else:
+                assert torch.equal(t, want[n]), n
