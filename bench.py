@@ -91,7 +91,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="olmoe", help="olmoe (headline) | fine | ep_share | tiny | skew")
+    ap.add_argument("--workload", default="olmoe", help="olmoe (headline) | fine | ep_share | tiny | skew | olmoe_fur | mula100b_ep12 | mula220b_ep12")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192,
                     help="tokens of the batch the CPU oracle is timed on (about 10-30 s of host work)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")

@@ -35,7 +35,7 @@ class MoEConfig:
     f: int
     e_begin: int = 0
     e_count: int = -1          # -1: all experts are local (no expert parallelism)
-    logits: str = "router"     # "router" | "zipf" | "iid"
+    logits: str = "router"     # "router" | "zipf" | "iid" | "fur"
     renormalize: int = 1
     seed: int = 0
 
@@ -62,6 +62,13 @@ CONFIGS: Dict[str, MoEConfig] = {
                           e_begin=0, e_count=8, logits="iid"),
     # fine-grained MoE: many small groups
     "fine": MoEConfig("fine", T=16384, d=2048, E=128, k=8, f=512),
+    # the larger models of Table 1 under 12-way expert parallelism (Section 4.2): one rank's share
+    # of the experts, tokens of all 12 ranks (12 sequences of context 2048)
+    "mula100b_ep12": MoEConfig("mula100b_ep12", T=24576, d=3072, E=144, k=8, f=1536, e_begin=0, e_count=12),
+    "mula220b_ep12": MoEConfig("mula220b_ep12", T=24576, d=3072, E=240, k=8, f=1536, e_begin=20, e_count=20),
+    # the headline shape under forced uniform routing (Section 4.3): every expert gets exactly
+    # T*k/E rows, in a fixed pattern
+    "olmoe_fur": MoEConfig("olmoe_fur", T=8192, d=2048, E=64, k=8, f=1024, logits="fur"),
 }
 
 
@@ -117,6 +124,17 @@ def zipf_bias(E: int, logit_std: float, s: float = 1.2, n_empty: int = 2) -> np.
     return b
 
 
+def fur_logits(T: int, E: int, k: int) -> np.ndarray:
+    """Logits that force uniform routing: slot i of token t goes to expert (t*k + i) mod E, with
+    decreasing logits 1, 1 - 1/k, ... for its k slots and -20 for every other expert.  When E
+    divides T*k every expert gets exactly T*k/E rows."""
+    logits = np.full((T, E), -20.0, dtype=np.float32)
+    t = np.arange(T)[:, None]
+    i = np.arange(k)[None, :]
+    logits[t, (t * k + i) % E] = (1.0 - i / k).astype(np.float32)
+    return logits
+
+
 def make_inputs(cfg: MoEConfig, with_weights: bool = True) -> Dict[str, np.ndarray]:
     """Draw one batch for ``cfg``.
 
@@ -125,10 +143,11 @@ def make_inputs(cfg: MoEConfig, with_weights: bool = True) -> Dict[str, np.ndarr
       dout   uint16 [T, d]      upstream gradient, N(0,1) as bf16 bits
       logits float32 [T, E]     router logits (input of the routing step)
       Wg,Wu  uint16 [n_local, f, d], Wd uint16 [n_local, d, f]   N(0,0.02) as bf16 bits
-      Wr     float32 [E, d]     the router weight the logits were made with (not for "iid")
+      Wr     float32 [E, d]     the router weight the logits were made with ("router" and "zipf" only)
     Router logits are ``x @ Wr.T`` with ``Wr ~ N(0,0.02)`` fp32 ("router"),
-    the same plus a Zipf bias ("zipf"), or i.i.d. N(0,1) ("iid": every
-    k-subset of experts is equally likely, as for already-dispatched tokens).
+    the same plus a Zipf bias ("zipf"), i.i.d. N(0,1) ("iid": every
+    k-subset of experts is equally likely, as for already-dispatched tokens),
+    or the fixed balanced pattern of ``fur_logits`` ("fur").
     """
     rng = np.random.Generator(np.random.PCG64(cfg.seed))
     T, d, E, f, nl = cfg.T, cfg.d, cfg.E, cfg.f, cfg.n_local
@@ -137,6 +156,8 @@ def make_inputs(cfg: MoEConfig, with_weights: bool = True) -> Dict[str, np.ndarr
     out["dout"] = _normal_bf16(rng, (T, d), 1.0)
     if cfg.logits == "iid":
         out["logits"] = rng.standard_normal((T, E), dtype=np.float32)
+    elif cfg.logits == "fur":
+        out["logits"] = fur_logits(T, E, cfg.k)
     else:
         Wr = rng.standard_normal((E, d), dtype=np.float32) * np.float32(0.02)
         logits = bf16_bits_to_f32(out["x"]) @ Wr.T

@@ -27,7 +27,7 @@ def sub_batch(inp, tokens, e_lo, e_hi):
     return s
 
 
-@pytest.mark.parametrize("name", ["olmoe", "fine", "ep_share"])
+@pytest.mark.parametrize("name", ["olmoe", "fine", "ep_share", "olmoe_fur", "mula100b_ep12", "mula220b_ep12"])
 def test_full_size_config(name):
     cfg = W.CONFIGS[name]
     print(f"full size {name}: generating inputs", flush=True)
