@@ -229,6 +229,21 @@ def main():
                                "flop_per_step": 6.0 * cfg.T * cfg.E * cfg.d,
                                "note": "router Linear layer, gradient of softmax/top-k/renormalisation, router weight "
                                        "and input gradients; not part of `value`"}
+    # ---- what the matrix pipe sustains for operand values like this workload's (the clock follows the
+    #      power draw, which follows the data): pure MFMA on register-resident fragments, no memory traffic
+    wgs = torch.cuda.get_device_properties(0).multi_processor_count
+    gen = torch.Generator(device=dev).manual_seed(1)
+    fa = torch.randn(wgs * 512, 32, device=dev, generator=gen).to(torch.bfloat16)                # activations ~ N(0,1)
+    fb = (torch.randn(wgs * 512, 16, device=dev, generator=gen) * 0.02).to(torch.bfloat16)       # weights ~ N(0,0.02)
+    B.moe_prof_mfma_ceiling(fa, fb, 2000)   # warm-up
+    tf_data, ghz_data = B.moe_prof_mfma_ceiling(fa, fb, 40000)
+    tf_zero, ghz_zero = B.moe_prof_mfma_ceiling(torch.zeros_like(fa), torch.zeros_like(fb), 40000)
+    line["mfma_ceiling"] = {
+        "workload_like_operands": {"tflops": round(tf_data, 1), "clock_ghz": round(ghz_data, 3)},
+        "zero_operands": {"tflops": round(tf_zero, 1), "clock_ghz": round(ghz_zero, 3)},
+        "grouped_gemm_frac_of_workload_like": round(gemm_tflops / tf_data, 4) if tf_data > 0 else None,
+        "note": "v_mfma_f32_32x32x16_bf16 only, operands in registers, 8 waves per CU, measured in this run; "
+                "`roofline.peak` stays the published 2500 TFLOP/s"}
     if not args.no_cpu:
         n = min(args.cpu_sample_tokens, cfg.T)
         cb, _ = cpu_baseline(cfg, inp, n)

@@ -211,6 +211,22 @@ int moe_prof_enable(int on);        /* also clears what was recorded */
 int moe_prof_count(void);
 int moe_prof_read(int index, char* name, int name_cap, float* total_ms, int* launches);
 
+/*
+ * Matrix-pipe probe for benchmarks (not part of the paper's method): what rate of
+ * v_mfma_f32_32x32x16_bf16 the chip sustains for given operand VALUES.  The clock
+ * of the chip follows its power draw, which depends on how many operand bits
+ * toggle, so the ceiling for real data lies below the published peak.
+ *   a    [workgroups*512, 32] bf16, device: 4 activation fragments per lane
+ *   b    [workgroups*512, 16] bf16, device: 2 weight fragments per lane
+ *   sink [workgroups*512] f32, device, overwritten (keeps the loop alive)
+ * Launches `workgroups` workgroups of 8 waves, each lane issuing 8*iters MFMAs on
+ * its register-resident fragments with no memory traffic, waits for the kernel
+ * (this call synchronises on its own events) and returns its duration in
+ * milliseconds, its FLOP count and the core clock in GHz observed by wave 0.
+ */
+int moe_prof_mfma_ceiling(const moe_bf16* a, const moe_bf16* b, int workgroups, int iters, float* sink,
+                          float* ms, double* flop, double* clock_ghz, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

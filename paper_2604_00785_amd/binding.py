@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libmoe_hotpath.so")
 EXPORTS = [
     "moe_version", "moe_permute_workspace_bytes", "moe_grouped_gemm_bwd_workspace_bytes", "moe_workspace_bytes",
     "moe_route", "moe_permute", "moe_permute_bwd", "moe_grouped_gemm_fwd", "moe_grouped_gemm_bwd",
-    "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_prof_enable", "moe_prof_count", "moe_prof_read",
+    "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_prof_enable", "moe_prof_count", "moe_prof_read", "moe_prof_mfma_ceiling",
     "moe_router_fwd", "moe_route_bwd", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
 ]
 
@@ -69,6 +69,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "moe_prof_enable": [c_int],
         "moe_prof_count": [],
         "moe_prof_read": [c_int, ctypes.c_char_p, c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(c_int)],
+        "moe_prof_mfma_ceiling": [vp, vp, c_int, c_int, vp, ctypes.POINTER(ctypes.c_float),
+                                  ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -253,6 +255,19 @@ def moe_prof_read() -> List[Tuple[str, float, int]]:
         _check(lib.moe_prof_read(i, buf, 64, ctypes.byref(ms), ctypes.byref(n)), "moe_prof_read")
         out.append((buf.value.decode(), float(ms.value), int(n.value)))
     return out
+
+
+def moe_prof_mfma_ceiling(a: torch.Tensor, b: torch.Tensor, iters: int) -> Tuple[float, float]:
+    """(TFLOP/s, core clock in GHz) of a pure MFMA loop on the operand values in ``a`` [n*512, 32]
+    and ``b`` [n*512, 16] (bf16; n workgroups)."""
+    n = a.shape[0] // 512
+    assert a.dtype == BF16 and b.dtype == BF16 and a.shape == (n * 512, 32) and b.shape == (n * 512, 16)
+    assert a.is_contiguous() and b.is_contiguous()
+    sink = torch.empty(n * 512, dtype=torch.float32, device=a.device)
+    ms, flop, ghz = ctypes.c_float(), ctypes.c_double(), ctypes.c_double()
+    _check(load().moe_prof_mfma_ceiling(_p(a), _p(b), n, iters, _p(sink), ctypes.byref(ms), ctypes.byref(flop),
+                                        ctypes.byref(ghz), _stream()), "moe_prof_mfma_ceiling")
+    return flop.value / (ms.value * 1e-3) / 1e12, ghz.value
 
 
 class MoELayerBuffers:

@@ -1,5 +1,6 @@
-// Library identification, launch error check and the optional per-kernel
-// event timing used by benchmarks.
+// Library identification, launch error check, the optional per-kernel
+// event timing used by benchmarks, and a probe of the matrix-pipe rate the chip
+// sustains for given operand values.
 #include <string.h>
 #include <string>
 #include <vector>
@@ -56,6 +57,51 @@ MoeLaunchScope::~MoeLaunchScope() {
 
 int moe_check_launch() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH; }
 
+namespace {
+// Nothing but v_mfma_f32_32x32x16_bf16: every lane keeps 4 + 2 operand fragments in registers (the
+// wave tile of the grouped GEMM, 8 accumulators) and multiplies them over and over.  No memory
+// traffic inside the loop, so the rate measured is the matrix pipe's at the clock the chip holds
+// for these operand values.
+__device__ long long g_ceiling_clk[2];
+__global__ __launch_bounds__(512) void mfma_ceiling_kernel(const uint16_t* __restrict__ a, const uint16_t* __restrict__ b,
+                                                           int iters, float* __restrict__ sink) {
+  const size_t t = static_cast<size_t>(blockIdx.x) * 512 + threadIdx.x;
+  bf16x8_t fa[4], fb[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(a + t * 32 + i * 8);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(b + t * 16 + j * 8);
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  const long long w0 = wall_clock64(), c0 = __builtin_readcyclecounter();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+  }
+  const long long c1 = __builtin_readcyclecounter(), w1 = wall_clock64();
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += acc[i][j][r];
+  sink[t] = s;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    g_ceiling_clk[0] = c1 - c0;   // core clock cycles
+    g_ceiling_clk[1] = w1 - w0;   // 100 MHz ticks
+  }
+}
+}  // namespace
+
 extern "C" {
 
 const char* moe_version(void) { return "moe_hotpath 0.1 (gfx950, bf16 MFMA)"; }
@@ -83,6 +129,28 @@ int moe_prof_read(int index, char* name, int name_cap, float* total_ms, int* lau
   *total_ms = total;
   *launches = static_cast<int>(en.starts.size());
   return MOE_OK;
+}
+
+int moe_prof_mfma_ceiling(const moe_bf16* a, const moe_bf16* b, int workgroups, int iters, float* sink,
+                          float* ms, double* flop, double* clock_ghz, void* stream) {
+  if (!a || !b || !sink || !ms || !flop || !clock_ghz || workgroups <= 0 || iters <= 0) return MOE_ERR_INVALID;
+  if (!moe_aligned16(a) || !moe_aligned16(b)) return MOE_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t e0 = take_event(), e1 = take_event();
+  if (!e0 || !e1) return MOE_ERR_LAUNCH;
+  (void)hipEventRecord(e0, s);
+  hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(workgroups), dim3(512), 0, s, a, b, iters, sink);
+  (void)hipEventRecord(e1, s);
+  int rc = MOE_OK;
+  long long clk[2] = {0, 0};
+  if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(ms, e0, e1) != hipSuccess ||
+      hipMemcpyFromSymbol(clk, HIP_SYMBOL(g_ceiling_clk), sizeof(clk)) != hipSuccess)
+    rc = MOE_ERR_LAUNCH;
+  g_pool.push_back(e0);
+  g_pool.push_back(e1);
+  *flop = 2.0 * 32 * 32 * 16 * 8.0 * iters * 8.0 * workgroups;
+  *clock_ghz = clk[1] > 0 ? static_cast<double>(clk[0]) / (static_cast<double>(clk[1]) * 10.0) : 0.0;
+  return rc == MOE_OK ? moe_check_launch() : rc;
 }
 
 }  // extern "C"

@@ -10,7 +10,8 @@
 //   x * lo are exact in fp32, so the result has fp32 accuracy at bf16 matrix-core speed.
 // moe_route_bwd    one group of G lanes per token, like moe_route: recomputes the softmax, forms the
 //   gradient of the k chosen probabilities, scatters it by expert through LDS.
-// moe_router_bwd   dx[T,d] += dlogits[T,E] . Wr[E,d]   (vector ALU, fp32; a workgroup owns 8 tokens)
+// moe_router_bwd   dx[T,d] += dlogits[T,E] . Wr[E,d]   (matrix cores, both operands split into two bf16
+//                  terms; the weights pass through LDS and the transposing LDS load)
 //                  dWr[E,d] = dlogits^T . x            (matrix cores, dlogits split into three bf16
 //                  terms; token chunks -> partial sums in the workspace -> one deterministic
 //                  reduction; no atomics)
@@ -201,55 +202,185 @@ void launch_route_bwd(const float* logits, const int32_t* idx, const float* dgat
 }
 
 // ------------------------------------------------------------------ router backward
-constexpr int DX_TOKENS = 8;   // tokens per workgroup; a thread owns 8 consecutive columns of each
+// dx += dlogits . Wr on the matrix cores.  A workgroup owns 128 columns and 128 tokens: its block of
+// the weights is split once into two bf16 terms (hi + mid: 16 significant bits, far more than the
+// bf16 result keeps) and kept in LDS as it lies in memory, experts as rows, to be read with the
+// transposing LDS load; dlogits goes from global memory straight into registers (eight consecutive
+// experts per lane) and is split the same way; the three products hi*hi, hi*mid, mid*hi are
+// accumulated.  Results are staged per wave in LDS so that dx is read and written 16 bytes per lane.
+constexpr int DX_COLS = 128;      // columns per workgroup: 4 waves x 32
+constexpr int DX_TOK = 32;        // tokens per MFMA block
+constexpr int DX_BLOCKS = 4;      // token blocks per workgroup
+constexpr int DX_EXP = 64;        // experts per LDS stage
+constexpr int DX_WROW = DX_COLS * 2;      // bytes of an expert row of a weight term
+constexpr int DX_OROW = 36;               // floats per token row of a wave's output stage (padded)
 
-__global__ __launch_bounds__(256) void router_bwd_dx_kernel(const float* __restrict__ dlogits,
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// 16-byte pieces of a row are XOR-swizzled with 4 * (row & 3): the four rows that 16 lanes of a
+// transposing read touch then fall into different bank groups
+__device__ __forceinline__ int tr_piece(int row, int piece) { return piece ^ ((row & 3) << 2); }
+
+// two bf16 terms of eight fp32 values
+__device__ __forceinline__ void split2(const float (&w)[8], bf16x8_t& hi, bf16x8_t& mid) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const __bf16 h = static_cast<__bf16>(w[i]);
+    hi[i] = h;
+    mid[i] = static_cast<__bf16>(w[i] - static_cast<float>(h));
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void router_bwd_dx_kernel(const float* __restrict__ dlogits,
                                                             const float* __restrict__ Wr, int T, int d, int E,
                                                             uint16_t* __restrict__ dx) {
-  extern __shared__ float s_dl[];   // [DX_TOKENS][E]
-  const int t0 = blockIdx.x * DX_TOKENS;
-  for (int i = threadIdx.x; i < DX_TOKENS * E; i += 256) {
-    const int t = t0 + i / E;
-    s_dl[i] = t < T ? dlogits[static_cast<size_t>(t) * E + i % E] : 0.f;
+  // grid: (column blocks of 128, token chunks of 128)
+  __shared__ __attribute__((aligned(16))) unsigned char s_w[2][DX_EXP * DX_WROW];
+  __shared__ __attribute__((aligned(16))) float s_o[4][DX_TOK * DX_OROW];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c_base = blockIdx.x * DX_COLS, t_base = blockIdx.y * (DX_TOK * DX_BLOCKS);
+  const int lrow = lane & 31, kg = lane >> 5;
+  // weight fragment address: within 16 lanes, lane i names expert row i / 4 and four columns
+  // 4 * (i % 4) of the wave's 32; lane l of the 16 receives rows 0..3 of column l
+  const int fi = lane & 15;
+  const int fcol = wave * 32 + ((lane >> 4) & 1) * 16 + 4 * (fi & 3);
+  const int frow = kg * 8 + (fi >> 2);
+  const int wfrag = frow * DX_WROW + tr_piece(frow, fcol >> 3) * 16 + (fcol & 7) * 2;
+
+  f32x16_t acc[DX_BLOCKS];
+#pragma unroll
+  for (int b = 0; b < DX_BLOCKS; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+
+  // what dx holds so far is requested now and needed only at the end: after the output stage lane l
+  // owns 16 consecutive columns (l % 2) of token l / 2 of each block
+  const int ot = lane >> 1, oc = (lane & 1) * 16;
+  const int col = c_base + wave * 32 + oc;
+  u32x4 old[DX_BLOCKS][2];
+#pragma unroll
+  for (int b = 0; b < DX_BLOCKS; ++b) {
+    const int t = t_base + b * DX_TOK + ot;
+    if (t < T && col < d) {
+      const u32x4* p = reinterpret_cast<const u32x4*>(dx + static_cast<size_t>(t) * d + col);
+      old[b][0] = p[0];
+      old[b][1] = p[1];
+    } else {
+      old[b][0] = u32x4{0u, 0u, 0u, 0u};
+      old[b][1] = u32x4{0u, 0u, 0u, 0u};
+    }
   }
-  __syncthreads();
-  for (int c0 = threadIdx.x * 8; c0 < d; c0 += 256 * 8) {
-    float acc[DX_TOKENS][8];
+
+  for (int e_base = 0; e_base < E; e_base += DX_EXP) {
+    __syncthreads();   // the previous stage has been read
+    // stage the weights: thread -> expert row tid / 4 (64 rows), pieces tid % 4 + 4 h of 16 (8 columns each)
+    {
+      const int er = tid >> 2, e = e_base + er;
 #pragma unroll
-    for (int r = 0; r < DX_TOKENS; ++r)
+      for (int h = 0; h < 4; ++h) {
+        const int piece = h * 4 + (tid & 3), c = c_base + piece * 8;
+        float w[8];
+        if (e < E && c < d) {
+          const f32x4 w0 = *reinterpret_cast<const f32x4*>(Wr + static_cast<size_t>(e) * d + c);
+          const f32x4 w1 = *reinterpret_cast<const f32x4*>(Wr + static_cast<size_t>(e) * d + c + 4);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc[r][j] = 0.f;
-    for (int eb = 0; eb < E; eb += 4) {   // four weight rows in flight
-      f32x4 w0[4], w1[4];
+          for (int j = 0; j < 4; ++j) { w[j] = w0[j]; w[4 + j] = w1[j]; }
+        } else {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int e = eb + u < E ? eb + u : E - 1;
-        w0[u] = *reinterpret_cast<const f32x4*>(Wr + static_cast<size_t>(e) * d + c0);
-        w1[u] = *reinterpret_cast<const f32x4*>(Wr + static_cast<size_t>(e) * d + c0 + 4);
+          for (int j = 0; j < 8; ++j) w[j] = 0.f;
+        }
+        bf16x8_t hi, mid;
+        split2(w, hi, mid);
+        const int off = er * DX_WROW + tr_piece(er, piece) * 16;
+        *reinterpret_cast<bf16x8_t*>(s_w[0] + off) = hi;
+        *reinterpret_cast<bf16x8_t*>(s_w[1] + off) = mid;
       }
+    }
+    __syncthreads();
+    // one 16-expert sub-step of token block b: three MFMAs on the fragments of sub-step ss
+    auto mma3 = [&](int b_, int ss, const float (&gv)[8]) __attribute__((always_inline)) {
+      bf16x8_t ghi, gmid;
+      split2(gv, ghi, gmid);
+      union { s16x4 h[2]; bf16x8_t v; } whi, wmid;
+      const unsigned char* wf = s_w[0] + wfrag + ss * 16 * DX_WROW;
+      whi.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(wf));
+      whi.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(wf + 4 * DX_WROW));
+      wmid.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(wf + DX_EXP * DX_WROW));
+      wmid.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(wf + DX_EXP * DX_WROW + 4 * DX_WROW));
+      // (gradient, weight): a lane ends up with one column and 16 tokens; smallest terms first
+      acc[b_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gmid, whi.v, acc[b_], 0, 0, 0);
+      acc[b_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ghi, wmid.v, acc[b_], 0, 0, 0);
+      acc[b_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ghi, whi.v, acc[b_], 0, 0, 0);
+    };
+    if ((E & 7) == 0) {
+      // Every group of eight experts is whole or absent.  All four sub-steps are run; a group past the
+      // last expert reads the last eight experts again and meets zero weight rows.  Several workgroups
+      // share a compute unit and hide each other's load latency.
+      f32x4 cur[4][2];
+      auto fetch = [&](int b_, f32x4 (&dst)[4][2]) __attribute__((always_inline)) {
+        const int t = t_base + b_ * DX_TOK + lrow;
+        const float* row = dlogits + static_cast<size_t>(t < T ? t : T - 1) * E;   // rows past the end are not stored
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (eb + u < E) {
+        for (int ss = 0; ss < 4; ++ss) {
+          int e = e_base + ss * 16 + kg * 8;
+          if (e > E - 8) e = E - 8;
+          dst[ss][0] = *reinterpret_cast<const f32x4*>(row + e);
+          dst[ss][1] = *reinterpret_cast<const f32x4*>(row + e + 4);
+        }
+      };
 #pragma unroll
-          for (int r = 0; r < DX_TOKENS; ++r) {
-            const float g = s_dl[r * E + eb + u];
+      for (int b = 0; b < DX_BLOCKS; ++b) {
+        fetch(b, cur);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { acc[r][j] += g * w0[u][j]; acc[r][4 + j] += g * w1[u][j]; }
-          }
+        for (int ss = 0; ss < 4; ++ss) {
+          const float gv[8] = {cur[ss][0][0], cur[ss][0][1], cur[ss][0][2], cur[ss][0][3],
+                               cur[ss][1][0], cur[ss][1][1], cur[ss][1][2], cur[ss][1][3]};
+          mma3(b, ss, gv);
+        }
+      }
+    } else {
+      const int nss = min(DX_EXP, E - e_base + 15) / 16;   // 16-expert sub-steps that hold an expert
+#pragma unroll
+      for (int b = 0; b < DX_BLOCKS; ++b) {
+        const int t = t_base + b * DX_TOK + lrow;
+        const int tc = t < T ? t : T - 1;   // rows past the end are computed and not stored
+        const float* g = dlogits + static_cast<size_t>(tc) * E + e_base + kg * 8;
+        for (int ss = 0; ss < nss; ++ss) {
+          const int e = e_base + ss * 16 + kg * 8;
+          float gv[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) gv[j] = e + j < E ? g[ss * 16 + j] : 0.f;
+          mma3(b, ss, gv);
         }
       }
     }
+  }
+  // acc[b][4q+c] = (token t_base + 32 b + 8 q + 4 kg + c, column c_base + 32 wave + lane % 32).
+  // Through the wave's own stage: afterwards lane l owns 16 consecutive columns (l % 2) of token l / 2.
+  float* so = s_o[wave];
 #pragma unroll
-    for (int r = 0; r < DX_TOKENS; ++r) {
-      const int t = t0 + r;
-      if (t < T) {
-        u32x4* p = reinterpret_cast<u32x4*>(dx + static_cast<size_t>(t) * d + c0);
-        const u32x4 old = *p;
+  for (int b = 0; b < DX_BLOCKS; ++b) {
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) so[(8 * (r >> 2) + 4 * kg + (r & 3)) * DX_OROW + lrow] = acc[b][r];
+    __builtin_amdgcn_wave_barrier();
+    const int t = t_base + b * DX_TOK + ot;
+    if (t < T && col < d) {
+      float v[16];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const f32x4 q = *reinterpret_cast<const f32x4*>(so + ot * DX_OROW + oc + 4 * j);
+        v[4 * j] = q[0]; v[4 * j + 1] = q[1]; v[4 * j + 2] = q[2]; v[4 * j + 3] = q[3];
+      }
+      u32x4* p = reinterpret_cast<u32x4*>(dx + static_cast<size_t>(t) * d + col);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
         u32x4 o;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          o[j] = pack_bf16(bf16lo(old[j]) + acc[r][2 * j], bf16hi(old[j]) + acc[r][2 * j + 1]);
-        *p = o;
+          o[j] = pack_bf16(bf16lo(old[b][h][j]) + v[8 * h + 2 * j], bf16hi(old[b][h][j]) + v[8 * h + 2 * j + 1]);
+        p[h] = o;
       }
     }
   }
@@ -267,13 +398,6 @@ constexpr int DW_EXP = 64;      // experts per workgroup: 2 MFMA row blocks
 constexpr int DW_TOK = 32;      // tokens per stage
 constexpr int DW_XROW = DW_COLS * 2;        // bytes of a token row of the x stage
 constexpr int DW_GROW = DW_TOK * 2 + 16;    // bytes of an expert row of a dlogits term (padded)
-
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
-// 16-byte pieces of a token row are XOR-swizzled with 4 * (row & 3): the four rows that 16 lanes of a
-// transposing read touch then fall into different bank groups
-__device__ __forceinline__ int dw_piece(int row, int piece) { return piece ^ ((row & 3) << 2); }
 
 __global__ __launch_bounds__(256) void router_bwd_dw_partial_kernel(const float* __restrict__ dlogits,
                                                                     const uint16_t* __restrict__ x, int T, int d,
@@ -311,7 +435,7 @@ __global__ __launch_bounds__(256) void router_bwd_dw_partial_kernel(const float*
   auto stage = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int h = 0; h < 2; ++h)
-      *reinterpret_cast<u32x4*>(s_x + ld_row * DW_XROW + dw_piece(ld_row, 2 * ld_sub + h) * 16) = rx[h];
+      *reinterpret_cast<u32x4*>(s_x + ld_row * DW_XROW + tr_piece(ld_row, 2 * ld_sub + h) * 16) = rx[h];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const __bf16 hi = static_cast<__bf16>(rg[j]);
@@ -331,7 +455,7 @@ __global__ __launch_bounds__(256) void router_bwd_dw_partial_kernel(const float*
   const int fi = lane & 15, kg = lane >> 5;
   const int fcol = wave * 32 + ((lane >> 4) & 1) * 16 + 4 * (fi & 3);
   const int frow = kg * 8 + (fi >> 2);
-  const unsigned char* xfrag = s_x + frow * DW_XROW + dw_piece(frow, fcol >> 3) * 16 + (fcol & 7) * 2;
+  const unsigned char* xfrag = s_x + frow * DW_XROW + tr_piece(frow, fcol >> 3) * 16 + (fcol & 7) * 2;
   const int gfrag = (lane & 31) * DW_GROW + kg * 16;   // expert lane % 32 of a block, tokens 8 * kg .. +8
 
   f32x16_t acc[2][3];   // [expert block][term]: independent chains
@@ -434,9 +558,8 @@ extern "C" int moe_router_bwd(const moe_bf16* x, const float* Wr, const float* d
   if (ws_bytes < moe_router_bwd_workspace_bytes(T, d, E)) return MOE_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   {
-    dim3 grid((T + DX_TOKENS - 1) / DX_TOKENS), block(256);
-    MOE_LAUNCH("router_bwd_dx", router_bwd_dx_kernel, grid, block, DX_TOKENS * E * sizeof(float), s, dlogits, Wr, T, d,
-               E, dx);
+    dim3 grid((d + DX_COLS - 1) / DX_COLS, (T + DX_TOK * DX_BLOCKS - 1) / (DX_TOK * DX_BLOCKS)), block(256);
+    MOE_LAUNCH("router_bwd_dx", router_bwd_dx_kernel, grid, block, 0, s, dlogits, Wr, T, d, E, dx);
   }
   const int chunks = (T + DW_CHUNK - 1) / DW_CHUNK;
   {

@@ -241,7 +241,8 @@ def test_route_bwd(T, E, k, renorm):
     assert np.abs(got - ref).max() <= 2e-5 * max(np.abs(ref).max(), 1e-30)
 
 
-@pytest.mark.parametrize("T,d,E", [(256, 128, 8), (1000, 2048, 64), (300, 64, 100), (33, 48, 5), (2100, 256, 130)])
+@pytest.mark.parametrize("T,d,E", [(256, 128, 8), (1000, 2048, 64), (300, 64, 100), (33, 48, 5), (2100, 256, 130),
+                                   (500, 192, 72), (70, 512, 136)])
 def test_router_bwd(T, d, E):
     print(f"router_bwd T={T} d={d} E={E}", flush=True)
     rng = np.random.default_rng(T + 3 * d + E)
