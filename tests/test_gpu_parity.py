@@ -297,6 +297,31 @@ def test_drop_in_block_router_to_gradients():
     assert np.abs(H.bf16_from_dev(buf.dx) - dx_expert).max() > 0
 
 
+def test_layer_without_local_rows():
+    """No token chooses a local expert: every offset is 0, no grouped row exists, the layer
+    output and every gradient are exactly zero (and written: the buffers start as NaN)."""
+    cfg = W.MoEConfig("custom", T=192, d=128, E=8, k=2, f=64, e_begin=6, e_count=2, seed=3)
+    inp = W.make_inputs(cfg)
+    inp["logits"][:, 6:] = -50.0          # experts 6 and 7 are never among the top 2
+    res = H.run_layer(cfg, inp)
+    ref = O.layer_fwd_bwd(inp, cfg.k, cfg.e_begin, cfg.n_local, cfg.renormalize)
+    assert int(ref["expert_offsets"][-1]) == 0
+    assert np.array_equal(res["expert_offsets"], np.zeros(3, dtype=np.int32))
+    assert np.array_equal(res["topk_idx"], ref["topk_idx"])
+    assert np.all(res["slot_row"] == -1)
+    for n in ("out", "dx", "dgate", "dWg", "dWu", "dWd"):
+        assert np.all(res[n] == 0.0), n
+
+
+def test_layer_single_token():
+    """T = 1: one token, k rows, every tile almost empty."""
+    cfg = W.MoEConfig("custom", T=1, d=64, E=4, k=2, f=64, seed=9)
+    inp = W.make_inputs(cfg)
+    res = H.run_layer(cfg, inp)
+    ref = O.layer_fwd_bwd(inp, cfg.k, cfg.e_begin, cfg.n_local, cfg.renormalize)
+    H.compare_layer(res, ref, cfg.n_local)
+
+
 def test_argument_checks():
     t = torch.zeros(64, 64, dtype=torch.float32, device=DEV)
     idx = torch.zeros(64, 2, dtype=torch.int32, device=DEV)
@@ -311,6 +336,18 @@ def test_argument_checks():
                            B._p(x), 0, None) == -2
     assert lib.moe_grouped_gemm_fwd(B._p(x), B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 60, 64,
                                     B._p(x), B._p(x), B._p(x), B._p(x), None) == -1
+    # router entry points: d must be a multiple of 16, the workspace large enough, pointers aligned
+    Wr = torch.zeros(8, 64, dtype=torch.float32, device=DEV)
+    lg = torch.zeros(64, 8, dtype=torch.float32, device=DEV)
+    assert lib.moe_router_fwd(B._p(x), B._p(Wr), 64, 40, 8, B._p(lg), None) == -1
+    assert lib.moe_router_fwd(B._p(x), B._p(Wr), 0, 64, 8, B._p(lg), None) == -1
+    assert lib.moe_router_fwd(B._p(x), Wr.data_ptr() + 4, 64, 64, 8, B._p(lg), None) == -1
+    assert lib.moe_route_bwd(B._p(lg), B._p(idx), B._p(w), 64, 8, 9, 1, B._p(lg), None) == -1
+    need = lib.moe_router_bwd_workspace_bytes(64, 64, 8)
+    assert need == 1 * 8 * 64 * 4
+    ws = torch.zeros(need, dtype=torch.uint8, device=DEV)
+    assert lib.moe_router_bwd(B._p(x), B._p(Wr), B._p(lg), 64, 64, 8, B._p(x), B._p(Wr), B._p(ws), need - 1, None) == -2
+    assert lib.moe_router_bwd(B._p(x), B._p(Wr), B._p(lg), 64, 64, 8, B._p(x), B._p(Wr), None, need, None) == -1
     torch.cuda.synchronize()
 
 
