@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192,
                     help="tokens of the batch the CPU oracle is timed on (about 10-30 s of host work)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--materialize-xp", action="store_true",
+                    help="gather the routed rows into xp with a kernel of its own (permute_rows) instead of letting "
+                         "the gate/up product and the two weight gradients read x through row_token")
     ap.add_argument("--graph", action="store_true",
                     help="time the step as one HIP graph replay instead of fifteen stream launches "
                          "(measured: no faster, the launches already queue ahead of the GPU)")
@@ -125,7 +128,8 @@ def main():
     x, dout = up(inp["x"]), up(inp["dout"])
     Wg, Wu, Wd = up(inp["Wg"]), up(inp["Wu"]), up(inp["Wd"])
     logits = torch.from_numpy(inp["logits"]).to(dev)
-    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.e_begin, cfg.n_local, cfg.renormalize, dev)
+    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.e_begin, cfg.n_local, cfg.renormalize, dev,
+                            gather=not args.materialize_xp)
 
     def eager_step():
         buf.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
@@ -197,7 +201,9 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} (local {cfg.n_local}) k={cfg.k} f={cfg.f}",
                    "routed_rows": R, "renormalize": cfg.renormalize,
-                   "launch": "hip graph replay" if args.graph else "stream launches"},
+                   "launch": "hip graph replay" if args.graph else "stream launches",
+                   "row_gather": "own kernel (xp materialised)" if args.materialize_xp
+                                 else "folded into the loads of the gate/up product and of two weight gradients"},
         "grouped_gemm": {"tflops": round(gemm_tflops, 1), "frac_of_bf16_peak": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                          "flop_per_step": 18.0 * R * cfg.d * cfg.f, "us_per_step": round(gemm_us, 1)},
         "roofline": roofline,

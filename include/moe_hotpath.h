@@ -95,7 +95,10 @@ int moe_route(const float* logits, int T, int E, int k, int renormalize,
  *   slot_row       [T, k] int32       out: grouped row of pair (t, i), -1 when its
  *                                     expert is not local (dense form of
  *                                     output_indices / selected_expert_indices)
- *   xp             [T*k, d] bf16      out: xp[r] = x[row_token[r]] for r < R
+ *   xp             [T*k, d] bf16      out: xp[r] = x[row_token[r]] for r < R.
+ *                                     May be NULL: then only the index arrays are
+ *                                     produced and x is not read (for the *_gather
+ *                                     products below, which read x through row_token)
  *   ws             at least moe_permute_workspace_bytes(T, k, e_count)
  */
 int moe_permute(const moe_bf16* x, const int32_t* topk_idx,
@@ -126,6 +129,19 @@ int moe_grouped_gemm_fwd(const moe_bf16* xp, const int32_t* expert_offsets,
                          moe_bf16* g, moe_bf16* u, moe_bf16* h, moe_bf16* yp, void* stream);
 
 /*
+ * Stage 4 with mlp_in = input[input_indices] folded into the first product: the
+ * same results as moe_grouped_gemm_fwd on xp[r] = x[row_token[r]], but the gate/up
+ * product loads the rows of x itself, so xp need not exist.
+ *   x [T, d] bf16, T*d*2 bytes at most 4 GiB (row offsets are 32-bit);
+ *   row_token [R_cap] int32 as written by moe_permute; everything else as above.
+ */
+int moe_grouped_gemm_fwd_gather(const moe_bf16* x, int T, const int32_t* row_token,
+                                const int32_t* expert_offsets,
+                                const moe_bf16* Wg, const moe_bf16* Wu, const moe_bf16* Wd,
+                                int E, int R_cap, int d, int f,
+                                moe_bf16* g, moe_bf16* u, moe_bf16* h, moe_bf16* yp, void* stream);
+
+/*
  * Derivative of Stage 4.  With s = sigmoid(g):
  *   dh = dyp . Wd[e];  dg = dh * u * s * (1 + g * (1 - s));  du = dh * g * s;
  *   dxp = dg . Wg[e] + du . Wu[e];
@@ -140,6 +156,16 @@ int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp,
                          int E, int R_cap, int d, int f,
                          moe_bf16* dxp, moe_bf16* dWg, moe_bf16* dWu, moe_bf16* dWd,
                          void* ws, size_t ws_bytes, void* stream);
+
+/* The same with xp[r] = x[row_token[r]] read through row_token by the two weight-gradient
+ * products that need it (dWg, dWu); x, T, row_token as for moe_grouped_gemm_fwd_gather. */
+int moe_grouped_gemm_bwd_gather(const moe_bf16* dyp, const moe_bf16* x, int T, const int32_t* row_token,
+                                const moe_bf16* g, const moe_bf16* u, const moe_bf16* h,
+                                const int32_t* expert_offsets,
+                                const moe_bf16* Wg, const moe_bf16* Wu, const moe_bf16* Wd,
+                                int E, int R_cap, int d, int f,
+                                moe_bf16* dxp, moe_bf16* dWg, moe_bf16* dWu, moe_bf16* dWd,
+                                void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Stage 5, ExpertOutputReductionForward:

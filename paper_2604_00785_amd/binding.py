@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libmoe_hotpath.so")
 EXPORTS = [
     "moe_version", "moe_permute_workspace_bytes", "moe_grouped_gemm_bwd_workspace_bytes", "moe_workspace_bytes",
     "moe_route", "moe_permute", "moe_permute_bwd", "moe_grouped_gemm_fwd", "moe_grouped_gemm_bwd",
+    "moe_grouped_gemm_fwd_gather", "moe_grouped_gemm_bwd_gather",
     "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_prof_enable", "moe_prof_count", "moe_prof_read", "moe_prof_mfma_ceiling",
     "moe_router_fwd", "moe_route_bwd", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
 ]
@@ -61,6 +62,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "moe_permute_bwd": [vp, vp, c_int, c_int, c_int, vp, vp],
         "moe_grouped_gemm_fwd": [vp, vp, vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp],
         "moe_grouped_gemm_bwd": [vp] * 9 + [c_int] * 4 + [vp] * 4 + [vp, c_sz, vp],
+        "moe_grouped_gemm_fwd_gather": [vp, c_int, vp, vp, vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp],
+        "moe_grouped_gemm_bwd_gather": [vp, vp, c_int, vp] + [vp] * 7 + [c_int] * 4 + [vp] * 4 + [vp, c_sz, vp],
         "moe_unpermute_combine": [vp, vp, vp, c_int, c_int, c_int, vp, vp],
         "moe_unpermute_combine_bwd": [vp, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp],
         "moe_router_fwd": [vp, vp, c_int, c_int, c_int, vp, vp],
@@ -140,7 +143,8 @@ def moe_permute(x, topk_idx, E_total: int, e_begin: int, e_count: int,
     _want(expert_offsets, torch.int32, (e_count + 1,), "expert_offsets")
     _want(row_token, torch.int32, (T * k,), "row_token")
     _want(slot_row, torch.int32, (T, k), "slot_row")
-    _want(xp, BF16, (T * k, d), "xp")
+    if xp is not None:      # None: index arrays only (the *_gather products read x through row_token)
+        _want(xp, BF16, (T * k, d), "xp")
     _check(load().moe_permute(_p(x), _p(topk_idx), T, d, E_total, k, e_begin, e_count, _p(expert_offsets),
                               _p(row_token), _p(slot_row), _p(xp), _p(ws), ws.numel() * ws.element_size(),
                               _stream()), "moe_permute")
@@ -164,6 +168,37 @@ def moe_grouped_gemm_fwd(xp, expert_offsets, Wg, Wu, Wd, g, u, h, yp) -> None:
     _want(expert_offsets, torch.int32, (E + 1,), "expert_offsets")
     _check(load().moe_grouped_gemm_fwd(_p(xp), _p(expert_offsets), _p(Wg), _p(Wu), _p(Wd), E, R_cap, d, f,
                                        _p(g), _p(u), _p(h), _p(yp), _stream()), "moe_grouped_gemm_fwd")
+
+
+def moe_grouped_gemm_fwd_gather(x, row_token, expert_offsets, Wg, Wu, Wd, g, u, h, yp) -> None:
+    T, d = x.shape
+    R_cap = row_token.shape[0]
+    E, f, _ = Wg.shape
+    for n, t, shp in (("x", x, (T, d)), ("Wg", Wg, (E, f, d)), ("Wu", Wu, (E, f, d)), ("Wd", Wd, (E, d, f)),
+                      ("g", g, (R_cap, f)), ("u", u, (R_cap, f)), ("h", h, (R_cap, f)), ("yp", yp, (R_cap, d))):
+        _want(t, BF16, shp, n)
+    _want(row_token, torch.int32, (R_cap,), "row_token")
+    _want(expert_offsets, torch.int32, (E + 1,), "expert_offsets")
+    _check(load().moe_grouped_gemm_fwd_gather(_p(x), T, _p(row_token), _p(expert_offsets), _p(Wg), _p(Wu), _p(Wd), E,
+                                              R_cap, d, f, _p(g), _p(u), _p(h), _p(yp), _stream()),
+           "moe_grouped_gemm_fwd_gather")
+
+
+def moe_grouped_gemm_bwd_gather(dyp, x, row_token, g, u, h, expert_offsets, Wg, Wu, Wd, dxp, dWg, dWu, dWd, ws) -> None:
+    T, d = x.shape
+    R_cap = row_token.shape[0]
+    E, f, _ = Wg.shape
+    for n, t, shp in (("dyp", dyp, (R_cap, d)), ("x", x, (T, d)), ("g", g, (R_cap, f)), ("u", u, (R_cap, f)),
+                      ("h", h, (R_cap, f)), ("Wg", Wg, (E, f, d)), ("Wu", Wu, (E, f, d)), ("Wd", Wd, (E, d, f)),
+                      ("dxp", dxp, (R_cap, d)), ("dWg", dWg, (E, f, d)), ("dWu", dWu, (E, f, d)),
+                      ("dWd", dWd, (E, d, f))):
+        _want(t, BF16, shp, n)
+    _want(row_token, torch.int32, (R_cap,), "row_token")
+    _want(expert_offsets, torch.int32, (E + 1,), "expert_offsets")
+    _check(load().moe_grouped_gemm_bwd_gather(_p(dyp), _p(x), T, _p(row_token), _p(g), _p(u), _p(h),
+                                              _p(expert_offsets), _p(Wg), _p(Wu), _p(Wd), E, R_cap, d, f, _p(dxp),
+                                              _p(dWg), _p(dWu), _p(dWd), _p(ws), ws.numel() * ws.element_size(),
+                                              _stream()), "moe_grouped_gemm_bwd_gather")
 
 
 def moe_grouped_gemm_bwd(dyp, xp, g, u, h, expert_offsets, Wg, Wu, Wd, dxp, dWg, dWu, dWd, ws) -> None:
@@ -279,8 +314,9 @@ class MoELayerBuffers:
     """
 
     def __init__(self, T: int, d: int, E: int, k: int, f: int, e_begin: int = 0, e_count: int = -1,
-                 renormalize: int = 1, device="cuda:0"):
+                 renormalize: int = 1, device="cuda:0", gather: bool = False):
         self.T, self.d, self.E, self.k, self.f = T, d, E, k, f
+        self.gather = gather     # True: no xp; the gate/up product and two weight gradients read x through row_token
         self.e_begin = e_begin
         self.e_count = E if e_count < 0 else e_count
         self.renormalize = renormalize
@@ -292,7 +328,8 @@ class MoELayerBuffers:
         self.expert_offsets = z(nl + 1, dt=torch.int32)
         self.row_token = z(R, dt=torch.int32)
         self.slot_row = z(T, k, dt=torch.int32)
-        self.xp, self.yp, self.dyp, self.dxp = z(R, d), z(R, d), z(R, d), z(R, d)
+        self.xp = None if gather else z(R, d)
+        self.yp, self.dyp, self.dxp = z(R, d), z(R, d), z(R, d)
         self.g, self.u, self.h = z(R, f), z(R, f), z(R, f)
         self.out, self.dx = z(T, d), z(T, d)
         self.dgate = z(T, k, dt=torch.float32)
@@ -304,13 +341,22 @@ class MoELayerBuffers:
         moe_route(logits, self.k, self.renormalize, self.topk_idx, self.topk_w)
         moe_permute(x, self.topk_idx, self.E, self.e_begin, self.e_count, self.expert_offsets, self.row_token,
                     self.slot_row, self.xp, self.ws)
-        moe_grouped_gemm_fwd(self.xp, self.expert_offsets, Wg, Wu, Wd, self.g, self.u, self.h, self.yp)
+        if self.gather:
+            self._x = x          # the backward reads the layer input again
+            moe_grouped_gemm_fwd_gather(x, self.row_token, self.expert_offsets, Wg, Wu, Wd, self.g, self.u, self.h,
+                                        self.yp)
+        else:
+            moe_grouped_gemm_fwd(self.xp, self.expert_offsets, Wg, Wu, Wd, self.g, self.u, self.h, self.yp)
         moe_unpermute_combine(self.yp, self.slot_row, self.topk_w, self.out)
 
     def run_bwd(self, dout, Wg, Wu, Wd) -> None:
         moe_unpermute_combine_bwd(dout, self.yp, self.slot_row, self.topk_w, self.dyp, self.dgate)
-        moe_grouped_gemm_bwd(self.dyp, self.xp, self.g, self.u, self.h, self.expert_offsets, Wg, Wu, Wd,
-                             self.dxp, self.dWg, self.dWu, self.dWd, self.ws)
+        if self.gather:
+            moe_grouped_gemm_bwd_gather(self.dyp, self._x, self.row_token, self.g, self.u, self.h, self.expert_offsets,
+                                        Wg, Wu, Wd, self.dxp, self.dWg, self.dWu, self.dWd, self.ws)
+        else:
+            moe_grouped_gemm_bwd(self.dyp, self.xp, self.g, self.u, self.h, self.expert_offsets, Wg, Wu, Wd,
+                                 self.dxp, self.dWg, self.dWu, self.dWd, self.ws)
         moe_permute_bwd(self.dxp, self.slot_row, self.dx)
 
     def run_fwd_bwd(self, x, logits, dout, Wg, Wu, Wd) -> None:
@@ -335,4 +381,4 @@ class MoELayerBuffers:
     def results(self) -> Dict[str, torch.Tensor]:
         names = ("topk_idx", "topk_w", "expert_offsets", "row_token", "slot_row", "xp", "g", "u", "h", "yp", "out",
                  "dyp", "dgate", "dxp", "dWg", "dWu", "dWd", "dx")
-        return {n: getattr(self, n) for n in names}
+        return {n: getattr(self, n) for n in names if getattr(self, n) is not None}

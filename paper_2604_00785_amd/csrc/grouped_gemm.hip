@@ -63,7 +63,9 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-enum GemmMode { GATE_UP = 0, DOWN = 1, DGRAD_H = 2, DGRAD_X = 3, WGRAD = 4 };
+enum GemmMode { GATE_UP = 0, DOWN = 1, DGRAD_H = 2, DGRAD_X = 3, WGRAD = 4, WGRAD_GATHER = 5 };
+// WGRAD_GATHER: a weight gradient whose B operand rows are token rows found through row_token
+constexpr bool is_wgrad(int mode) { return mode == WGRAD || mode == WGRAD_GATHER; }
 
 struct GemmArgs {
   // row-grouped products (modes 0-3)
@@ -77,6 +79,8 @@ struct GemmArgs {
   uint16_t* O1;         // u | du
   uint16_t* O2;         // h
   const int32_t* offsets;
+  const int32_t* row_token;   // not null: rows of the activation operand are gathered, row r lies at A0[row_token[r]]
+                              // (GATE_UP: the A operand; WGRAD: the B operand)
   int E;
   int K;                // reduction length of one phase (modes 0-3)
   int N;                // output columns (per half for GATE_UP)
@@ -121,6 +125,13 @@ template <int OFF> __device__ __forceinline__ void dma16(uint32_t lds_base, uint
 template <int OFF> __device__ __forceinline__ void dma16_lane(uint32_t lds_base, const char* p) {
   asm volatile("s_add_i32 m0, %0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                :: "s"(lds_base), "v"(p), "n"(OFF) : "memory", "scc");
+}
+// A 4-byte load as (scalar base) + (32-bit lane offset) + immediate, awaited by hand like the loads
+// above (the compiler's own wait would count only the loads it knows of and so drain the whole queue).
+template <int OFF> __device__ __forceinline__ int load_i32(uint32_t voff, const int32_t* sbase) {
+  int v;
+  asm volatile("global_load_dword %0, %1, %2 offset:%3" : "=v"(v) : "v"(voff), "s"(sbase), "n"(OFF) : "memory");
+  return v;
 }
 template <int N> __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
 
@@ -220,7 +231,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   // (b % 8) * (gridDim.x / 8) + b / 8 of every round: each XCD then works on a run of
   // consecutive tiles (same expert, neighbouring panels) that share its L2.
   int total;
-  if constexpr (MODE == WGRAD) total = a.E * a.m_tiles_cap * a.n_tiles;
+  if constexpr (is_wgrad(MODE)) total = a.E * a.m_tiles_cap * a.n_tiles;
   else total = count_row_tiles(a.offsets, a.E, tid0 & 63) * a.n_tiles;
   const int per_xcd = gridDim.x >> 3;
   const int first_tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -233,7 +244,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   const int lane = tid & 63;
   int e, m0, m_end;
   const int nt = tile % a.n_tiles;
-  if constexpr (MODE == WGRAD) {
+  if constexpr (is_wgrad(MODE)) {
     const int rest = tile / a.n_tiles;
     e = rest / a.m_tiles_cap;
     m0 = (rest % a.m_tiles_cap) * BM;   // output row of dW
@@ -252,8 +263,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   nfa = nfa < 0 ? 0 : (nfa > 4 ? 4 : nfa);
   nfa = __builtin_amdgcn_readfirstlane(nfa);
 
-  constexpr bool A_KN = (MODE == WGRAD);                                        // stored [k][m]
-  constexpr bool B_KN = (MODE == WGRAD || MODE == DGRAD_H || MODE == DGRAD_X);  // stored [k][n]
+  constexpr bool A_KN = is_wgrad(MODE);                                       // stored [k][m]
+  constexpr bool B_KN = (is_wgrad(MODE) || MODE == DGRAD_H || MODE == DGRAD_X);  // stored [k][n]
 
   // ---------------- operand sources -------------------------------------------
   // A tile <-> output rows m0 + r ; B tile <-> output columns.  Per step and operand a wave issues
@@ -270,17 +281,28 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   ptrdiff_t a_phase = 0, b_phase = 0;   // byte offset of the second K phase (DGRAD_X)
   size_t a_step, b_step;                // bytes per step
   int k_lo = 0, k_hi = 0;               // WGRAD: the expert's row range is the reduction
+  constexpr bool GATHER_B = (MODE == WGRAD_GATHER);
+  const int32_t* row_tok = nullptr;     // GATHER_B: token of the expert's first reduction row onwards
+  uint32_t vcb[4] = {0, 0, 0, 0};       // GATHER_B: byte offset of the lane's columns within a token row
+  int tokn[4] = {0, 0, 0, 0};           // GATHER_B: tokens of the lane's four reduction rows of a coming step
   int nk, nk_phase;                     // steps in total / in the first K phase
 
-  if constexpr (MODE == WGRAD) {
+  if constexpr (is_wgrad(MODE)) {
     k_lo = __builtin_amdgcn_readfirstlane(a.offsets[e]);
     k_hi = __builtin_amdgcn_readfirstlane(a.offsets[e + 1]);
     nk = (k_hi - k_lo + BK - 1) / BK;
     nk_phase = nk;
     abase = reinterpret_cast<const char*>(a.A0 + static_cast<size_t>(k_lo) * a.M + m0);
-    bbase = reinterpret_cast<const char*>(a.B0 + static_cast<size_t>(k_lo) * a.N + n0);
     a_step = static_cast<size_t>(BK) * a.M * 2;
-    b_step = static_cast<size_t>(BK) * a.N * 2;
+    if constexpr (GATHER_B) {
+      // the base stays at the first token row; a load's lane offset carries its token (set per step)
+      bbase = reinterpret_cast<const char*>(a.B0 + n0);
+      b_step = 0;
+      row_tok = a.row_token + k_lo;
+    } else {
+      bbase = reinterpret_cast<const char*>(a.B0 + static_cast<size_t>(k_lo) * a.N + n0);
+      b_step = static_cast<size_t>(BK) * a.N * 2;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int krow = (wave * 4 + i) * 2 + (lane >> 5);
@@ -289,19 +311,24 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       int cb = piece * 8;  if (n0 + cb > a.N - 8) cb = a.N - 8 - n0;
       voa[i] = static_cast<uint32_t>((krow * a.M + ca) * 2);
       vob[i] = static_cast<uint32_t>((krow * a.N + cb) * 2);
+      if constexpr (GATHER_B) vcb[i] = static_cast<uint32_t>(cb * 2);
     }
   } else {
     nk = a.K / BK;
     nk_phase = nk;
     abase = reinterpret_cast<const char*>(a.A0 + static_cast<size_t>(m0) * a.K);
     a_step = BK * 2;
+    bool gathered = false;
+    if constexpr (MODE == GATE_UP) gathered = a.row_token != nullptr;
+    if (gathered) abase = reinterpret_cast<const char*>(a.A0);   // lane offsets carry the token row
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = (wave * 4 + i) * 8 + (lane >> 3);
       const int chunk = (kc_off(row, lane & 7) >> 4) & 7;   // the swizzle is its own inverse
       int r = row;
       if (m0 + r > m_end - 1) r = m_end - 1 - m0;
-      voa[i] = static_cast<uint32_t>((r * a.K + chunk * 8) * 2);
+      if (gathered) voa[i] = (static_cast<uint32_t>(a.row_token[m0 + r]) * a.K + chunk * 8) * 2u;
+      else voa[i] = static_cast<uint32_t>((r * a.K + chunk * 8) * 2);
     }
     if constexpr (MODE == DGRAD_X) { a_phase = (a.A1 - a.A0) * 2; nk *= 2; }
     const size_t wsz = static_cast<size_t>(a.N) * a.K;
@@ -360,7 +387,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   auto a_part = [&](int kt, auto slot_tag, auto i_tag) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_tag)::value, i = decltype(i_tag)::value;
     constexpr int OFF = SLOT * TILE_BYTES + i * 1024;
-    if constexpr (MODE == WGRAD) {
+    if constexpr (is_wgrad(MODE)) {
       if (k_lo + (kt + 1) * BK > k_hi) {
         // last, partial step of the expert: reduction rows at or past its end read zeros
         // (per-lane 64-bit addresses; once per tile)
@@ -377,7 +404,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   auto b_part = [&](int kt, auto slot_tag, auto i_tag) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_tag)::value, i = decltype(i_tag)::value;
     constexpr int OFF = SLOT * TILE_BYTES + i * 1024;
-    if constexpr (MODE == WGRAD) {
+    if constexpr (GATHER_B) {
+      dma16<OFF>(lds_fill, vob[i], sb_next);   // rows past the expert's end were clamped when their tokens were fetched
+    } else if constexpr (MODE == WGRAD) {
       if (k_lo + (kt + 1) * BK > k_hi) {
         // ... and the other operand reads its last valid row there, so that zero times it is zero
         const int krow = k_lo + kt * BK + (wave * 4 + i) * 2 + (lane >> 5);
@@ -399,6 +428,40 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     sb_next += b_step;
     if constexpr (MODE == DGRAD_X) {
       if (kt + 1 == nk_phase) sb_next = sb_phase1;
+    }
+  };
+  // GATHER_B: the tokens of the lane's four reduction rows of step kt, loaded without any vector-ALU
+  // work except in an expert's last, partial step (rows past its end repeat its last row: the other
+  // operand is zero there), and their turn into lane offsets of the B loads.  The loads are asynchronous:
+  // apply_tok may only run after a wait that covers them.
+  const uint32_t tok_voff = static_cast<uint32_t>(((wave * 4) * 2 + (lane >> 5)) * 4);   // row of load 0; load i: + 2 i rows
+  auto fetch_tok = [&](int kt) __attribute__((always_inline)) {
+    if constexpr (GATHER_B) {
+      if (k_lo + (kt + 1) * BK > k_hi) {
+        const int last = k_hi - k_lo - 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          int r = kt * BK + (wave * 4 + i) * 2 + (lane >> 5);
+          if (r > last) r = last;
+          tokn[i] = load_i32<0>(static_cast<uint32_t>(r) * 4u, row_tok);
+        }
+      } else {
+        const int32_t* base = row_tok + static_cast<size_t>(kt) * BK;
+        tokn[0] = load_i32<0>(tok_voff, base);
+        tokn[1] = load_i32<8>(tok_voff, base);
+        tokn[2] = load_i32<16>(tok_voff, base);
+        tokn[3] = load_i32<24>(tok_voff, base);
+      }
+    }
+  };
+  auto apply_tok = [&]() __attribute__((always_inline)) {
+    if constexpr (GATHER_B) {
+      const uint32_t row_bytes = static_cast<uint32_t>(a.N) * 2u;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        asm volatile("" : "+v"(tokn[i]));   // not before the wait that precedes this call
+        vob[i] = static_cast<uint32_t>(tokn[i]) * row_bytes + vcb[i];
+      }
     }
   };
   auto a_unit = [&](int kt, auto slot_tag) __attribute__((always_inline)) {
@@ -578,7 +641,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     fence();
     // B(kt+2) goes into A(kt)'s slot, one load after each MFMA pair
     mma_pair(I1{}, J0{}, full_tag);
-    if (more) b_part(kt + 2, SA{}, J0{});
+    if (more) { apply_tok(); b_part(kt + 2, SA{}, J0{}); }
     fence();
     mma_pair(I1{}, J1{}, full_tag);
     if (more) b_part(kt + 2, SA{}, J1{});
@@ -588,18 +651,32 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     fence();
     mma_pair(I1{}, J3{}, full_tag);
     if (more) { b_part(kt + 2, SA{}, J3{}); b_end(kt + 2); }
+    if constexpr (GATHER_B) {
+      // a whole step ahead of their use; the next step's wait for B(kt+2) covers them (they are older
+      // than the loads of A(kt+3), the only ones that wait leaves in flight)
+      if (kt + 3 < nk) fetch_tok(kt + 3);
+    }
     fence();
   };
   auto main_loop = [&](auto full_tag) __attribute__((always_inline)) {
     if (nk > 0) {
+      fetch_tok(0);
       a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
+      if constexpr (GATHER_B) wait_vm<4>();   // the tokens are older than the four loads of A(0)
+      apply_tok();
       b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
       if (nk > 1) {
+        fetch_tok(1);
         a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
+        if constexpr (GATHER_B) wait_vm<4>();
+        apply_tok();
         b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
       }
       if (nk > 1) wait_vm<8>(); else wait_vm<0>();
       wg_barrier();
+      if constexpr (GATHER_B) {
+        if (nk > 2) fetch_tok(2);
+      }
       read_frags(std::integral_constant<int, slot_of_a(0)>{}, std::integral_constant<int, slot_of_b(0)>{}, I0{}, I0{}, full_tag);
     }
     for (int kt = 0; kt < nk; kt += NSLOT) {
@@ -745,7 +822,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
           put_quad(i * 32 + lrow, j * 4 + q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
     __builtin_amdgcn_wave_barrier();
     uint16_t* out = ae->O0;
-    if constexpr (MODE == WGRAD) out += static_cast<size_t>(e) * ae->M * ae->N;
+    if constexpr (is_wgrad(MODE)) out += static_cast<size_t>(e) * ae->M * ae->N;
     flush(out, ae->N, grow0, 128, 0, 8, gcol0, ae->N);
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's staging reads are done
@@ -809,9 +886,11 @@ extern "C" size_t moe_workspace_bytes(int T, int E, int k, int d, int f) {
   return p > b ? p : b;
 }
 
-extern "C" int moe_grouped_gemm_fwd(const moe_bf16* xp, const int32_t* expert_offsets, const moe_bf16* Wg,
-                                    const moe_bf16* Wu, const moe_bf16* Wd, int E, int R_cap, int d, int f,
-                                    moe_bf16* g, moe_bf16* u, moe_bf16* h, moe_bf16* yp, void* stream) {
+namespace {
+// xp grouped rows, or (row_token not null) the token rows themselves, gathered by the GEMM's loads
+int gemm_fwd(const moe_bf16* xp, const int32_t* row_token, const int32_t* expert_offsets, const moe_bf16* Wg,
+             const moe_bf16* Wu, const moe_bf16* Wd, int E, int R_cap, int d, int f, moe_bf16* g, moe_bf16* u,
+             moe_bf16* h, moe_bf16* yp, void* stream) {
   if (!xp || !expert_offsets || !Wg || !Wu || !Wd || !g || !u || !h || !yp) return MOE_ERR_INVALID;
   if (bad_gemm_dims(E, R_cap, d, f)) return MOE_ERR_INVALID;
   const void* ptrs[] = {xp, expert_offsets, Wg, Wu, Wd, g, u, h, yp};
@@ -820,7 +899,7 @@ extern "C" int moe_grouped_gemm_fwd(const moe_bf16* xp, const int32_t* expert_of
   const int m_tiles = R_cap / BM + E;
 
   GemmArgs a{};
-  a.offsets = expert_offsets; a.E = E; a.m_tiles_cap = m_tiles;
+  a.offsets = expert_offsets; a.E = E; a.m_tiles_cap = m_tiles; a.row_token = row_token;
   // gate | up with the SwiGLU epilogue
   a.A0 = U16(xp); a.B0 = U16(Wg); a.B1 = U16(Wu); a.O0 = g; a.O1 = u; a.O2 = h;
   a.K = d; a.N = f; a.n_tiles = (f + BN / 2 - 1) / (BN / 2);
@@ -834,11 +913,34 @@ extern "C" int moe_grouped_gemm_fwd(const moe_bf16* xp, const int32_t* expert_of
   return launch_gemm<DOWN>(b, static_cast<long long>(b.n_tiles) * m_tiles, s, "gemm_down");
 }
 
-extern "C" int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, const moe_bf16* g, const moe_bf16* u,
-                                    const moe_bf16* h, const int32_t* expert_offsets, const moe_bf16* Wg,
+// byte offsets of gathered rows are 32-bit lane offsets from the start of x
+bool bad_gather(const moe_bf16* x, int T, const int32_t* row_token, int width) {
+  return !x || !row_token || T <= 0 || !moe_aligned16(row_token) ||
+         static_cast<unsigned long long>(T) * width * sizeof(moe_bf16) > 0xFFFFFFFFull;
+}
+}  // namespace
+
+extern "C" int moe_grouped_gemm_fwd(const moe_bf16* xp, const int32_t* expert_offsets, const moe_bf16* Wg,
                                     const moe_bf16* Wu, const moe_bf16* Wd, int E, int R_cap, int d, int f,
-                                    moe_bf16* dxp, moe_bf16* dWg, moe_bf16* dWu, moe_bf16* dWd, void* ws,
-                                    size_t ws_bytes, void* stream) {
+                                    moe_bf16* g, moe_bf16* u, moe_bf16* h, moe_bf16* yp, void* stream) {
+  return gemm_fwd(xp, nullptr, expert_offsets, Wg, Wu, Wd, E, R_cap, d, f, g, u, h, yp, stream);
+}
+
+extern "C" int moe_grouped_gemm_fwd_gather(const moe_bf16* x, int T, const int32_t* row_token,
+                                           const int32_t* expert_offsets, const moe_bf16* Wg, const moe_bf16* Wu,
+                                           const moe_bf16* Wd, int E, int R_cap, int d, int f, moe_bf16* g,
+                                           moe_bf16* u, moe_bf16* h, moe_bf16* yp, void* stream) {
+  if (bad_gather(x, T, row_token, d)) return MOE_ERR_INVALID;
+  return gemm_fwd(x, row_token, expert_offsets, Wg, Wu, Wd, E, R_cap, d, f, g, u, h, yp, stream);
+}
+
+namespace {
+// xp grouped rows, or (row_token not null) the token rows themselves, gathered by the loads of the
+// two weight-gradient products that read them
+int gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, const int32_t* row_token, const moe_bf16* g, const moe_bf16* u,
+             const moe_bf16* h, const int32_t* expert_offsets, const moe_bf16* Wg, const moe_bf16* Wu,
+             const moe_bf16* Wd, int E, int R_cap, int d, int f, moe_bf16* dxp, moe_bf16* dWg, moe_bf16* dWu,
+             moe_bf16* dWd, void* ws, size_t ws_bytes, void* stream) {
   if (!dyp || !xp || !g || !u || !h || !expert_offsets || !Wg || !Wu || !Wd || !dxp || !dWg || !dWu || !dWd || !ws)
     return MOE_ERR_INVALID;
   if (bad_gemm_dims(E, R_cap, d, f)) return MOE_ERR_INVALID;
@@ -858,17 +960,23 @@ extern "C" int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, con
   int rc = launch_gemm<DGRAD_H>(a, static_cast<long long>(a.n_tiles) * m_tiles, s, "gemm_dgrad_h");
   if (rc != MOE_OK) return rc;
   // weight gradients: dWg = dg^T xp ; dWu = du^T xp (dg, du still warm) ; dWd = dyp^T h
-  struct W { const uint16_t* A; const uint16_t* B; uint16_t* O; int M, N; const char* name; };
-  const W jobs[3] = {{dg, U16(xp), dWg, f, d, "gemm_wgrad_gate"},
-                     {du, U16(xp), dWu, f, d, "gemm_wgrad_up"},
-                     {U16(dyp), U16(h), dWd, d, f, "gemm_wgrad_down"}};
+  struct W { const uint16_t* A; const uint16_t* B; uint16_t* O; int M, N; bool gather; const char* name; };
+  const W jobs[3] = {{dg, U16(xp), dWg, f, d, row_token != nullptr, "gemm_wgrad_gate"},
+                     {du, U16(xp), dWu, f, d, row_token != nullptr, "gemm_wgrad_up"},
+                     {U16(dyp), U16(h), dWd, d, f, false, "gemm_wgrad_down"}};
   for (const W& j : jobs) {
     GemmArgs w{};
     w.offsets = expert_offsets; w.E = E;
     w.A0 = j.A; w.B0 = j.B; w.O0 = j.O; w.M = j.M; w.N = j.N;
     w.n_tiles = (j.N + BN - 1) / BN;
     w.m_tiles_cap = (j.M + BM - 1) / BM;   // row tiles of one expert's dW
-    rc = launch_gemm<WGRAD>(w, static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E, s, j.name);
+    const long long tiles = static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E;
+    if (j.gather) {
+      w.row_token = row_token;
+      rc = launch_gemm<WGRAD_GATHER>(w, tiles, s, j.name);
+    } else {
+      rc = launch_gemm<WGRAD>(w, tiles, s, j.name);
+    }
     if (rc != MOE_OK) return rc;
   }
   // dxp = dg . Wg + du . Wu  (last, so that the dx reduction that follows finds dxp in the last-level cache)
@@ -877,4 +985,25 @@ extern "C" int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, con
   b.A0 = dg; b.A1 = du; b.B0 = U16(Wg); b.B1 = U16(Wu); b.O0 = dxp;
   b.K = f; b.N = d; b.n_tiles = (d + BN - 1) / BN;
   return launch_gemm<DGRAD_X>(b, static_cast<long long>(b.n_tiles) * m_tiles, s, "gemm_dgrad_x");
+}
+}  // namespace
+
+extern "C" int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, const moe_bf16* g, const moe_bf16* u,
+                                    const moe_bf16* h, const int32_t* expert_offsets, const moe_bf16* Wg,
+                                    const moe_bf16* Wu, const moe_bf16* Wd, int E, int R_cap, int d, int f,
+                                    moe_bf16* dxp, moe_bf16* dWg, moe_bf16* dWu, moe_bf16* dWd, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  return gemm_bwd(dyp, xp, nullptr, g, u, h, expert_offsets, Wg, Wu, Wd, E, R_cap, d, f, dxp, dWg, dWu, dWd, ws,
+                  ws_bytes, stream);
+}
+
+extern "C" int moe_grouped_gemm_bwd_gather(const moe_bf16* dyp, const moe_bf16* x, int T, const int32_t* row_token,
+                                           const moe_bf16* g, const moe_bf16* u, const moe_bf16* h,
+                                           const int32_t* expert_offsets, const moe_bf16* Wg, const moe_bf16* Wu,
+                                           const moe_bf16* Wd, int E, int R_cap, int d, int f, moe_bf16* dxp,
+                                           moe_bf16* dWg, moe_bf16* dWu, moe_bf16* dWd, void* ws, size_t ws_bytes,
+                                           void* stream) {
+  if (bad_gather(x, T, row_token, d)) return MOE_ERR_INVALID;
+  return gemm_bwd(dyp, x, row_token, g, u, h, expert_offsets, Wg, Wu, Wd, E, R_cap, d, f, dxp, dWg, dWu, dWd, ws,
+                  ws_bytes, stream);
 }

@@ -226,11 +226,12 @@ extern "C" size_t moe_permute_workspace_bytes(int T, int k, int e_count) {
 extern "C" int moe_permute(const moe_bf16* x, const int32_t* topk_idx, int T, int d, int E_total, int k, int e_begin,
                            int e_count, int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row, moe_bf16* xp,
                            void* ws, size_t ws_bytes, void* stream) {
-  if (!x || !topk_idx || !expert_offsets || !row_token || !slot_row || !xp || !ws) return MOE_ERR_INVALID;
+  // xp == NULL: index generation only (for callers that let the GEMMs gather the rows); x is not read then
+  if (!topk_idx || !expert_offsets || !row_token || !slot_row || !ws || (xp && !x)) return MOE_ERR_INVALID;
   if (T <= 0 || d <= 0 || d % 8 != 0 || E_total <= 0 || k <= 0 || k > E_total) return MOE_ERR_INVALID;
   if (e_begin < 0 || e_count <= 0 || e_begin + e_count > E_total || e_count > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
   if (static_cast<long long>(T) * k > 0x7FFFFFFFll / 2) return MOE_ERR_INVALID;
-  if (!moe_aligned16(x) || !moe_aligned16(xp) || !moe_aligned16(ws) || !moe_aligned16(topk_idx) ||
+  if ((xp && (!moe_aligned16(x) || !moe_aligned16(xp))) || !moe_aligned16(ws) || !moe_aligned16(topk_idx) ||
       !moe_aligned16(slot_row) || !moe_aligned16(row_token) || !moe_aligned16(expert_offsets))
     return MOE_ERR_INVALID;
   if (ws_bytes < moe_permute_workspace_bytes(T, k, e_count)) return MOE_ERR_WORKSPACE;
@@ -244,6 +245,7 @@ extern "C" int moe_permute(const moe_bf16* x, const int32_t* topk_idx, int T, in
   MOE_LAUNCH("permute_scan", permute_scan_kernel, dim3(1), dim3(1024), 0, s, block_hist, e_count, nb, expert_offsets);
   MOE_LAUNCH("permute_place", permute_place_kernel, dim3(nb), dim3(PERM_THREADS), 0, s, topk_idx, n, k, e_begin,
              e_count, nbits, nb, static_cast<const int32_t*>(block_hist), row_token, slot_row);
+  if (!xp) return moe_check_launch();
   const int chunks = d / 8;
   dim3 grid((T + 3) / 4), block(256);
   const uint4* xs = reinterpret_cast<const uint4*>(x);

@@ -207,6 +207,32 @@ def test_layer_ragged_shapes(T, d, E, k, f, eb, ec, renorm):
     H.compare_layer(res, ref, ec)
 
 
+@pytest.mark.parametrize("T,d,E,k,f,eb,ec,renorm", [
+    (256, 128, 8, 2, 256, 0, 8, 1),       # the tiny config's shape
+    (700, 192, 6, 3, 320, 0, 6, 1),       # ragged in every dimension
+    (2048, 256, 16, 4, 128, 4, 8, 0),     # expert-parallel share
+    (1500, 128, 4, 2, 64, 0, 4, 1),       # several row tiles and several reduction steps per expert
+    (64, 64, 300, 9, 64, 100, 150, 1),    # most experts empty, experts with a single row
+    (3000, 512, 3, 1, 192, 0, 3, 1),      # about 1000 rows per expert: many reduction steps in the weight gradients
+])
+def test_layer_gathered_rows(T, d, E, k, f, eb, ec, renorm):
+    """The products that read x through row_token instead of a materialised xp: against the oracle,
+    and bit for bit against the xp path (same operands, same order of arithmetic)."""
+    print(f"gathered layer T={T} d={d} E={E} k={k} f={f} local=[{eb},{eb+ec}) renorm={renorm}", flush=True)
+    cfg = W.MoEConfig("custom", T=T, d=d, E=E, k=k, f=f, e_begin=eb, e_count=ec, renormalize=renorm, seed=T + 1)
+    inp = W.make_inputs(cfg)
+    res = H.run_layer(cfg, inp, gather=True)
+    assert "xp" not in res
+    ref = O.layer_fwd_bwd(inp, k, eb, ec, renorm)
+    H.compare_layer(res, ref, ec)
+    plain = H.run_layer(cfg, inp)
+    R = int(ref["expert_offsets"][-1])
+    for n in ("g", "u", "h", "yp", "dyp", "dxp"):
+        assert np.array_equal(res[n][:R], plain[n][:R]), n
+    for n in ("out", "dx", "dgate", "dWg", "dWu", "dWd"):
+        assert np.array_equal(res[n], plain[n]), n
+
+
 # ----------------------------------------------------------------------------- router and Stage-1 backward
 @pytest.mark.parametrize("T,d,E", [(256, 128, 8), (1000, 2048, 64), (77, 64, 100), (33, 48, 5), (4096, 256, 300)])
 def test_router_fwd(T, d, E):
@@ -336,6 +362,13 @@ def test_argument_checks():
                            B._p(x), 0, None) == -2
     assert lib.moe_grouped_gemm_fwd(B._p(x), B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 60, 64,
                                     B._p(x), B._p(x), B._p(x), B._p(x), None) == -1
+    # gathered products: x, T and row_token are required
+    assert lib.moe_grouped_gemm_fwd_gather(None, 64, B._p(idx), B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 64, 64,
+                                           B._p(x), B._p(x), B._p(x), B._p(x), None) == -1
+    assert lib.moe_grouped_gemm_fwd_gather(B._p(x), 0, B._p(idx), B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 64, 64,
+                                           B._p(x), B._p(x), B._p(x), B._p(x), None) == -1
+    assert lib.moe_grouped_gemm_fwd_gather(B._p(x), 64, None, B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 64, 64,
+                                           B._p(x), B._p(x), B._p(x), B._p(x), None) == -1
     # router entry points: d must be a multiple of 16, the workspace large enough, pointers aligned
     Wr = torch.zeros(8, 64, dtype=torch.float32, device=DEV)
     lg = torch.zeros(64, 8, dtype=torch.float32, device=DEV)
