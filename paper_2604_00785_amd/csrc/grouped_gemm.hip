@@ -263,6 +263,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   nfa = nfa < 0 ? 0 : (nfa > 4 ? 4 : nfa);
   nfa = __builtin_amdgcn_readfirstlane(nfa);
 
+  // The 32 tile rows this wave loads of every activation tile (rows 32 * wave ..) are one fragment of
+  // some wave; if none of them is a valid row nobody reads them, and the wave skips those loads
+  // (a row tile with few rows is bound by its loads, not by its MFMAs).
+  bool a_live = true;
+  if constexpr (!is_wgrad(MODE)) a_live = wave * 32 < m_end - m0;
+
   constexpr bool A_KN = is_wgrad(MODE);                                       // stored [k][m]
   constexpr bool B_KN = (is_wgrad(MODE) || MODE == DGRAD_H || MODE == DGRAD_X);  // stored [k][n]
 
@@ -611,27 +617,28 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     using NB = std::integral_constant<int, slot_of_b((P + 1) % NSLOT)>;
     using LA = std::integral_constant<int, slot_of_a((P + 2) % NSLOT)>;   // where A(kt+2) goes: B(kt-1)'s slot
     const bool more = kt + 2 < nk;
+    const bool more_a = more && a_live;
     read_frags(SA{}, SB{}, I1{}, I1{}, full_tag);
     lds_wait<nreads(decltype(full_tag)::value)>();  fence();
     mma_pair(I0{}, J0{}, full_tag);  mma_pair(I0{}, J1{}, full_tag);
-    if (more) a_part(kt + 2, LA{}, J0{});
+    if (more_a) a_part(kt + 2, LA{}, J0{});
     fence();
     mma_pair(I0{}, J2{}, full_tag);  mma_pair(I0{}, J3{}, full_tag);
-    if (more) a_part(kt + 2, LA{}, J1{});
+    if (more_a) a_part(kt + 2, LA{}, J1{});
     fence();
     read_frags(SA{}, SB{}, I2{}, I0{}, full_tag);
     lds_wait<nreads(decltype(full_tag)::value)>();  fence();
     mma_pair(I1{}, J0{}, full_tag);  mma_pair(I1{}, J1{}, full_tag);
-    if (more) a_part(kt + 2, LA{}, J2{});
+    if (more_a) a_part(kt + 2, LA{}, J2{});
     fence();
     mma_pair(I1{}, J2{}, full_tag);  mma_pair(I1{}, J3{}, full_tag);
-    if (more) { a_part(kt + 2, LA{}, J3{}); a_end(kt + 2); }
+    if (more_a) { a_part(kt + 2, LA{}, J3{}); a_end(kt + 2); }
     fence();
     read_frags(SA{}, SB{}, I3{}, I1{}, full_tag);
     lds_wait<nreads(decltype(full_tag)::value)>();  fence();
     mma(I0{}, full_tag);  fence();
     if (kt + 1 < nk) {
-      if (more) wait_vm<4>(); else wait_vm<0>();
+      if (more_a) wait_vm<4>(); else wait_vm<0>();   // this wave's loads of A(kt+2), if it has any, may stay in flight
       lds_wait<0>();
       wg_barrier();
       read_frags(NA{}, NB{}, I0{}, I0{}, full_tag);
@@ -661,18 +668,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   auto main_loop = [&](auto full_tag) __attribute__((always_inline)) {
     if (nk > 0) {
       fetch_tok(0);
-      a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
+      if (a_live) a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
       if constexpr (GATHER_B) wait_vm<4>();   // the tokens are older than the four loads of A(0)
       apply_tok();
       b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
       if (nk > 1) {
         fetch_tok(1);
-        a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
+        if (a_live) a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
         if constexpr (GATHER_B) wait_vm<4>();
         apply_tok();
         b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
       }
-      if (nk > 1) wait_vm<8>(); else wait_vm<0>();
+      if (nk > 1 && a_live) wait_vm<8>(); else if (nk > 1) wait_vm<4>(); else wait_vm<0>();
       wg_barrier();
       if constexpr (GATHER_B) {
         if (nk > 2) fetch_tok(2);
