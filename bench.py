@@ -209,7 +209,7 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
-    # ---- the router and the Stage-1 backward (rows "next" of the scope table): timed apart, not in `value`
+    # ---- the router and the backward of Stage 1 (they make the layer a drop-in block): timed apart, not in `value`
     if "Wr" in inp:
         Wr = torch.from_numpy(inp["Wr"]).to(dev)
         lg = torch.empty_like(logits)

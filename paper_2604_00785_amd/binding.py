@@ -316,7 +316,10 @@ class MoELayerBuffers:
     def __init__(self, T: int, d: int, E: int, k: int, f: int, e_begin: int = 0, e_count: int = -1,
                  renormalize: int = 1, device="cuda:0", gather: bool = False):
         self.T, self.d, self.E, self.k, self.f = T, d, E, k, f
-        self.gather = gather     # True: no xp; the gate/up product and two weight gradients read x through row_token
+        # True: no xp; the gate/up product and two weight gradients read x through row_token
+        # (32-bit row offsets: x must stay under 4 GiB, else xp is materialised after all)
+        gather = gather and T * d * 2 <= 0xFFFFFFFF
+        self.gather = gather
         self.e_begin = e_begin
         self.e_count = E if e_count < 0 else e_count
         self.renormalize = renormalize
