@@ -37,84 +37,111 @@ __device__ __forceinline__ void split3(const float (&w)[8], bf16x8_t& hi, bf16x8
   }
 }
 
-constexpr int RF_WAVES = 4;   // waves per workgroup: they share one 32x32 block and split the reduction
+constexpr int RF_WAVES = 8;   // waves per workgroup: they share one block of logits and split the reduction
+constexpr int RF_UNROLL = 2;  // reduction steps whose loads a wave has in flight together
+constexpr int RF_TB = 2;      // 32-token blocks per workgroup: a weight fragment is split once and used for both
 
 __global__ __launch_bounds__(64 * RF_WAVES) void router_fwd_kernel(const uint16_t* __restrict__ x,
                                                                    const float* __restrict__ Wr, int T, int d,
                                                                    int E, float* __restrict__ logits) {
-  __shared__ float s_part[RF_WAVES - 1][16][64];
+  __shared__ float s_part[RF_WAVES - 1][RF_TB * 16][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int e_blocks = (E + 31) / 32;
-  const int t0 = (blockIdx.x / e_blocks) * 32, e0 = (blockIdx.x % e_blocks) * 32;
+  const int t0 = (blockIdx.x / e_blocks) * (32 * RF_TB), e0 = (blockIdx.x % e_blocks) * 32;
   const int lrow = lane & 31, lgrp = lane >> 5;
-  int tr = t0 + lrow;  if (tr > T - 1) tr = T - 1;     // rows past the end shadow the last one
-  int er = e0 + lrow;  if (er > E - 1) er = E - 1;
-  const uint16_t* xa = x + static_cast<size_t>(tr) * d + lgrp * 8;
+  int er = e0 + lrow;  if (er > E - 1) er = E - 1;     // rows past the end shadow the last one
   const float* wb = Wr + static_cast<size_t>(er) * d + lgrp * 8;
-  // three independent accumulation chains (one per weight term), so that consecutive MFMAs do not
-  // wait for each other; wave w takes the 16-wide reduction steps w, w+4, w+8, ...
-  f32x16_t acc_hi, acc_mid, acc_lo;
+  const uint16_t* xa[RF_TB];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) { acc_hi[r] = 0.f; acc_mid[r] = 0.f; acc_lo[r] = 0.f; }
+  for (int b = 0; b < RF_TB; ++b) {
+    int tr = t0 + b * 32 + lrow;  if (tr > T - 1) tr = T - 1;
+    xa[b] = x + static_cast<size_t>(tr) * d + lgrp * 8;
+  }
+  // Three independent accumulation chains per token block (one per weight term), so that consecutive
+  // MFMAs do not wait for each other.  Wave w takes a contiguous eighth of the 16-wide reduction
+  // steps.  The kernel is bound by what it pulls through the L2: the weights are read once per
+  // workgroup, so a workgroup covers two token blocks with each weight fragment it loads and splits.
+  f32x16_t acc[RF_TB][3];
+#pragma unroll
+  for (int b = 0; b < RF_TB; ++b)
+#pragma unroll
+    for (int m = 0; m < 3; ++m)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[b][m][r] = 0.f;
   const int nsteps = d / 16;
-  int st = wave;
-  for (; st + RF_WAVES < nsteps; st += 2 * RF_WAVES) {   // two steps per trip: four loads in flight per operand
-    const int k0 = st * 16, k1 = (st + RF_WAVES) * 16;
-    const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(xa + k0);
-    const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(xa + k1);
-    const f32x4 w00 = *reinterpret_cast<const f32x4*>(wb + k0), w01 = *reinterpret_cast<const f32x4*>(wb + k0 + 4);
-    const f32x4 w10 = *reinterpret_cast<const f32x4*>(wb + k1), w11 = *reinterpret_cast<const f32x4*>(wb + k1 + 4);
-    const float wa[8] = {w00[0], w00[1], w00[2], w00[3], w01[0], w01[1], w01[2], w01[3]};
-    const float wc[8] = {w10[0], w10[1], w10[2], w10[3], w11[0], w11[1], w11[2], w11[3]};
+  auto mma = [&](const bf16x8_t (&a)[RF_TB], const f32x4& w0, const f32x4& w1) __attribute__((always_inline)) {
+    const float wa[8] = {w0[0], w0[1], w0[2], w0[3], w1[0], w1[1], w1[2], w1[3]};
     bf16x8_t hi, mid, lo;
     split3(wa, hi, mid, lo);
     // operand order (weights, activations) gives a lane 4 consecutive experts of one token
-    acc_lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, a0, acc_lo, 0, 0, 0);
-    acc_mid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mid, a0, acc_mid, 0, 0, 0);
-    acc_hi = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, a0, acc_hi, 0, 0, 0);
-    split3(wc, hi, mid, lo);
-    acc_lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, a1, acc_lo, 0, 0, 0);
-    acc_mid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mid, a1, acc_mid, 0, 0, 0);
-    acc_hi = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, a1, acc_hi, 0, 0, 0);
-  }
-  for (; st < nsteps; st += RF_WAVES) {
-    const int k0 = st * 16;
-    const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(xa + k0);
-    const f32x4 w00 = *reinterpret_cast<const f32x4*>(wb + k0), w01 = *reinterpret_cast<const f32x4*>(wb + k0 + 4);
-    const float wa[8] = {w00[0], w00[1], w00[2], w00[3], w01[0], w01[1], w01[2], w01[3]};
-    bf16x8_t hi, mid, lo;
-    split3(wa, hi, mid, lo);
-    acc_lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, a0, acc_lo, 0, 0, 0);
-    acc_mid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mid, a0, acc_mid, 0, 0, 0);
-    acc_hi = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, a0, acc_hi, 0, 0, 0);
-  }
-  f32x16_t acc;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = (acc_lo[r] + acc_mid[r]) + acc_hi[r];   // smallest terms first
-  // the four partial sums are added in wave order
+    for (int b = 0; b < RF_TB; ++b) {
+      acc[b][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, a[b], acc[b][0], 0, 0, 0);
+      acc[b][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mid, a[b], acc[b][1], 0, 0, 0);
+      acc[b][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, a[b], acc[b][2], 0, 0, 0);
+    }
+  };
+  const int per_wave = (nsteps + RF_WAVES - 1) / RF_WAVES;
+  int st = wave * per_wave;
+  const int st_end = min(nsteps, st + per_wave);
+  for (; st + RF_UNROLL <= st_end; st += RF_UNROLL) {
+    bf16x8_t a[RF_UNROLL][RF_TB];
+    f32x4 w0[RF_UNROLL], w1[RF_UNROLL];
+#pragma unroll
+    for (int u = 0; u < RF_UNROLL; ++u) {
+      const int k = (st + u) * 16;
+#pragma unroll
+      for (int b = 0; b < RF_TB; ++b) a[u][b] = *reinterpret_cast<const bf16x8_t*>(xa[b] + k);
+      w0[u] = *reinterpret_cast<const f32x4*>(wb + k);
+      w1[u] = *reinterpret_cast<const f32x4*>(wb + k + 4);
+    }
+#pragma unroll
+    for (int u = 0; u < RF_UNROLL; ++u) mma(a[u], w0[u], w1[u]);
+  }
+  for (; st < st_end; ++st) {
+    const int k = st * 16;
+    bf16x8_t a[RF_TB];
+#pragma unroll
+    for (int b = 0; b < RF_TB; ++b) a[b] = *reinterpret_cast<const bf16x8_t*>(xa[b] + k);
+    const f32x4 w0 = *reinterpret_cast<const f32x4*>(wb + k), w1 = *reinterpret_cast<const f32x4*>(wb + k + 4);
+    mma(a, w0, w1);
+  }
+  f32x16_t sum[RF_TB];
+#pragma unroll
+  for (int b = 0; b < RF_TB; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum[b][r] = (acc[b][0][r] + acc[b][1][r]) + acc[b][2][r];   // smallest terms first
+  // the partial sums of the waves are added in wave order
   if (wave > 0) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s_part[wave - 1][r][lane] = acc[r];
+    for (int b = 0; b < RF_TB; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_part[wave - 1][b * 16 + r][lane] = sum[b][r];
   }
   __syncthreads();
   if (wave != 0) return;
 #pragma unroll
   for (int w = 0; w < RF_WAVES - 1; ++w)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] += s_part[w][r][lane];
-  // acc[4q+c] = (token t0 + lrow, expert e0 + q*8 + lgrp*4 + c)
-  const int t = t0 + lrow;
-  if (t < T) {
+    for (int b = 0; b < RF_TB; ++b)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int e = e0 + q * 8 + lgrp * 4;
-      float* o = logits + static_cast<size_t>(t) * E + e;
-      if (e + 3 < E && (E & 3) == 0) {
-        *reinterpret_cast<f32x4*>(o) = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-      } else {
+      for (int r = 0; r < 16; ++r) sum[b][r] += s_part[w][b * 16 + r][lane];
+  // sum[b][4q+c] = (token t0 + 32 b + lrow, expert e0 + q*8 + lgrp*4 + c)
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (e + c < E) o[c] = acc[4 * q + c];
+  for (int b = 0; b < RF_TB; ++b) {
+    const int t = t0 + b * 32 + lrow;
+    if (t < T) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int e = e0 + q * 8 + lgrp * 4;
+        float* o = logits + static_cast<size_t>(t) * E + e;
+        if (e + 3 < E && (E & 3) == 0) {
+          *reinterpret_cast<f32x4*>(o) = f32x4{sum[b][4 * q], sum[b][4 * q + 1], sum[b][4 * q + 2], sum[b][4 * q + 3]};
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (e + c < E) o[c] = sum[b][4 * q + c];
+        }
       }
     }
   }
@@ -519,7 +546,7 @@ extern "C" int moe_router_fwd(const moe_bf16* x, const float* Wr, int T, int d, 
   if (bad_router_dims(T, d, E)) return MOE_ERR_INVALID;
   if (!moe_aligned16(x) || !moe_aligned16(Wr) || !moe_aligned16(logits)) return MOE_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const long long blocks = static_cast<long long>((T + 31) / 32) * ((E + 31) / 32);
+  const long long blocks = static_cast<long long>((T + 32 * RF_TB - 1) / (32 * RF_TB)) * ((E + 31) / 32);
   dim3 grid(static_cast<unsigned>(blocks)), block(64 * RF_WAVES);
   MOE_LAUNCH("router_fwd", router_fwd_kernel, grid, block, 0, s, x, Wr, T, d, E, logits);
   return moe_check_launch();
