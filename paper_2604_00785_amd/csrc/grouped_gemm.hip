@@ -186,21 +186,31 @@ __device__ __forceinline__ int count_row_tiles(const int32_t* offsets, int E, in
   }
   return __builtin_amdgcn_readfirstlane(total);
 }
-__device__ __forceinline__ void find_row_tile(const int32_t* offsets, int E, int mt, int lane, int& e, int& m0, int& m_end) {
+// Tile number `tile` of a row-grouped product -> expert, first row, column tile.  An expert's tiles are
+// numbered column tile by column tile, its row tiles innermost: the workgroups of an XCD, which take a
+// run of consecutive tiles, then share each weight panel among all row tiles of the expert at the same
+// time, so that it is fetched from memory once (weights are the larger operand and are used by only
+// rows_e / 256 tiles each; activations of a row tile recur every rows_e / 256 tiles).
+__device__ __forceinline__ void find_tile(const int32_t* offsets, int E, int n_tiles, int tile, int lane, int& e, int& m0,
+                                          int& m_end, int& nt) {
   int base = 0;
-  e = 0; m0 = 0; m_end = 0;
+  e = 0; m0 = 0; m_end = 0; nt = 0;
   for (int e0 = 0; e0 < E; e0 += 64) {
     const int ee = e0 + lane;
     const int lo = ee < E ? offsets[ee] : 0;
     const int hi = ee < E ? offsets[ee + 1] : 0;
-    const int tiles = (hi - lo + BM - 1) / BM;
+    const int row_tiles = (hi - lo + BM - 1) / BM;
+    const int tiles = row_tiles * n_tiles;
     const int inc = wave_incl_scan(tiles, lane);
     const int excl = base + inc - tiles;
-    const unsigned long long hit = __ballot(tiles > 0 && excl <= mt && mt < excl + tiles);
+    const unsigned long long hit = __ballot(tiles > 0 && excl <= tile && tile < excl + tiles);
     if (hit) {
       const int l = __ffsll(hit) - 1;
       e = e0 + l;
-      m0 = __shfl(lo, l, 64) + (mt - __shfl(excl, l, 64)) * BM;
+      const int q = tile - __shfl(excl, l, 64);
+      const int rt = __shfl(row_tiles, l, 64);
+      nt = q / rt;
+      m0 = __shfl(lo, l, 64) + (q - nt * rt) * BM;
       m_end = __shfl(hi, l, 64);
       return;
     }
@@ -242,15 +252,16 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   int tid = tid0;
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
-  int e, m0, m_end;
-  const int nt = tile % a.n_tiles;
+  int e, m0, m_end, nt;
   if constexpr (is_wgrad(MODE)) {
+    nt = tile % a.n_tiles;
     const int rest = tile / a.n_tiles;
     e = rest / a.m_tiles_cap;
     m0 = (rest % a.m_tiles_cap) * BM;   // output row of dW
     m_end = a.M;
   } else {
-    find_row_tile(a.offsets, a.E, tile / a.n_tiles, lane, e, m0, m_end);
+    find_tile(a.offsets, a.E, a.n_tiles, tile, lane, e, m0, m_end, nt);
+    nt = __builtin_amdgcn_readfirstlane(nt);
   }
   // tile coordinates are wave-uniform: keep them in scalar registers, so that everything derived
   // from them (operand base addresses in particular) is scalar too
