@@ -38,9 +38,10 @@
 // formulas are applied on the way, on the fp32 accumulators.
 //
 // Tiles of the row-grouped products are found on the device from
-// expert_offsets: every wave turns the M-tile number into (expert, first row)
-// with a wave-wide prefix sum over ceil(rows_e / 256) (no LDS is left for a table); experts
-// without rows own no tile; rows past an expert's end are clamped on load and masked on store.
+// expert_offsets: every wave turns the tile number into (expert, first row, column tile)
+// with a wave-wide prefix sum over ceil(rows_e / 256) * column tiles (no LDS is left for a table);
+// inside an expert the row tiles are innermost; experts without rows own no tile; rows past an
+// expert's end are clamped on load and masked on store.
 #include <type_traits>
 #include "common.h"
 
