@@ -33,3 +33,50 @@ def test_host_only_calls():
     lib = B.load()
     assert lib.moe_route(None, 1, 1, 1, 1, None, None, None) == -1
     assert lib.moe_unpermute_combine(None, None, None, 4, 2, 64, None, None) == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No CPU fallback: without the built library the binding raises, and it refuses host tensors."""
+    import pytest
+    import torch
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libmoe_hotpath_absent.so"))
+    with pytest.raises(B.MoeError):
+        B.load(build_if_missing=False)
+    monkeypatch.undo()
+    logits = torch.zeros(4, 4)
+    idx = torch.zeros(4, 2, dtype=torch.int32)
+    w = torch.zeros(4, 2)
+    with pytest.raises(B.MoeError):
+        B.moe_route(logits, 2, 1, idx, w)
+
+
+def test_host_only_calls_router_and_gather():
+    lib = B.load()
+    assert B.moe_router_bwd_workspace_bytes(8192, 2048, 64) == 32 * 64 * 2048 * 4   # one partial sum per 256 tokens
+    assert B.moe_router_bwd_workspace_bytes(0, 2048, 64) == 0
+    assert lib.moe_router_fwd(None, None, 64, 64, 8, None, None) == -1
+    assert lib.moe_route_bwd(None, None, None, 64, 8, 2, 1, None, None) == -1
+    assert lib.moe_router_bwd(None, None, None, 64, 64, 8, None, None, None, 0, None) == -1
+    assert lib.moe_grouped_gemm_fwd_gather(None, 64, None, None, None, None, None, 1, 64, 64, 64,
+                                           None, None, None, None, None) == -1
+    assert lib.moe_grouped_gemm_bwd_gather(None, None, 64, None, None, None, None, None, None, None, None,
+                                           1, 64, 64, 64, None, None, None, None, None, 0, None) == -1
+
+
+def test_forced_uniform_routing_workload():
+    """The forced-uniform-routing logits give every expert exactly T*k/E rows, slot i of token t on
+    expert (t*k + i) mod E, in decreasing order of the logits."""
+    import numpy as np
+    from oracle import moe_oracle as O
+    from paper_2604_00785_amd import workloads as W
+    T, E, k = 96, 16, 4
+    logits = W.fur_logits(T, E, k)
+    idx, w = O.route(logits, k, 1)
+    want = (np.arange(T)[:, None] * k + np.arange(k)[None, :]) % E
+    assert np.array_equal(idx, want)
+    assert np.all(np.bincount(idx.ravel(), minlength=E) == T * k // E)
+    assert np.all(np.diff(w, axis=1) < 0)
+    for name in ("mula100b_ep12", "mula220b_ep12", "olmoe_fur"):
+        cfg = W.CONFIGS[name]
+        assert cfg.e_begin + cfg.n_local <= cfg.E and cfg.d % 64 == 0 and cfg.f % 64 == 0
