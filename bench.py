@@ -231,10 +231,23 @@ def main():
         torch.cuda.synchronize()
         rp = {n: round(ms / max(c, 1) * 1e3, 2) for n, ms, c in B.moe_prof_read()}
         B.moe_prof_enable(False)
+        # the whole drop-in block (router in front, its backward behind), timed like `value`
+        for _ in range(3):
+            buf.run_block_fwd_bwd(x, Wr, dout, Wg, Wu, Wd)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            buf.run_block_fwd_bwd(x, Wr, dout, Wg, Wu, Wd)
+        torch.cuda.synchronize()
+        block_ms = (time.perf_counter() - t0) / args.steps * 1e3
         line["router_path"] = {"kernels_us": rp, "us_per_step": round(sum(rp.values()), 1),
+                               "block_ms_per_step": round(block_ms, 4),
+                               "block_tokens_per_s": round(cfg.T / (block_ms * 1e-3), 1),
                                "flop_per_step": 6.0 * cfg.T * cfg.E * cfg.d,
                                "note": "router Linear layer, gradient of softmax/top-k/renormalisation, router weight "
-                                       "and input gradients; not part of `value`"}
+                                       "and input gradients, timed apart; block_* = the whole drop-in block "
+                                       "(router + expert path + router backward) timed like `value`; "
+                                       "neither is part of `value`"}
     # ---- what the matrix pipe sustains for operand values like this workload's (the clock follows the
     #      power draw, which follows the data): pure MFMA on register-resident fragments, no memory traffic
     wgs = torch.cuda.get_device_properties(0).multi_processor_count

@@ -366,6 +366,23 @@ class MoELayerBuffers:
         self.run_fwd(x, logits, Wg, Wu, Wd)
         self.run_bwd(dout, Wg, Wu, Wd)
 
+    def run_block_fwd_bwd(self, x, Wr, dout, Wg, Wu, Wd) -> None:
+        """The layer as a drop-in block: the router's Linear layer in front (logits from ``x`` and
+        ``Wr``), and behind the expert path the gradient of the gates pushed back to the logits, to
+        ``dWr`` and into ``dx`` (which then holds the expert path's and the router's share).  The
+        buffers ``logits``, ``dlogits``, ``dWr`` and the router workspace are created on first use."""
+        if getattr(self, "logits", None) is None:
+            dev = x.device
+            self.logits = torch.zeros(self.T, self.E, dtype=torch.float32, device=dev)
+            self.dlogits = torch.zeros(self.T, self.E, dtype=torch.float32, device=dev)
+            self.dWr = torch.zeros(self.E, self.d, dtype=torch.float32, device=dev)
+            self.router_ws = torch.zeros(max(moe_router_bwd_workspace_bytes(self.T, self.d, self.E), 256),
+                                         dtype=torch.uint8, device=dev)
+        moe_router_fwd(x, Wr, self.logits)
+        self.run_fwd_bwd(x, self.logits, dout, Wg, Wu, Wd)
+        moe_route_bwd(self.logits, self.topk_idx, self.dgate, self.renormalize, self.dlogits)
+        moe_router_bwd(x, Wr, self.dlogits, self.dx, self.dWr, self.router_ws)
+
     def capture_fwd_bwd(self, x, logits, dout, Wg, Wu, Wd) -> "torch.cuda.CUDAGraph":
         """Record ``run_fwd_bwd`` on these buffers and arguments into a HIP graph.
 

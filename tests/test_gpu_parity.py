@@ -292,35 +292,34 @@ def test_router_bwd(T, d, E):
     assert torch.equal(dWr, dWr2)
 
 
-def test_drop_in_block_router_to_gradients():
+@pytest.mark.parametrize("gather", [False, True])
+def test_drop_in_block_router_to_gradients(gather):
     """Router -> route on the device's own logits -> ... -> dgate -> dlogits -> dWr, dx: the chain a
     training step runs, against the oracle fed with the same (device) logits."""
     cfg = W.MoEConfig("custom", T=512, d=128, E=16, k=4, f=64, seed=5)
     inp = W.make_inputs(cfg)
-    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f)
+    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, gather=gather)
     x, dout = H.bf16_to_dev(inp["x"]), H.bf16_to_dev(inp["dout"])
     Wg, Wu, Wd = (H.bf16_to_dev(inp[n]) for n in ("Wg", "Wu", "Wd"))
     Wr = torch.from_numpy(inp["Wr"]).to(DEV)
-    logits = torch.zeros(cfg.T, cfg.E, dtype=torch.float32, device=DEV)
-    B.moe_router_fwd(x, Wr, logits)
-    buf.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
-    dl = torch.zeros_like(logits)
-    dWr = torch.zeros_like(Wr)
-    ws = torch.zeros(B.moe_router_bwd_workspace_bytes(cfg.T, cfg.d, cfg.E), dtype=torch.uint8, device=DEV)
-    dx_expert = H.bf16_from_dev(buf.dx)
-    B.moe_route_bwd(logits, buf.topk_idx, buf.dgate, cfg.renormalize, dl)
-    B.moe_router_bwd(x, Wr, dl, buf.dx, dWr, ws)
+    buf.run_block_fwd_bwd(x, Wr, dout, Wg, Wu, Wd)
     torch.cuda.synchronize()
+    dx_block = H.bf16_from_dev(buf.dx)
     inp2 = dict(inp)
-    inp2["logits"] = logits.cpu().numpy()
+    inp2["logits"] = buf.logits.cpu().numpy()
     ref = O.layer_fwd_bwd(inp2, cfg.k, 0, cfg.E, cfg.renormalize)
     assert np.array_equal(buf.topk_idx.cpu().numpy(), ref["topk_idx"])
+    np.testing.assert_allclose(inp2["logits"], O.router_logits(O.decode_bf16(inp["x"]), inp["Wr"]), rtol=0, atol=2e-5)
     rdl = O.route_bwd(inp2["logits"], ref["topk_idx"], ref["dgate"], cfg.renormalize)
     rdWr, rdx = O.router_bwd(O.decode_bf16(inp["x"]), inp["Wr"], rdl)
-    H.assert_close(dl.cpu().numpy().astype(np.float64), rdl, "dlogits")
-    H.assert_close(dWr.cpu().numpy().astype(np.float64), rdWr, "dWr")
-    H.assert_close(H.bf16_from_dev(buf.dx), ref["dx"] + rdx, "dx (expert path + router path)")
-    assert np.abs(H.bf16_from_dev(buf.dx) - dx_expert).max() > 0
+    H.assert_close(buf.dlogits.cpu().numpy().astype(np.float64), rdl, "dlogits")
+    H.assert_close(buf.dWr.cpu().numpy().astype(np.float64), rdWr, "dWr")
+    H.assert_close(dx_block, ref["dx"] + rdx, "dx (expert path + router path)")
+    H.assert_close(H.bf16_from_dev(buf.out), ref["out"], "out")
+    # the router's share is really in dx: the expert path alone leaves something else
+    buf.run_fwd_bwd(x, buf.logits, dout, Wg, Wu, Wd)
+    torch.cuda.synchronize()
+    assert np.abs(dx_block - H.bf16_from_dev(buf.dx)).max() > 0
 
 
 def test_layer_without_local_rows():
