@@ -849,7 +849,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   }  // tile loop
 }
 
-// Workgroups of the persistent launch: one per compute unit (the 128 KB of LDS allow no more),
+// Workgroups of the persistent launch: one per compute unit (the 160 KB of LDS allow no more),
 // a multiple of 8 so that every XCD gets the same share, and no more than there can be tiles.
 int persistent_grid(long long max_tiles) {
   static int cus = 0;
