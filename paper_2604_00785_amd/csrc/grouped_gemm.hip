@@ -192,14 +192,18 @@ __device__ __forceinline__ int count_row_tiles(const int32_t* offsets, int E, in
 // run of consecutive tiles, then share each weight panel among all row tiles of the expert at the same
 // time, so that it is fetched from memory once (weights are the larger operand and are used by only
 // rows_e / 256 tiles each; activations of a row tile recur every rows_e / 256 tiles).
-__device__ __forceinline__ void find_tile(const int32_t* offsets, int E, int n_tiles, int tile, int lane, int& e, int& m0,
-                                          int& m_end, int& nt) {
+// With at most 64 experts the lane's two offsets are read once per kernel (lo0, hi0) instead of once
+// per tile: the lookup then needs no memory access, which would otherwise sit in front of every
+// tile's first loads.
+__device__ __forceinline__ void find_tile(const int32_t* offsets, int E, int lo0, int hi0, int n_tiles, int tile, int lane,
+                                          int& e, int& m0, int& m_end, int& nt) {
   int base = 0;
   e = 0; m0 = 0; m_end = 0; nt = 0;
   for (int e0 = 0; e0 < E; e0 += 64) {
     const int ee = e0 + lane;
-    const int lo = ee < E ? offsets[ee] : 0;
-    const int hi = ee < E ? offsets[ee + 1] : 0;
+    int lo, hi;
+    if (E <= 64) { lo = lo0; hi = hi0; }
+    else { lo = ee < E ? offsets[ee] : 0; hi = ee < E ? offsets[ee + 1] : 0; }
     const int row_tiles = (hi - lo + BM - 1) / BM;
     const int tiles = row_tiles * n_tiles;
     const int inc = wave_incl_scan(tiles, lane);
@@ -242,8 +246,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   // (b % 8) * (gridDim.x / 8) + b / 8 of every round: each XCD then works on a run of
   // consecutive tiles (same expert, neighbouring panels) that share its L2.
   int total;
-  if constexpr (is_wgrad(MODE)) total = a.E * a.m_tiles_cap * a.n_tiles;
-  else total = count_row_tiles(a.offsets, a.E, tid0 & 63) * a.n_tiles;
+  int lo0 = 0, hi0 = 0;   // this lane's expert's row range, kept for the whole kernel when E <= 64
+  if constexpr (is_wgrad(MODE)) {
+    total = a.E * a.m_tiles_cap * a.n_tiles;
+  } else {
+    total = count_row_tiles(a.offsets, a.E, tid0 & 63) * a.n_tiles;
+    if (a.E <= 64 && (tid0 & 63) < a.E) { lo0 = a.offsets[tid0 & 63]; hi0 = a.offsets[(tid0 & 63) + 1]; }
+  }
   const int per_xcd = gridDim.x >> 3;
   const int first_tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
 
@@ -261,7 +270,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     m0 = (rest % a.m_tiles_cap) * BM;   // output row of dW
     m_end = a.M;
   } else {
-    find_tile(a.offsets, a.E, a.n_tiles, tile, lane, e, m0, m_end, nt);
+    find_tile(a.offsets, a.E, lo0, hi0, a.n_tiles, tile, lane, e, m0, m_end, nt);
     nt = __builtin_amdgcn_readfirstlane(nt);
   }
   // tile coordinates are wave-uniform: keep them in scalar registers, so that everything derived
@@ -679,17 +688,28 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   };
   auto main_loop = [&](auto full_tag) __attribute__((always_inline)) {
     if (nk > 0) {
-      fetch_tok(0);
-      if (a_live) a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
-      if constexpr (GATHER_B) wait_vm<4>();   // the tokens are older than the four loads of A(0)
-      apply_tok();
-      b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
-      if (nk > 1) {
-        fetch_tok(1);
-        if (a_live) a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
-        if constexpr (GATHER_B) wait_vm<4>();
+      if constexpr (GATHER_B) {
+        fetch_tok(0);
+        a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
+        wait_vm<4>();   // the tokens are older than the four loads of A(0)
         apply_tok();
-        b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
+        b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
+        if (nk > 1) {
+          fetch_tok(1);
+          a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
+          wait_vm<4>();
+          apply_tok();
+          b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
+        }
+      } else {
+        // the weight tile first: its addresses are ready, while those of the activation tile may still
+        // wait for the tokens of the tile's rows (gathered rows)
+        b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
+        if (a_live) a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
+        if (nk > 1) {
+          b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
+          if (a_live) a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
+        }
       }
       if (nk > 1 && a_live) wait_vm<8>(); else if (nk > 1) wait_vm<4>(); else wait_vm<0>();
       wg_barrier();
