@@ -50,6 +50,7 @@ def kernel_work(cfg, R):
         "permute_count": ("hbm", 4.0 * T * k),
         "permute_scan": ("hbm", 0.0),
         "permute_place": ("hbm", 12.0 * T * k),
+        "dgate_finish": ("hbm", 4.0 * R * (f // 64) + 8.0 * T * k),
     }
 
 
@@ -98,6 +99,10 @@ def main():
     ap.add_argument("--materialize-xp", action="store_true",
                     help="gather the routed rows into xp with a kernel of its own (permute_rows) instead of letting "
                          "the gate/up product and the two weight gradients read x through row_token")
+    ap.add_argument("--no-fold", action="store_true",
+                    help="keep the gate weights in the combine (Stage 5 and its backward as kernels of their own) "
+                         "instead of folding them into h, which takes dgate out of the backward product of the "
+                         "down projection and needs no backward pass over the [R, d] rows")
     ap.add_argument("--graph", action="store_true",
                     help="time the step as one HIP graph replay instead of fifteen stream launches "
                          "(measured: no faster, the launches already queue ahead of the GPU)")
@@ -128,8 +133,9 @@ def main():
     x, dout = up(inp["x"]), up(inp["dout"])
     Wg, Wu, Wd = up(inp["Wg"]), up(inp["Wu"]), up(inp["Wd"])
     logits = torch.from_numpy(inp["logits"]).to(dev)
+    fold = not args.no_fold and not args.materialize_xp and cfg.T * cfg.d * 2 <= 0xFFFFFFFF
     buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.e_begin, cfg.n_local, cfg.renormalize, dev,
-                            gather=not args.materialize_xp)
+                            gather=not args.materialize_xp, fold=fold)
 
     def eager_step():
         buf.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
@@ -202,6 +208,8 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} (local {cfg.n_local}) k={cfg.k} f={cfg.f}",
                    "routed_rows": R, "renormalize": cfg.renormalize,
                    "launch": "hip graph replay" if args.graph else "stream launches",
+                   "gate_weights": "folded into h (dgate from the backward product of the down projection)" if fold
+                                   else "applied by the combine (combine backward as a kernel of its own)",
                    "row_gather": "own kernel (xp materialised)" if args.materialize_xp
                                  else "folded into the loads of the gate/up product and of two weight gradients"},
         "grouped_gemm": {"tflops": round(gemm_tflops, 1), "frac_of_bf16_peak": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),

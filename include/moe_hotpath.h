@@ -168,6 +168,58 @@ int moe_grouped_gemm_bwd_gather(const moe_bf16* dyp, const moe_bf16* x, int T, c
                                 void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The layer with the gate weights folded into the expert MLP (Stages 2-5 and their derivatives give the
+ * same out, dx, dW and dgate; the gate-weighted sum of Stage 5 is linear, so the weight of a routed row
+ * may multiply h instead of the expert's output).  Forward: moe_permute_gate, moe_grouped_gemm_fwd_folded,
+ * moe_unpermute_sum.  Backward: moe_grouped_gemm_bwd_folded, moe_permute_bwd.  The backward then needs
+ * neither yp nor the scaled output gradient dyp[r] = w_r dout[token_r]: no separate pass over [R, d] rows
+ * computes dgate and dyp.
+ *
+ * moe_permute_gate: moe_permute without moving rows, plus the gate weight of every routed row:
+ *   row_weight[slot_row[t, i]] = topk_w[t, i] for every local slot.  topk_w [T, k] fp32 (device),
+ *   row_weight [R_cap] fp32 (device, written for rows below expert_offsets[e_count]); the rest as moe_permute.
+ */
+int moe_permute_gate(const int32_t* topk_idx, const float* topk_w, int T, int E_total, int k, int e_begin, int e_count,
+                     int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row, float* row_weight,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * moe_grouped_gemm_fwd_gather with hw = w_r * silu(g) * u in place of h (w_r = row_weight[r], applied to
+ * the fp32 value before the one rounding to bf16) and therefore ypw = hw . Wd[e]^T = w_r * yp in place of yp.
+ * g and u are as before.  row_weight [R_cap] fp32 (device); the rest as moe_grouped_gemm_fwd_gather.
+ */
+int moe_grouped_gemm_fwd_folded(const moe_bf16* x, int T, const int32_t* row_token, const float* row_weight,
+                                const int32_t* expert_offsets,
+                                const moe_bf16* Wg, const moe_bf16* Wu, const moe_bf16* Wd,
+                                int E, int R_cap, int d, int f,
+                                moe_bf16* g, moe_bf16* u, moe_bf16* hw, moe_bf16* ypw, void* stream);
+
+/* out[t] = sum over local slots i, in slot order, of ypw[slot_row[t, i]] (fp32 sum, rounded once): Stage 5
+ * for rows that already carry their gate weight.  Shapes as moe_unpermute_combine. */
+int moe_unpermute_sum(const moe_bf16* ypw, const int32_t* slot_row, int T, int k, int d, moe_bf16* out, void* stream);
+
+/*
+ * Derivative of Stages 4 and 5 after moe_grouped_gemm_fwd_folded, from dout [T, d] itself.  With
+ * t_r = row_token[r], w_r = row_weight[r], s = sigmoid(g):
+ *   dh0 = dout[t_r] . Wd[e];  dgate[t, i] = sum_c dh0[r, c] * silu(g[r, c]) * u[r, c] for r = slot_row[t, i]
+ *   (0 for a slot without local row; fp32: per 64-column strip in column order, strips added in order);
+ *   dh = w_r * dh0;  dg, du, dxp, dWg, dWu as in moe_grouped_gemm_bwd (rows of x read through row_token);
+ *   dWd[e] = dout[t_r]^T . hw   (rows of dout read through row_token).
+ *   dout, x [T, d] bf16 (T*d*2 bytes at most 4 GiB); slot_row [T, k] int32; g, u, hw [R_cap, f] bf16;
+ *   dgate [T, k] fp32; dxp [R_cap, d]; dWg, dWu [E, f, d]; dWd [E, d, f]; all device memory.
+ *   ws at least moe_grouped_gemm_bwd_folded_workspace_bytes(R_cap, f): dg, du and the strips' partial sums.
+ */
+size_t moe_grouped_gemm_bwd_folded_workspace_bytes(int R_cap, int f);
+int moe_grouped_gemm_bwd_folded(const moe_bf16* dout, const moe_bf16* x, int T, int k,
+                                const int32_t* row_token, const float* row_weight, const int32_t* slot_row,
+                                const moe_bf16* g, const moe_bf16* u, const moe_bf16* hw,
+                                const int32_t* expert_offsets,
+                                const moe_bf16* Wg, const moe_bf16* Wu, const moe_bf16* Wd,
+                                int E, int R_cap, int d, int f,
+                                moe_bf16* dxp, moe_bf16* dWg, moe_bf16* dWu, moe_bf16* dWd, float* dgate,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Stage 5, ExpertOutputReductionForward:
  *   out[t] = sum over local slots i, in slot order, of topk_w[t, i] * yp[slot_row[t, i]]
  * (fp32 sum, rounded once); zeros for a token without local slot.

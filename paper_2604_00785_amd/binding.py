@@ -20,6 +20,8 @@ EXPORTS = [
     "moe_version", "moe_permute_workspace_bytes", "moe_grouped_gemm_bwd_workspace_bytes", "moe_workspace_bytes",
     "moe_route", "moe_permute", "moe_permute_bwd", "moe_grouped_gemm_fwd", "moe_grouped_gemm_bwd",
     "moe_grouped_gemm_fwd_gather", "moe_grouped_gemm_bwd_gather",
+    "moe_permute_gate", "moe_grouped_gemm_fwd_folded", "moe_unpermute_sum",
+    "moe_grouped_gemm_bwd_folded_workspace_bytes", "moe_grouped_gemm_bwd_folded",
     "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_prof_enable", "moe_prof_count", "moe_prof_read", "moe_prof_mfma_ceiling",
     "moe_router_fwd", "moe_route_bwd", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
 ]
@@ -54,6 +56,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.moe_grouped_gemm_bwd_workspace_bytes.argtypes = [c_int] * 2
     lib.moe_workspace_bytes.restype = c_sz
     lib.moe_workspace_bytes.argtypes = [c_int] * 5
+    lib.moe_grouped_gemm_bwd_folded_workspace_bytes.restype = c_sz
+    lib.moe_grouped_gemm_bwd_folded_workspace_bytes.argtypes = [c_int] * 2
     lib.moe_router_bwd_workspace_bytes.restype = c_sz
     lib.moe_router_bwd_workspace_bytes.argtypes = [c_int] * 3
     sigs = {
@@ -64,6 +68,10 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "moe_grouped_gemm_bwd": [vp] * 9 + [c_int] * 4 + [vp] * 4 + [vp, c_sz, vp],
         "moe_grouped_gemm_fwd_gather": [vp, c_int, vp, vp, vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp],
         "moe_grouped_gemm_bwd_gather": [vp, vp, c_int, vp] + [vp] * 7 + [c_int] * 4 + [vp] * 4 + [vp, c_sz, vp],
+        "moe_permute_gate": [vp, vp, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, c_sz, vp],
+        "moe_grouped_gemm_fwd_folded": [vp, c_int, vp, vp, vp, vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp],
+        "moe_unpermute_sum": [vp, vp, c_int, c_int, c_int, vp, vp],
+        "moe_grouped_gemm_bwd_folded": [vp, vp, c_int, c_int, vp, vp, vp] + [vp] * 7 + [c_int] * 4 + [vp] * 5 + [vp, c_sz, vp],
         "moe_unpermute_combine": [vp, vp, vp, c_int, c_int, c_int, vp, vp],
         "moe_unpermute_combine_bwd": [vp, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp],
         "moe_router_fwd": [vp, vp, c_int, c_int, c_int, vp, vp],
@@ -215,6 +223,71 @@ def moe_grouped_gemm_bwd(dyp, xp, g, u, h, expert_offsets, Wg, Wu, Wd, dxp, dWg,
                                        ws.numel() * ws.element_size(), _stream()), "moe_grouped_gemm_bwd")
 
 
+def moe_grouped_gemm_bwd_folded_workspace_bytes(R_cap: int, f: int) -> int:
+    return int(load().moe_grouped_gemm_bwd_folded_workspace_bytes(R_cap, f))
+
+
+def moe_permute_gate(topk_idx, topk_w, E_total: int, e_begin: int, e_count: int,
+                     expert_offsets, row_token, slot_row, row_weight, ws) -> None:
+    T, k = topk_idx.shape
+    _want(topk_idx, torch.int32, (T, k), "topk_idx")
+    _want(topk_w, torch.float32, (T, k), "topk_w")
+    _want(expert_offsets, torch.int32, (e_count + 1,), "expert_offsets")
+    _want(row_token, torch.int32, (T * k,), "row_token")
+    _want(slot_row, torch.int32, (T, k), "slot_row")
+    _want(row_weight, torch.float32, (T * k,), "row_weight")
+    _check(load().moe_permute_gate(_p(topk_idx), _p(topk_w), T, E_total, k, e_begin, e_count, _p(expert_offsets),
+                                   _p(row_token), _p(slot_row), _p(row_weight), _p(ws),
+                                   ws.numel() * ws.element_size(), _stream()), "moe_permute_gate")
+
+
+def moe_grouped_gemm_fwd_folded(x, row_token, row_weight, expert_offsets, Wg, Wu, Wd, g, u, hw, ypw) -> None:
+    T, d = x.shape
+    R_cap = row_token.shape[0]
+    E, f, _ = Wg.shape
+    for n, t, shp in (("x", x, (T, d)), ("Wg", Wg, (E, f, d)), ("Wu", Wu, (E, f, d)), ("Wd", Wd, (E, d, f)),
+                      ("g", g, (R_cap, f)), ("u", u, (R_cap, f)), ("hw", hw, (R_cap, f)), ("ypw", ypw, (R_cap, d))):
+        _want(t, BF16, shp, n)
+    _want(row_token, torch.int32, (R_cap,), "row_token")
+    _want(row_weight, torch.float32, (R_cap,), "row_weight")
+    _want(expert_offsets, torch.int32, (E + 1,), "expert_offsets")
+    _check(load().moe_grouped_gemm_fwd_folded(_p(x), T, _p(row_token), _p(row_weight), _p(expert_offsets), _p(Wg),
+                                              _p(Wu), _p(Wd), E, R_cap, d, f, _p(g), _p(u), _p(hw), _p(ypw),
+                                              _stream()), "moe_grouped_gemm_fwd_folded")
+
+
+def moe_unpermute_sum(ypw, slot_row, out) -> None:
+    T, k = slot_row.shape
+    d = ypw.shape[1]
+    _want(ypw, BF16, name="ypw")
+    _want(slot_row, torch.int32, name="slot_row")
+    _want(out, BF16, (T, d), "out")
+    _check(load().moe_unpermute_sum(_p(ypw), _p(slot_row), T, k, d, _p(out), _stream()), "moe_unpermute_sum")
+
+
+def moe_grouped_gemm_bwd_folded(dout, x, row_token, row_weight, slot_row, g, u, hw, expert_offsets, Wg, Wu, Wd,
+                                dxp, dWg, dWu, dWd, dgate, ws) -> None:
+    T, d = x.shape
+    k = slot_row.shape[1]
+    R_cap = row_token.shape[0]
+    E, f, _ = Wg.shape
+    for n, t, shp in (("dout", dout, (T, d)), ("x", x, (T, d)), ("g", g, (R_cap, f)), ("u", u, (R_cap, f)),
+                      ("hw", hw, (R_cap, f)), ("Wg", Wg, (E, f, d)), ("Wu", Wu, (E, f, d)), ("Wd", Wd, (E, d, f)),
+                      ("dxp", dxp, (R_cap, d)), ("dWg", dWg, (E, f, d)), ("dWu", dWu, (E, f, d)),
+                      ("dWd", dWd, (E, d, f))):
+        _want(t, BF16, shp, n)
+    _want(row_token, torch.int32, (R_cap,), "row_token")
+    _want(row_weight, torch.float32, (R_cap,), "row_weight")
+    _want(slot_row, torch.int32, (T, k), "slot_row")
+    _want(dgate, torch.float32, (T, k), "dgate")
+    _want(expert_offsets, torch.int32, (E + 1,), "expert_offsets")
+    _check(load().moe_grouped_gemm_bwd_folded(_p(dout), _p(x), T, k, _p(row_token), _p(row_weight), _p(slot_row),
+                                              _p(g), _p(u), _p(hw), _p(expert_offsets), _p(Wg), _p(Wu), _p(Wd), E,
+                                              R_cap, d, f, _p(dxp), _p(dWg), _p(dWu), _p(dWd), _p(dgate), _p(ws),
+                                              ws.numel() * ws.element_size(), _stream()),
+           "moe_grouped_gemm_bwd_folded")
+
+
 def moe_unpermute_combine(yp, slot_row, topk_w, out) -> None:
     T, k = slot_row.shape
     d = yp.shape[1]
@@ -314,8 +387,14 @@ class MoELayerBuffers:
     """
 
     def __init__(self, T: int, d: int, E: int, k: int, f: int, e_begin: int = 0, e_count: int = -1,
-                 renormalize: int = 1, device="cuda:0", gather: bool = False):
+                 renormalize: int = 1, device="cuda:0", gather: bool = False, fold: bool = False):
         self.T, self.d, self.E, self.k, self.f = T, d, E, k, f
+        # fold: the gate weights are folded into h (``h`` and ``yp`` then hold hw and ypw, there is no dyp and
+        # no separate backward of the combine); rows are gathered by the products, as with ``gather``
+        if fold and T * d * 2 > 0xFFFFFFFF:
+            raise MoeError("fold=True needs x under 4 GiB (32-bit row offsets)")
+        self.fold = fold
+        gather = gather or fold
         # True: no xp; the gate/up product and two weight gradients read x through row_token
         # (32-bit row offsets: x must stay under 4 GiB, else xp is materialised after all)
         gather = gather and T * d * 2 <= 0xFFFFFFFF
@@ -332,16 +411,27 @@ class MoELayerBuffers:
         self.row_token = z(R, dt=torch.int32)
         self.slot_row = z(T, k, dt=torch.int32)
         self.xp = None if gather else z(R, d)
-        self.yp, self.dyp, self.dxp = z(R, d), z(R, d), z(R, d)
+        self.yp, self.dyp, self.dxp = z(R, d), (None if fold else z(R, d)), z(R, d)
+        self.row_weight = z(R, dt=torch.float32) if fold else None
         self.g, self.u, self.h = z(R, f), z(R, f), z(R, f)
         self.out, self.dx = z(T, d), z(T, d)
         self.dgate = z(T, k, dt=torch.float32)
         self.dWg, self.dWu, self.dWd = z(nl, f, d), z(nl, f, d), z(nl, d, f)
         ws_bytes = max(moe_permute_workspace_bytes(T, k, nl), moe_grouped_gemm_bwd_workspace_bytes(R, f), 256)
+        if fold:
+            ws_bytes = max(ws_bytes, moe_grouped_gemm_bwd_folded_workspace_bytes(R, f))
         self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
 
     def run_fwd(self, x, logits, Wg, Wu, Wd) -> None:
         moe_route(logits, self.k, self.renormalize, self.topk_idx, self.topk_w)
+        if self.fold:
+            self._x = x
+            moe_permute_gate(self.topk_idx, self.topk_w, self.E, self.e_begin, self.e_count, self.expert_offsets,
+                             self.row_token, self.slot_row, self.row_weight, self.ws)
+            moe_grouped_gemm_fwd_folded(x, self.row_token, self.row_weight, self.expert_offsets, Wg, Wu, Wd, self.g,
+                                        self.u, self.h, self.yp)
+            moe_unpermute_sum(self.yp, self.slot_row, self.out)
+            return
         moe_permute(x, self.topk_idx, self.E, self.e_begin, self.e_count, self.expert_offsets, self.row_token,
                     self.slot_row, self.xp, self.ws)
         if self.gather:
@@ -353,6 +443,12 @@ class MoELayerBuffers:
         moe_unpermute_combine(self.yp, self.slot_row, self.topk_w, self.out)
 
     def run_bwd(self, dout, Wg, Wu, Wd) -> None:
+        if self.fold:
+            moe_grouped_gemm_bwd_folded(dout, self._x, self.row_token, self.row_weight, self.slot_row, self.g, self.u,
+                                        self.h, self.expert_offsets, Wg, Wu, Wd, self.dxp, self.dWg, self.dWu,
+                                        self.dWd, self.dgate, self.ws)
+            moe_permute_bwd(self.dxp, self.slot_row, self.dx)
+            return
         moe_unpermute_combine_bwd(dout, self.yp, self.slot_row, self.topk_w, self.dyp, self.dgate)
         if self.gather:
             moe_grouped_gemm_bwd_gather(self.dyp, self._x, self.row_token, self.g, self.u, self.h, self.expert_offsets,
@@ -400,5 +496,8 @@ class MoELayerBuffers:
 
     def results(self) -> Dict[str, torch.Tensor]:
         names = ("topk_idx", "topk_w", "expert_offsets", "row_token", "slot_row", "xp", "g", "u", "h", "yp", "out",
-                 "dyp", "dgate", "dxp", "dWg", "dWu", "dWd", "dx")
-        return {n: getattr(self, n) for n in names if getattr(self, n) is not None}
+                 "dyp", "dgate", "dxp", "dWg", "dWu", "dWd", "dx", "row_weight")
+        res = {n: getattr(self, n) for n in names if getattr(self, n) is not None}
+        if self.fold:      # these two carry the gate weight of their row
+            res["hw"], res["ypw"] = res.pop("h"), res.pop("yp")
+        return res

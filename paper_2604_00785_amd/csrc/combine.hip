@@ -171,6 +171,13 @@ extern "C" int moe_permute_bwd(const moe_bf16* dxp, const int32_t* slot_row, int
   return launch_combine<false>(dxp, slot_row, nullptr, T, k, d, dx, static_cast<hipStream_t>(stream), "permute_bwd");
 }
 
+extern "C" int moe_unpermute_sum(const moe_bf16* ypw, const int32_t* slot_row, int T, int k, int d, moe_bf16* out,
+                                 void* stream) {
+  if (!ypw || !slot_row || !out || bad_dims(T, k, d)) return MOE_ERR_INVALID;
+  if (!moe_aligned16(ypw) || !moe_aligned16(out) || !moe_aligned16(slot_row)) return MOE_ERR_INVALID;
+  return launch_combine<false>(ypw, slot_row, nullptr, T, k, d, out, static_cast<hipStream_t>(stream), "combine");
+}
+
 extern "C" int moe_unpermute_combine_bwd(const moe_bf16* dout, const moe_bf16* yp, const int32_t* slot_row,
                                          const float* topk_w, int T, int k, int d, moe_bf16* dyp, float* dgate,
                                          void* stream) {

@@ -64,9 +64,14 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-enum GemmMode { GATE_UP = 0, DOWN = 1, DGRAD_H = 2, DGRAD_X = 3, WGRAD = 4, WGRAD_GATHER = 5 };
-// WGRAD_GATHER: a weight gradient whose B operand rows are token rows found through row_token
-constexpr bool is_wgrad(int mode) { return mode == WGRAD || mode == WGRAD_GATHER; }
+enum GemmMode { GATE_UP = 0, DOWN = 1, DGRAD_H = 2, DGRAD_X = 3, WGRAD = 4, WGRAD_GATHER = 5, DGRAD_H_GATE = 6,
+                WGRAD_GATHER_A = 7 };
+// WGRAD_GATHER / WGRAD_GATHER_A: a weight gradient whose B / A operand rows are token rows found through
+// row_token.  DGRAD_H_GATE: DGRAD_H for a forward pass that folded the gate weight into h: its A rows are
+// rows of dout found through row_token, its epilogue scales by the row's gate weight and also emits the
+// row's partial dot product with h = silu(g) u (the gradient of the gate weight).
+constexpr bool is_wgrad(int mode) { return mode == WGRAD || mode == WGRAD_GATHER || mode == WGRAD_GATHER_A; }
+constexpr bool is_dgrad_h(int mode) { return mode == DGRAD_H || mode == DGRAD_H_GATE; }
 
 struct GemmArgs {
   // row-grouped products (modes 0-3)
@@ -81,7 +86,10 @@ struct GemmArgs {
   uint16_t* O2;         // h
   const int32_t* offsets;
   const int32_t* row_token;   // not null: rows of the activation operand are gathered, row r lies at A0[row_token[r]]
-                              // (GATE_UP: the A operand; WGRAD: the B operand)
+                              // (GATE_UP, DGRAD_H_GATE, WGRAD_GATHER_A: the A operand; WGRAD_GATHER: the B operand)
+  const float* row_weight;    // GATE_UP: not null = h is scaled by the row's gate weight; DGRAD_H_GATE: required
+  float* dgate_part;          // DGRAD_H_GATE: [n_tiles * 4][R_cap] partial dot products, one plane per 64-column strip
+  int R_cap;                  // DGRAD_H_GATE: plane stride of dgate_part
   int E;
   int K;                // reduction length of one phase (modes 0-3)
   int N;                // output columns (per half for GATE_UP)
@@ -291,7 +299,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   if constexpr (!is_wgrad(MODE)) a_live = wave * 32 < m_end - m0;
 
   constexpr bool A_KN = is_wgrad(MODE);                                       // stored [k][m]
-  constexpr bool B_KN = (is_wgrad(MODE) || MODE == DGRAD_H || MODE == DGRAD_X);  // stored [k][n]
+  constexpr bool B_KN = (is_wgrad(MODE) || is_dgrad_h(MODE) || MODE == DGRAD_X);  // stored [k][n]
 
   // ---------------- operand sources -------------------------------------------
   // A tile <-> output rows m0 + r ; B tile <-> output columns.  Per step and operand a wave issues
@@ -309,9 +317,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   size_t a_step, b_step;                // bytes per step
   int k_lo = 0, k_hi = 0;               // WGRAD: the expert's row range is the reduction
   constexpr bool GATHER_B = (MODE == WGRAD_GATHER);
-  const int32_t* row_tok = nullptr;     // GATHER_B: token of the expert's first reduction row onwards
-  uint32_t vcb[4] = {0, 0, 0, 0};       // GATHER_B: byte offset of the lane's columns within a token row
-  int tokn[4] = {0, 0, 0, 0};           // GATHER_B: tokens of the lane's four reduction rows of a coming step
+  constexpr bool GATHER_A = (MODE == WGRAD_GATHER_A);
+  const int32_t* row_tok = nullptr;     // GATHER_A/B: token of the expert's first reduction row onwards
+  uint32_t vcb[4] = {0, 0, 0, 0};       // GATHER_A/B: byte offset of the lane's columns within a token row
+  int tokn[4] = {0, 0, 0, 0};           // GATHER_A/B: tokens of the lane's four reduction rows of a coming step
   int nk, nk_phase;                     // steps in total / in the first K phase
 
   if constexpr (is_wgrad(MODE)) {
@@ -319,8 +328,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     k_hi = __builtin_amdgcn_readfirstlane(a.offsets[e + 1]);
     nk = (k_hi - k_lo + BK - 1) / BK;
     nk_phase = nk;
-    abase = reinterpret_cast<const char*>(a.A0 + static_cast<size_t>(k_lo) * a.M + m0);
-    a_step = static_cast<size_t>(BK) * a.M * 2;
+    if constexpr (GATHER_A) {
+      abase = reinterpret_cast<const char*>(a.A0 + m0);
+      a_step = 0;
+      row_tok = a.row_token + k_lo;
+    } else {
+      abase = reinterpret_cast<const char*>(a.A0 + static_cast<size_t>(k_lo) * a.M + m0);
+      a_step = static_cast<size_t>(BK) * a.M * 2;
+    }
     if constexpr (GATHER_B) {
       // the base stays at the first token row; a load's lane offset carries its token (set per step)
       bbase = reinterpret_cast<const char*>(a.B0 + n0);
@@ -339,6 +354,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       voa[i] = static_cast<uint32_t>((krow * a.M + ca) * 2);
       vob[i] = static_cast<uint32_t>((krow * a.N + cb) * 2);
       if constexpr (GATHER_B) vcb[i] = static_cast<uint32_t>(cb * 2);
+      if constexpr (GATHER_A) vcb[i] = static_cast<uint32_t>(ca * 2);
     }
   } else {
     nk = a.K / BK;
@@ -347,6 +363,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     a_step = BK * 2;
     bool gathered = false;
     if constexpr (MODE == GATE_UP) gathered = a.row_token != nullptr;
+    if constexpr (MODE == DGRAD_H_GATE) gathered = true;
     if (gathered) abase = reinterpret_cast<const char*>(a.A0);   // lane offsets carry the token row
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -414,7 +431,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   auto a_part = [&](int kt, auto slot_tag, auto i_tag) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_tag)::value, i = decltype(i_tag)::value;
     constexpr int OFF = SLOT * TILE_BYTES + i * 1024;
-    if constexpr (is_wgrad(MODE)) {
+    if constexpr (GATHER_A) {
+      dma16<OFF>(lds_fill, voa[i], sa_next);   // rows past the expert's end were clamped when their tokens were fetched
+    } else if constexpr (is_wgrad(MODE)) {
       if (k_lo + (kt + 1) * BK > k_hi) {
         // last, partial step of the expert: reduction rows at or past its end read zeros
         // (per-lane 64-bit addresses; once per tile)
@@ -433,6 +452,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     constexpr int OFF = SLOT * TILE_BYTES + i * 1024;
     if constexpr (GATHER_B) {
       dma16<OFF>(lds_fill, vob[i], sb_next);   // rows past the expert's end were clamped when their tokens were fetched
+    } else if constexpr (GATHER_A) {
+      if (k_lo + (kt + 1) * BK > k_hi) {
+        // the gathered operand repeats the expert's last row past its end: this one reads zeros there
+        const int krow = k_lo + kt * BK + (wave * 4 + i) * 2 + (lane >> 5);
+        dma16_lane<OFF>(lds_fill, krow < k_hi ? sb_next + vob[i]
+                                   : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16);
+      } else {
+        dma16<OFF>(lds_fill, vob[i], sb_next);
+      }
     } else if constexpr (MODE == WGRAD) {
       if (k_lo + (kt + 1) * BK > k_hi) {
         // ... and the other operand reads its last valid row there, so that zero times it is zero
@@ -463,7 +491,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   // apply_tok may only run after a wait that covers them.
   const uint32_t tok_voff = static_cast<uint32_t>(((wave * 4) * 2 + (lane >> 5)) * 4);   // row of load 0; load i: + 2 i rows
   auto fetch_tok = [&](int kt) __attribute__((always_inline)) {
-    if constexpr (GATHER_B) {
+    if constexpr (GATHER_B || GATHER_A) {
       if (k_lo + (kt + 1) * BK > k_hi) {
         const int last = k_hi - k_lo - 1;
 #pragma unroll
@@ -482,12 +510,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     }
   };
   auto apply_tok = [&]() __attribute__((always_inline)) {
-    if constexpr (GATHER_B) {
-      const uint32_t row_bytes = static_cast<uint32_t>(a.N) * 2u;
+    if constexpr (GATHER_B || GATHER_A) {
+      const uint32_t row_bytes = static_cast<uint32_t>(GATHER_B ? a.N : a.M) * 2u;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         asm volatile("" : "+v"(tokn[i]));   // not before the wait that precedes this call
-        vob[i] = static_cast<uint32_t>(tokn[i]) * row_bytes + vcb[i];
+        const uint32_t off = static_cast<uint32_t>(tokn[i]) * row_bytes + vcb[i];
+        if constexpr (GATHER_B) vob[i] = off; else voa[i] = off;
       }
     }
   };
@@ -600,17 +629,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
 
   const int grow0 = m0 + wm * 128;                                   // wave's first output row
   const int gcol0 = n0 + wn * (MODE == GATE_UP ? 32 : 64);           // wave's first output column
-  // DGRAD_H: saved g / u rows of one 64-row half of the wave's piece, 16 bytes per lane and pass
-  u32x4 pg[8], pu[8];
+  // DGRAD_H: saved g / u rows of one part of the wave's 128 rows (a 64-row half; a 32-row quarter for
+  // DGRAD_H_GATE, whose epilogue needs more registers for itself), 16 bytes per lane and pass
+  constexpr int GU_PARTS = (MODE == DGRAD_H_GATE) ? 4 : 2;
+  constexpr int GU_ROWS = 128 / GU_PARTS;
+  constexpr int GU_PASSES = GU_ROWS / 8;
+  u32x4 pg[GU_PASSES], pu[GU_PASSES];
   auto gu_load = [&](int hh, ArgPtr ap) __attribute__((always_inline)) {
-    if constexpr (MODE == DGRAD_H) {
+    if constexpr (is_dgrad_h(MODE)) {
       const int ncol = ap->N;
       const uint16_t* gsrc = ap->G;
       const uint16_t* usrc = ap->U;
 #pragma unroll
-      for (int p = 0; p < 8; ++p) {
+      for (int p = 0; p < GU_PASSES; ++p) {
         const int row = p * 8 + (lane >> 3), piece = lane & 7;
-        int gr = grow0 + hh * 64 + row;  if (gr > m_end - 1) gr = m_end - 1;
+        int gr = grow0 + hh * GU_ROWS + row;  if (gr > m_end - 1) gr = m_end - 1;
         int gc = gcol0 + piece * 8;  if (gc > ncol - 8) gc = ncol - 8;
         const size_t o = static_cast<size_t>(gr) * ncol + gc;
         pg[p] = *reinterpret_cast<const u32x4*>(gsrc + o);
@@ -639,6 +672,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     using LA = std::integral_constant<int, slot_of_a((P + 2) % NSLOT)>;   // where A(kt+2) goes: B(kt-1)'s slot
     const bool more = kt + 2 < nk;
     const bool more_a = more && a_live;
+    if constexpr (GATHER_A) {
+      // the tokens of A(kt+2) were fetched a step ago and are covered by that step's wait; those of
+      // A(kt+3) are requested before the loads of A(kt+2), the only ones this step's wait leaves in flight
+      if (more) apply_tok();
+      if (kt + 3 < nk) fetch_tok(kt + 3);
+    }
     read_frags(SA{}, SB{}, I1{}, I1{}, full_tag);
     lds_wait<nreads(decltype(full_tag)::value)>();  fence();
     mma_pair(I0{}, J0{}, full_tag);  mma_pair(I0{}, J1{}, full_tag);
@@ -701,6 +740,20 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
           apply_tok();
           b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
         }
+      } else if constexpr (GATHER_A) {
+        fetch_tok(0);
+        b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
+        wait_vm<4>();   // the tokens are older than the four loads of B(0)
+        apply_tok();
+        a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
+        if (nk > 1) {
+          fetch_tok(1);
+          b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
+          wait_vm<4>();
+          apply_tok();
+          if (nk > 2) fetch_tok(2);   // applied at the start of step 0: older than the loads of A(1)
+          a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
+        }
       } else {
         // the weight tile first: its addresses are ready, while those of the activation tile may still
         // wait for the tokens of the tile's rows (gathered rows)
@@ -711,7 +764,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
           if (a_live) a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
         }
       }
-      if (nk > 1 && a_live) wait_vm<8>(); else if (nk > 1) wait_vm<4>(); else wait_vm<0>();
+      if constexpr (GATHER_A) {
+        if (nk > 1) wait_vm<4>(); else wait_vm<0>();   // only the loads of A(1) stay in flight: the tokens of A(2) are in
+      } else {
+        if (nk > 1 && a_live) wait_vm<8>(); else if (nk > 1) wait_vm<4>(); else wait_vm<0>();
+      }
       wg_barrier();
       if constexpr (GATHER_B) {
         if (nk > 2) fetch_tok(2);
@@ -767,6 +824,16 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   };
 
   if constexpr (MODE == GATE_UP) {
+    // gate weight of the lane's four rows (1 unless the caller folds the weights into h)
+    float wv[4] = {1.f, 1.f, 1.f, 1.f};
+    if (ae->row_weight != nullptr) {
+      const float* rw = ae->row_weight;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int r = grow0 + i * 32 + lrow;  if (r > m_end - 1) r = m_end - 1;
+        wv[i] = rw[r];
+      }
+    }
     // pass 1: g in pieces 0-3, u in pieces 4-7
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -786,30 +853,44 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       for (int q = 0; q < 4; ++q) {
         float h[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) h[c] = silu_f(acc[i][0][4 * q + c]) * acc[i][1][4 * q + c];
+        for (int c = 0; c < 4; ++c) h[c] = silu_f(acc[i][0][4 * q + c]) * acc[i][1][4 * q + c] * wv[i];
         put_quad(i * 32 + lrow, q, h[0], h[1], h[2], h[3]);
       }
     __builtin_amdgcn_wave_barrier();
     flush(ae->O2, ae->N, grow0, 128, 0, 4, gcol0, ae->N);
-  } else if constexpr (MODE == DGRAD_H) {
-    // two halves of 64 rows: g rows at stage[0, 8K), u rows at stage[8K, 16K).  The g/u rows of
-    // the first half were requested before the last K step, those of the second half are
-    // requested before the first half is processed, so their latency stays hidden.
+  } else if constexpr (is_dgrad_h(MODE)) {
+    // in parts of GU_ROWS rows: g rows at stage[0, 8K), u rows at stage[8K, 16K).  The g/u rows of
+    // the first part were requested at the end of the main loop, those of the next part are
+    // requested before a part is processed, so their latency stays hidden.
+    // DGRAD_H_GATE: the accumulators hold dh0 = dout[token] . Wd; the row's gate weight w turns them into
+    // dh = w dh0, and sum over the wave's 64 columns of dh0 * silu(g) * u is the wave's share of the
+    // gradient of w (a lane holds 32 of the columns of its row, lane ^ 32 the other 32).
+    constexpr bool GATE = (MODE == DGRAD_H_GATE);
     char* ustage = stage + WAVE_STAGE_BYTES / 2;
+    constexpr int NI = GU_ROWS / 32;    // 32-row accumulator blocks per part
 #pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
-      const int first = grow0 + hh * 64;
+    for (int hh = 0; hh < GU_PARTS; ++hh) {
+      const int first = grow0 + hh * GU_ROWS;
+      float wrow[2] = {1.f, 1.f}, dsum[2] = {0.f, 0.f};
+      if constexpr (GATE) {
+        const float* rw = ae->row_weight;
 #pragma unroll
-      for (int p = 0; p < 8; ++p) {
+        for (int i2 = 0; i2 < NI; ++i2) {
+          int r = first + i2 * 32 + lrow;  if (r > m_end - 1) r = m_end - 1;
+          wrow[i2] = rw[r];
+        }
+      }
+#pragma unroll
+      for (int p = 0; p < GU_PASSES; ++p) {
         const int row = p * 8 + (lane >> 3), piece = lane & 7;
         const int so = row * 128 + ((piece ^ (row & 7)) << 4);
         *reinterpret_cast<u32x4*>(stage + so) = pg[p];
         *reinterpret_cast<u32x4*>(ustage + so) = pu[p];
       }
-      if (hh == 0) gu_load(1, ae);
+      if (hh + 1 < GU_PARTS) gu_load(hh + 1, ae);
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int i2 = 0; i2 < 2; ++i2)
+      for (int i2 = 0; i2 < NI; ++i2)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -824,11 +905,20 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
             float dg[4], du[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-              const float dh = acc[hh * 2 + i2][j][4 * q + c];
               const float sg = sigmoid_f(g4[c]);
-              const float a = dh * sg;                       // shared by both derivatives
-              du[c] = a * g4[c];
-              dg[c] = (a * u4[c]) * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f);
+              if constexpr (GATE) {
+                const float dh0 = acc[hh * NI + i2][j][4 * q + c];
+                const float sl = g4[c] * sg;                 // silu(g)
+                const float t0 = dh0 * u4[c];
+                dsum[i2] = __builtin_fmaf(t0, sl, dsum[i2]);
+                du[c] = (dh0 * wrow[i2]) * sl;
+                dg[c] = (t0 * wrow[i2]) * (sg * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f));
+              } else {
+                const float dh = acc[hh * NI + i2][j][4 * q + c];
+                const float a = dh * sg;                     // shared by both derivatives
+                du[c] = a * g4[c];
+                dg[c] = (a * u4[c]) * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f);
+              }
             }
             u32x2 o;
             o.x = pack_bf16(dg[0], dg[1]);  o.y = pack_bf16(dg[2], dg[3]);
@@ -836,8 +926,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
             o.x = pack_bf16(du[0], du[1]);  o.y = pack_bf16(du[2], du[3]);
             *reinterpret_cast<u32x2*>(ua) = o;
           }
+      if constexpr (GATE) {
+        if (gcol0 < ae->N) {     // a strip past the last column holds repeated columns: no share
+          float* part = ae->dgate_part + static_cast<size_t>(gcol0 >> 6) * ae->R_cap;
+#pragma unroll
+          for (int i2 = 0; i2 < NI; ++i2) {
+            const float t = dsum[i2] + __shfl_xor(dsum[i2], 32, 64);
+            const int r = first + i2 * 32 + lrow;
+            if (lgrp == 0 && r < m_end) part[r] = t;
+          }
+        }
+      }
       __builtin_amdgcn_wave_barrier();
-      for (int p = 0; p < 8; ++p) {
+      for (int p = 0; p < GU_PASSES; ++p) {
         const int row = p * 8 + (lane >> 3), piece = lane & 7;
         const int so = row * 128 + ((piece ^ (row & 7)) << 4);
         const u32x4 dgv = *reinterpret_cast<const u32x4*>(stage + so);
@@ -927,7 +1028,7 @@ extern "C" size_t moe_workspace_bytes(int T, int E, int k, int d, int f) {
 
 namespace {
 // xp grouped rows, or (row_token not null) the token rows themselves, gathered by the GEMM's loads
-int gemm_fwd(const moe_bf16* xp, const int32_t* row_token, const int32_t* expert_offsets, const moe_bf16* Wg,
+int gemm_fwd(const moe_bf16* xp, const int32_t* row_token, const float* row_weight, const int32_t* expert_offsets, const moe_bf16* Wg,
              const moe_bf16* Wu, const moe_bf16* Wd, int E, int R_cap, int d, int f, moe_bf16* g, moe_bf16* u,
              moe_bf16* h, moe_bf16* yp, void* stream) {
   if (!xp || !expert_offsets || !Wg || !Wu || !Wd || !g || !u || !h || !yp) return MOE_ERR_INVALID;
@@ -938,7 +1039,7 @@ int gemm_fwd(const moe_bf16* xp, const int32_t* row_token, const int32_t* expert
   const int m_tiles = R_cap / BM + E;
 
   GemmArgs a{};
-  a.offsets = expert_offsets; a.E = E; a.m_tiles_cap = m_tiles; a.row_token = row_token;
+  a.offsets = expert_offsets; a.E = E; a.m_tiles_cap = m_tiles; a.row_token = row_token; a.row_weight = row_weight;
   // gate | up with the SwiGLU epilogue
   a.A0 = U16(xp); a.B0 = U16(Wg); a.B1 = U16(Wu); a.O0 = g; a.O1 = u; a.O2 = h;
   a.K = d; a.N = f; a.n_tiles = (f + BN / 2 - 1) / (BN / 2);
@@ -962,7 +1063,7 @@ bool bad_gather(const moe_bf16* x, int T, const int32_t* row_token, int width) {
 extern "C" int moe_grouped_gemm_fwd(const moe_bf16* xp, const int32_t* expert_offsets, const moe_bf16* Wg,
                                     const moe_bf16* Wu, const moe_bf16* Wd, int E, int R_cap, int d, int f,
                                     moe_bf16* g, moe_bf16* u, moe_bf16* h, moe_bf16* yp, void* stream) {
-  return gemm_fwd(xp, nullptr, expert_offsets, Wg, Wu, Wd, E, R_cap, d, f, g, u, h, yp, stream);
+  return gemm_fwd(xp, nullptr, nullptr, expert_offsets, Wg, Wu, Wd, E, R_cap, d, f, g, u, h, yp, stream);
 }
 
 extern "C" int moe_grouped_gemm_fwd_gather(const moe_bf16* x, int T, const int32_t* row_token,
@@ -970,7 +1071,15 @@ extern "C" int moe_grouped_gemm_fwd_gather(const moe_bf16* x, int T, const int32
                                            const moe_bf16* Wd, int E, int R_cap, int d, int f, moe_bf16* g,
                                            moe_bf16* u, moe_bf16* h, moe_bf16* yp, void* stream) {
   if (bad_gather(x, T, row_token, d)) return MOE_ERR_INVALID;
-  return gemm_fwd(x, row_token, expert_offsets, Wg, Wu, Wd, E, R_cap, d, f, g, u, h, yp, stream);
+  return gemm_fwd(x, row_token, nullptr, expert_offsets, Wg, Wu, Wd, E, R_cap, d, f, g, u, h, yp, stream);
+}
+
+extern "C" int moe_grouped_gemm_fwd_folded(const moe_bf16* x, int T, const int32_t* row_token, const float* row_weight,
+                                           const int32_t* expert_offsets, const moe_bf16* Wg, const moe_bf16* Wu,
+                                           const moe_bf16* Wd, int E, int R_cap, int d, int f, moe_bf16* g,
+                                           moe_bf16* u, moe_bf16* hw, moe_bf16* ypw, void* stream) {
+  if (bad_gather(x, T, row_token, d) || !row_weight || !moe_aligned16(row_weight)) return MOE_ERR_INVALID;
+  return gemm_fwd(x, row_token, row_weight, expert_offsets, Wg, Wu, Wd, E, R_cap, d, f, g, u, hw, ypw, stream);
 }
 
 namespace {
@@ -1045,4 +1154,93 @@ extern "C" int moe_grouped_gemm_bwd_gather(const moe_bf16* dyp, const moe_bf16* 
   if (bad_gather(x, T, row_token, d)) return MOE_ERR_INVALID;
   return gemm_bwd(dyp, x, row_token, g, u, h, expert_offsets, Wg, Wu, Wd, E, R_cap, d, f, dxp, dWg, dWu, dWd, ws,
                   ws_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Backward of a forward pass that folded the gate weights into h (moe_grouped_gemm_fwd_folded).
+namespace {
+// dgate[t, i] = sum over the column strips of the row's partial dot products (0 for a slot without a local row)
+__global__ __launch_bounds__(256) void dgate_finish_kernel(const float* __restrict__ part, int planes, int R_cap,
+                                                           const int32_t* __restrict__ slot_row, int n,
+                                                           float* __restrict__ dgate) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= n) return;
+  const int row = slot_row[idx];
+  float sum = 0.f;
+  if (row >= 0)
+    for (int p = 0; p < planes; ++p) sum += part[static_cast<size_t>(p) * R_cap + row];
+  dgate[idx] = sum;
+}
+
+size_t folded_part_bytes(int R_cap, int f) {
+  return (static_cast<size_t>(f / 64) * R_cap * sizeof(float) + 255) & ~static_cast<size_t>(255);
+}
+}  // namespace
+
+extern "C" size_t moe_grouped_gemm_bwd_folded_workspace_bytes(int R_cap, int f) {
+  if (R_cap <= 0 || f <= 0) return 0;
+  return moe_grouped_gemm_bwd_workspace_bytes(R_cap, f) + folded_part_bytes(R_cap, f);
+}
+
+extern "C" int moe_grouped_gemm_bwd_folded(const moe_bf16* dout, const moe_bf16* x, int T, int k,
+                                           const int32_t* row_token, const float* row_weight, const int32_t* slot_row,
+                                           const moe_bf16* g, const moe_bf16* u, const moe_bf16* hw,
+                                           const int32_t* expert_offsets, const moe_bf16* Wg, const moe_bf16* Wu,
+                                           const moe_bf16* Wd, int E, int R_cap, int d, int f, moe_bf16* dxp,
+                                           moe_bf16* dWg, moe_bf16* dWu, moe_bf16* dWd, float* dgate, void* ws,
+                                           size_t ws_bytes, void* stream) {
+  if (!dout || !g || !u || !hw || !expert_offsets || !Wg || !Wu || !Wd || !dxp || !dWg || !dWu || !dWd || !dgate ||
+      !ws || !row_weight || !slot_row || k <= 0)
+    return MOE_ERR_INVALID;
+  if (bad_gemm_dims(E, R_cap, d, f) || bad_gather(x, T, row_token, d) || bad_gather(dout, T, row_token, d))
+    return MOE_ERR_INVALID;
+  const void* ptrs[] = {dout, x, g, u, hw, expert_offsets, Wg, Wu, Wd, dxp, dWg, dWu, dWd, dgate, ws, row_weight, slot_row};
+  for (const void* p : ptrs) if (!moe_aligned16(p)) return MOE_ERR_INVALID;
+  if (ws_bytes < moe_grouped_gemm_bwd_folded_workspace_bytes(R_cap, f)) return MOE_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int m_tiles = R_cap / BM + E;
+  const size_t one = moe_grouped_gemm_bwd_workspace_bytes(R_cap, f) / 2;
+  uint16_t* dg = static_cast<uint16_t*>(ws);
+  uint16_t* du = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + one);
+  float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + 2 * one);
+
+  // dWd = (w dout[token])^T h = dout[token]^T hw: rows of dout gathered by the loads of the A operand
+  {
+    GemmArgs w{};
+    w.offsets = expert_offsets; w.E = E; w.row_token = row_token;
+    w.A0 = U16(dout); w.B0 = U16(hw); w.O0 = dWd; w.M = d; w.N = f;
+    w.n_tiles = (f + BN - 1) / BN;
+    w.m_tiles_cap = (d + BM - 1) / BM;
+    int rc = launch_gemm<WGRAD_GATHER_A>(w, static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E, s, "gemm_wgrad_down");
+    if (rc != MOE_OK) return rc;
+  }
+  // dh0 = dout[token] . Wd; dh = w dh0 -> dg, du; partial dot products of dh0 with h for the gate gradient
+  GemmArgs a{};
+  a.offsets = expert_offsets; a.E = E; a.m_tiles_cap = m_tiles; a.row_token = row_token; a.row_weight = row_weight;
+  a.dgate_part = part; a.R_cap = R_cap;
+  a.A0 = U16(dout); a.B0 = U16(Wd); a.G = U16(g); a.U = U16(u); a.O0 = dg; a.O1 = du;
+  a.K = d; a.N = f; a.n_tiles = (f + BN - 1) / BN;
+  int rc = launch_gemm<DGRAD_H_GATE>(a, static_cast<long long>(a.n_tiles) * m_tiles, s, "gemm_dgrad_h");
+  if (rc != MOE_OK) return rc;
+  const int n = T * k;
+  MOE_LAUNCH("dgate_finish", dgate_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, s, static_cast<const float*>(part),
+             f / 64, R_cap, slot_row, n, dgate);
+  // dWg = dg^T x[token] ; dWu = du^T x[token]
+  const uint16_t* srcs[2] = {dg, du};
+  uint16_t* outs[2] = {dWg, dWu};
+  const char* names[2] = {"gemm_wgrad_gate", "gemm_wgrad_up"};
+  for (int j = 0; j < 2; ++j) {
+    GemmArgs w{};
+    w.offsets = expert_offsets; w.E = E; w.row_token = row_token;
+    w.A0 = srcs[j]; w.B0 = U16(x); w.O0 = outs[j]; w.M = f; w.N = d;
+    w.n_tiles = (d + BN - 1) / BN;
+    w.m_tiles_cap = (f + BM - 1) / BM;
+    rc = launch_gemm<WGRAD_GATHER>(w, static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E, s, names[j]);
+    if (rc != MOE_OK) return rc;
+  }
+  GemmArgs b{};
+  b.offsets = expert_offsets; b.E = E; b.m_tiles_cap = m_tiles;
+  b.A0 = dg; b.A1 = du; b.B0 = U16(Wg); b.B1 = U16(Wu); b.O0 = dxp;
+  b.K = f; b.N = d; b.n_tiles = (d + BN - 1) / BN;
+  return launch_gemm<DGRAD_X>(b, static_cast<long long>(b.n_tiles) * m_tiles, s, "gemm_dgrad_x");
 }

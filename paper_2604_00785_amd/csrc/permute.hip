@@ -137,7 +137,9 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32
                                                                      int e_begin, int e_count, int nbits, int nblocks,
                                                                      const int32_t* __restrict__ block_base,
                                                                      int32_t* __restrict__ row_token,
-                                                                     int32_t* __restrict__ slot_row) {
+                                                                     int32_t* __restrict__ slot_row,
+                                                                     const float* __restrict__ topk_w,
+                                                                     float* __restrict__ row_weight) {
   __shared__ int wcnt[PERM_WAVES][MOE_MAX_EXPERTS];
   const int tid = threadIdx.x, w = tid / MOE_WAVE, lane = tid % MOE_WAVE;
   for (int e = tid; e < e_count; e += PERM_THREADS) {
@@ -177,7 +179,10 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32
     __builtin_amdgcn_wave_barrier();
     if (idx < n) {
       slot_row[idx] = row;
-      if (row >= 0) row_token[row] = idx / k;
+      if (row >= 0) {
+        row_token[row] = idx / k;
+        if (row_weight != nullptr) row_weight[row] = topk_w[idx];   // the row's gate weight, for callers that fold it into h
+      }
     }
   }
 }
@@ -223,9 +228,10 @@ extern "C" size_t moe_permute_workspace_bytes(int T, int k, int e_count) {
   return (cells * sizeof(int32_t) + 16 + 255) & ~static_cast<size_t>(255);   // + one 16-byte access of slack
 }
 
-extern "C" int moe_permute(const moe_bf16* x, const int32_t* topk_idx, int T, int d, int E_total, int k, int e_begin,
-                           int e_count, int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row, moe_bf16* xp,
-                           void* ws, size_t ws_bytes, void* stream) {
+namespace {
+int permute_impl(const moe_bf16* x, const int32_t* topk_idx, const float* topk_w, int T, int d, int E_total, int k,
+                 int e_begin, int e_count, int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row,
+                 float* row_weight, moe_bf16* xp, void* ws, size_t ws_bytes, void* stream) {
   // xp == NULL: index generation only (for callers that let the GEMMs gather the rows); x is not read then
   if (!topk_idx || !expert_offsets || !row_token || !slot_row || !ws || (xp && !x)) return MOE_ERR_INVALID;
   if (T <= 0 || d <= 0 || d % 8 != 0 || E_total <= 0 || k <= 0 || k > E_total) return MOE_ERR_INVALID;
@@ -244,7 +250,7 @@ extern "C" int moe_permute(const moe_bf16* x, const int32_t* topk_idx, int T, in
              nbits, nb, block_hist);
   MOE_LAUNCH("permute_scan", permute_scan_kernel, dim3(1), dim3(1024), 0, s, block_hist, e_count, nb, expert_offsets);
   MOE_LAUNCH("permute_place", permute_place_kernel, dim3(nb), dim3(PERM_THREADS), 0, s, topk_idx, n, k, e_begin,
-             e_count, nbits, nb, static_cast<const int32_t*>(block_hist), row_token, slot_row);
+             e_count, nbits, nb, static_cast<const int32_t*>(block_hist), row_token, slot_row, topk_w, row_weight);
   if (!xp) return moe_check_launch();
   const int chunks = d / 8;
   dim3 grid((T + 3) / 4), block(256);
@@ -257,4 +263,20 @@ extern "C" int moe_permute(const moe_bf16* x, const int32_t* topk_idx, int T, in
   else
     MOE_LAUNCH("permute_rows", permute_rows_kernel<4>, grid, block, 0, s, xs, static_cast<const int32_t*>(slot_row), T, k, chunks, xd);
   return moe_check_launch();
+}
+}  // namespace
+
+extern "C" int moe_permute(const moe_bf16* x, const int32_t* topk_idx, int T, int d, int E_total, int k, int e_begin,
+                           int e_count, int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row, moe_bf16* xp,
+                           void* ws, size_t ws_bytes, void* stream) {
+  return permute_impl(x, topk_idx, nullptr, T, d, E_total, k, e_begin, e_count, expert_offsets, row_token, slot_row,
+                      nullptr, xp, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_permute_gate(const int32_t* topk_idx, const float* topk_w, int T, int E_total, int k, int e_begin,
+                                int e_count, int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row,
+                                float* row_weight, void* ws, size_t ws_bytes, void* stream) {
+  if (!topk_w || !row_weight || !moe_aligned16(topk_w) || !moe_aligned16(row_weight)) return MOE_ERR_INVALID;
+  return permute_impl(nullptr, topk_idx, topk_w, T, 8, E_total, k, e_begin, e_count, expert_offsets, row_token,
+                      slot_row, row_weight, nullptr, ws, ws_bytes, stream);
 }

@@ -50,11 +50,13 @@ class DeviceResults:
         return self._sel(name, idx).contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def run_layer(cfg: W.MoEConfig, inp: Dict[str, np.ndarray], device="cuda:0", keep_on_device=False, gather=False):
+def run_layer(cfg: W.MoEConfig, inp: Dict[str, np.ndarray], device="cuda:0", keep_on_device=False, gather=False,
+              fold=False):
     """Whole hot path on the GPU for one generated batch; returns numpy results
-    (or a DeviceResults when keep_on_device is set).  gather: no xp, the GEMMs read x through row_token."""
+    (or a DeviceResults when keep_on_device is set).  gather: no xp, the GEMMs read x through row_token.
+    fold: the gate weights are folded into h (results hw, ypw and row_weight instead of h, yp and dyp)."""
     buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.e_begin, cfg.n_local, cfg.renormalize, device,
-                            gather=gather)
+                            gather=gather, fold=fold)
     x, dout = bf16_to_dev(inp["x"], device), bf16_to_dev(inp["dout"], device)
     Wg, Wu, Wd = (bf16_to_dev(inp[n], device) for n in ("Wg", "Wu", "Wd"))
     logits = torch.from_numpy(inp["logits"]).to(device)
@@ -97,6 +99,14 @@ def assert_close(got, ref, name, tol=REL_TOL):
     assert fr <= 1e-3, f"{name}: {fr:.2e} of elements off by more than {REL_TOL} relative"
 
 
+def row_weights(ref: Dict[str, np.ndarray]) -> np.ndarray:
+    """Gate weight of every routed row of an oracle result: w_row[slot_row[t, i]] = topk_w[t, i]."""
+    sr, w = ref["slot_row"], ref["topk_w"]
+    out = np.zeros(int(ref["expert_offsets"][-1]), dtype=np.float64)
+    out[sr[sr >= 0]] = w[sr >= 0]
+    return out
+
+
 def compare_layer(res: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], n_local: int):
     """Bit-exact integer results, toleranced floating-point ones (rows < R only)."""
     for n in ("topk_idx", "expert_offsets", "slot_row"):
@@ -106,8 +116,17 @@ def compare_layer(res: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], n_loca
     np.testing.assert_allclose(res["topk_w"], ref["topk_w"], rtol=GATE_TOL, atol=1e-30)
     if "xp" in res:
         assert np.array_equal(res["xp"][:R], ref["xp"]), "xp is not an exact copy"
-    for n in ("g", "u", "h", "yp", "dyp", "dxp"):
-        assert_close(res[n][:R], ref[n], n)
+    if "hw" in res:      # gate weights folded into h: the oracle's h and yp times the row's weight; no dyp
+        wr = row_weights(ref)
+        np.testing.assert_allclose(res["row_weight"][:R], wr, rtol=GATE_TOL, atol=1e-30)
+        assert_close(res["hw"][:R], ref["h"] * wr[:, None], "hw")
+        assert_close(res["ypw"][:R], ref["yp"] * wr[:, None], "ypw")
+        assert "dyp" not in res
+        for n in ("g", "u", "dxp"):
+            assert_close(res[n][:R], ref[n], n)
+    else:
+        for n in ("g", "u", "h", "yp", "dyp", "dxp"):
+            assert_close(res[n][:R], ref[n], n)
     for n in ("out", "dx", "dgate"):
         assert_close(res[n], ref[n], n)
     off = ref["expert_offsets"]

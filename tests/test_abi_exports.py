@@ -80,3 +80,16 @@ def test_forced_uniform_routing_workload():
     for name in ("mula100b_ep12", "mula220b_ep12", "olmoe_fur"):
         cfg = W.CONFIGS[name]
         assert cfg.e_begin + cfg.n_local <= cfg.E and cfg.d % 64 == 0 and cfg.f % 64 == 0
+
+
+def test_host_only_calls_folded_gate_weights():
+    lib = B.load()
+    base = B.moe_grouped_gemm_bwd_workspace_bytes(65536, 1024)
+    assert B.moe_grouped_gemm_bwd_folded_workspace_bytes(65536, 1024) == base + 16 * 65536 * 4   # one fp32 per row and 64-column strip
+    assert B.moe_grouped_gemm_bwd_folded_workspace_bytes(0, 1024) == 0
+    assert lib.moe_permute_gate(None, None, 64, 8, 2, 0, 8, None, None, None, None, None, 0, None) == -1
+    assert lib.moe_unpermute_sum(None, None, 4, 2, 64, None, None) == -1
+    assert lib.moe_grouped_gemm_fwd_folded(None, 64, None, None, None, None, None, None, 1, 64, 64, 64,
+                                           None, None, None, None, None) == -1
+    assert lib.moe_grouped_gemm_bwd_folded(None, None, 64, 2, None, None, None, None, None, None, None, None, None,
+                                           None, 1, 64, 64, 64, None, None, None, None, None, None, 0, None) == -1

@@ -29,15 +29,16 @@ def sub_batch(inp, tokens, e_lo, e_hi):
 
 # gather=True is what bench.py times (rows of x read through row_token by the GEMMs, no xp);
 # gather=False materialises xp with permute_rows.
-@pytest.mark.parametrize("name,gather", [("olmoe", True), ("olmoe", False), ("fine", True), ("ep_share", True),
-                                         ("ep_share", False), ("olmoe_fur", True), ("mula100b_ep12", True),
-                                         ("mula220b_ep12", True)])
-def test_full_size_config(name, gather):
+@pytest.mark.parametrize("name,gather,fold", [
+    ("olmoe", True, False), ("olmoe", False, False), ("olmoe", True, True), ("fine", True, False), ("fine", True, True),
+    ("ep_share", True, False), ("ep_share", False, False), ("ep_share", True, True), ("olmoe_fur", True, False),
+    ("mula100b_ep12", True, False), ("mula100b_ep12", True, True), ("mula220b_ep12", True, False)])
+def test_full_size_config(name, gather, fold):
     cfg = W.CONFIGS[name]
-    print(f"full size {name} (gather={gather}): generating inputs", flush=True)
+    print(f"full size {name} (gather={gather}, fold={fold}): generating inputs", flush=True)
     inp = W.make_inputs(cfg)
     print("running the HIP path", flush=True)
-    res = H.run_layer(cfg, inp, keep_on_device=True, gather=gather)
+    res = H.run_layer(cfg, inp, keep_on_device=True, gather=gather, fold=fold)
     T, k, nl, eb = cfg.T, cfg.k, cfg.n_local, cfg.e_begin
 
     # ---- routing and permutation: in full, bit-exact --------------------------------
@@ -74,7 +75,12 @@ def test_full_size_config(name, gather):
         tokens = rrt[a:b]
         ref = O.layer_fwd_bwd(sub_batch(inp, tokens, e, e + 1), k, eb + e, 1, cfg.renormalize)
         assert int(ref["expert_offsets"][-1]) == b - a
-        for n in ("g", "u", "h", "yp", "dyp", "dxp"):
+        if fold:    # h and yp carry the row's gate weight; there is no dyp
+            wr = H.row_weights(ref)
+            H.assert_close(res.rows("hw", slice(a, b)), ref["h"] * wr[:, None], f"hw[expert {e}]")
+            H.assert_close(res.rows("ypw", slice(a, b)), ref["yp"] * wr[:, None], f"ypw[expert {e}]")
+            np.testing.assert_allclose(res.rows("row_weight", slice(a, b)), wr, rtol=H.GATE_TOL)
+        for n in ("g", "u", "dxp") if fold else ("g", "u", "h", "yp", "dyp", "dxp"):
             H.assert_close(res.rows(n, slice(a, b)), ref[n], f"{n}[expert {e}]")
         for n in ("dWg", "dWu", "dWd"):
             H.assert_close(res.rows(n, slice(e, e + 1))[0], ref[n][0], f"{n}[{e}]")

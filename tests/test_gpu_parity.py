@@ -233,6 +233,43 @@ def test_layer_gathered_rows(T, d, E, k, f, eb, ec, renorm):
         assert np.array_equal(res[n], plain[n]), n
 
 
+@pytest.mark.parametrize("T,d,E,k,f,eb,ec,renorm", [
+    (256, 128, 8, 2, 256, 0, 8, 1),       # the tiny config's shape
+    (700, 192, 6, 3, 320, 0, 6, 1),       # ragged in every dimension
+    (2048, 256, 16, 4, 128, 4, 8, 0),     # expert-parallel share, no renormalisation
+    (1500, 128, 4, 2, 64, 0, 4, 1),       # several row tiles and several reduction steps per expert
+    (64, 64, 300, 9, 64, 100, 150, 1),    # most experts empty, experts with a single row
+    (3000, 512, 3, 1, 192, 0, 3, 1),      # about 1000 rows per expert: many reduction steps in the weight gradients
+    (1, 64, 4, 2, 64, 0, 4, 1),           # a single token
+])
+def test_layer_folded_gate_weights(T, d, E, k, f, eb, ec, renorm):
+    """The path that folds the gate weights into h and takes dgate from the backward product of the down
+    projection: against the oracle (hw = w h, ypw = w yp, everything else unchanged)."""
+    print(f"folded layer T={T} d={d} E={E} k={k} f={f} local=[{eb},{eb+ec}) renorm={renorm}", flush=True)
+    cfg = W.MoEConfig("custom", T=T, d=d, E=E, k=k, f=f, e_begin=eb, e_count=ec, renormalize=renorm, seed=T + 3)
+    inp = W.make_inputs(cfg)
+    res = H.run_layer(cfg, inp, fold=True)
+    assert "xp" not in res and "dyp" not in res
+    ref = O.layer_fwd_bwd(inp, k, eb, ec, renorm)
+    H.compare_layer(res, ref, ec)
+    # g and u do not depend on the gate weights: bit for bit those of the gathered path
+    plain = H.run_layer(cfg, inp, gather=True)
+    R = int(ref["expert_offsets"][-1])
+    for n in ("g", "u"):
+        assert np.array_equal(res[n][:R], plain[n][:R]), n
+
+
+def test_layer_folded_without_local_rows():
+    """No token routed to the local experts: zeros everywhere, through the folded path."""
+    cfg = W.MoEConfig("custom", T=192, d=128, E=8, k=2, f=64, e_begin=6, e_count=2, seed=3)
+    inp = W.make_inputs(cfg)
+    inp["logits"][:, 6:] = -50.0          # experts 6 and 7 are never among the top 2
+    res = H.run_layer(cfg, inp, fold=True)
+    assert int(res["expert_offsets"][-1]) == 0
+    for n in ("out", "dx", "dgate", "dWg", "dWu", "dWd"):
+        assert np.all(res[n] == 0.0), n
+
+
 # ----------------------------------------------------------------------------- router and Stage-1 backward
 @pytest.mark.parametrize("T,d,E", [(256, 128, 8), (1000, 2048, 64), (77, 64, 100), (33, 48, 5), (4096, 256, 300)])
 def test_router_fwd(T, d, E):
@@ -292,13 +329,13 @@ def test_router_bwd(T, d, E):
     assert torch.equal(dWr, dWr2)
 
 
-@pytest.mark.parametrize("gather", [False, True])
+@pytest.mark.parametrize("gather", [False, True, "fold"])
 def test_drop_in_block_router_to_gradients(gather):
     """Router -> route on the device's own logits -> ... -> dgate -> dlogits -> dWr, dx: the chain a
     training step runs, against the oracle fed with the same (device) logits."""
     cfg = W.MoEConfig("custom", T=512, d=128, E=16, k=4, f=64, seed=5)
     inp = W.make_inputs(cfg)
-    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, gather=gather)
+    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, gather=bool(gather), fold=(gather == "fold"))
     x, dout = H.bf16_to_dev(inp["x"]), H.bf16_to_dev(inp["dout"])
     Wg, Wu, Wd = (H.bf16_to_dev(inp[n]) for n in ("Wg", "Wu", "Wd"))
     Wr = torch.from_numpy(inp["Wr"]).to(DEV)
@@ -368,6 +405,22 @@ def test_argument_checks():
                                            B._p(x), B._p(x), B._p(x), B._p(x), None) == -1
     assert lib.moe_grouped_gemm_fwd_gather(B._p(x), 64, None, B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 64, 64,
                                            B._p(x), B._p(x), B._p(x), B._p(x), None) == -1
+    # folded gate weights: the row weights are required, the workspace must hold the strips' partial sums too
+    rw = torch.zeros(128, dtype=torch.float32, device=DEV)
+    rt = torch.zeros(128, dtype=torch.int32, device=DEV)
+    assert lib.moe_grouped_gemm_fwd_folded(B._p(x), 64, B._p(rt), None, B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 64,
+                                           64, B._p(x), B._p(x), B._p(x), B._p(x), None) == -1
+    assert lib.moe_permute_gate(B._p(idx), None, 64, 8, 2, 0, 8, B._p(idx), B._p(rt), B._p(idx), B._p(rw), B._p(x),
+                                1 << 20, None) == -1
+    small = lib.moe_grouped_gemm_bwd_workspace_bytes(64, 64)
+    assert lib.moe_grouped_gemm_bwd_folded_workspace_bytes(64, 64) > small
+    big = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
+    assert lib.moe_grouped_gemm_bwd_folded(B._p(x), B._p(x), 64, 2, B._p(rt), B._p(rw), B._p(idx), B._p(x), B._p(x),
+                                           B._p(x), B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 64, 64, B._p(x),
+                                           B._p(x), B._p(x), B._p(x), B._p(w), B._p(big), small, None) == -2
+    assert lib.moe_grouped_gemm_bwd_folded(B._p(x), B._p(x), 64, 2, B._p(rt), None, B._p(idx), B._p(x), B._p(x),
+                                           B._p(x), B._p(idx), B._p(x), B._p(x), B._p(x), 1, 64, 64, 64, B._p(x),
+                                           B._p(x), B._p(x), B._p(x), B._p(w), B._p(big), 1 << 16, None) == -1
     # router entry points: d must be a multiple of 16, the workspace large enough, pointers aligned
     Wr = torch.zeros(8, 64, dtype=torch.float32, device=DEV)
     lg = torch.zeros(64, 8, dtype=torch.float32, device=DEV)
@@ -383,7 +436,8 @@ def test_argument_checks():
     torch.cuda.synchronize()
 
 
-def test_graph_replay_matches_eager():
+@pytest.mark.parametrize("fold", [False, True])
+def test_graph_replay_matches_eager(fold):
     """The whole step recorded into a HIP graph: every replay, with eager work and
     synchronisations in between, leaves exactly the bits the eager step leaves."""
     cfg = W.MoEConfig("custom", T=700, d=256, E=16, k=4, f=128, seed=11)
@@ -391,11 +445,11 @@ def test_graph_replay_matches_eager():
     x, dout = H.bf16_to_dev(inp["x"]), H.bf16_to_dev(inp["dout"])
     Wg, Wu, Wd = (H.bf16_to_dev(inp[n]) for n in ("Wg", "Wu", "Wd"))
     logits = torch.from_numpy(inp["logits"]).to(DEV)
-    ref = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f)
+    ref = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, fold=fold)
     ref.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
     torch.cuda.synchronize()
     want = {n: t.clone() for n, t in ref.results().items()}
-    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f)
+    buf = B.MoELayerBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, fold=fold)
     graph = buf.capture_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
     for rep in range(3):
         print(f"graph replay {rep}", flush=True)
@@ -406,7 +460,7 @@ def test_graph_replay_matches_eager():
         torch.cuda.synchronize()
         for n, t in buf.results().items():
             R = int(want["expert_offsets"][-1])
-            if n in ("xp", "g", "u", "h", "yp", "dyp", "dxp"):
+            if n in ("xp", "g", "u", "h", "yp", "dyp", "dxp", "hw", "ypw", "row_weight"):
                 assert torch.equal(t[:R], want[n][:R]), n
             elif n == "row_token":
                 assert torch.equal(t[:R], want[n][:R]), n
