@@ -88,8 +88,7 @@ struct GemmArgs {
   const int32_t* row_token;   // not null: rows of the activation operand are gathered, row r lies at A0[row_token[r]]
                               // (GATE_UP, DGRAD_H_GATE, WGRAD_GATHER_A: the A operand; WGRAD_GATHER: the B operand)
   const float* row_weight;    // GATE_UP: not null = h is scaled by the row's gate weight; DGRAD_H_GATE: required
-  float* dgate_part;          // DGRAD_H_GATE: [n_tiles * 4][R_cap] partial dot products, one plane per 64-column strip
-  int R_cap;                  // DGRAD_H_GATE: plane stride of dgate_part
+  float* dgate_part;          // DGRAD_H_GATE: [R_cap][N / 64] partial dot products, one per row and 64-column strip
   int E;
   int K;                // reduction length of one phase (modes 0-3)
   int N;                // output columns (per half for GATE_UP)
@@ -928,12 +927,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
           }
       if constexpr (GATE) {
         if (gcol0 < ae->N) {     // a strip past the last column holds repeated columns: no share
-          float* part = ae->dgate_part + static_cast<size_t>(gcol0 >> 6) * ae->R_cap;
+          const int strips = ae->N >> 6;
+          float* part = ae->dgate_part + (gcol0 >> 6);
 #pragma unroll
           for (int i2 = 0; i2 < NI; ++i2) {
             const float t = dsum[i2] + __shfl_xor(dsum[i2], 32, 64);
             const int r = first + i2 * 32 + lrow;
-            if (lgrp == 0 && r < m_end) part[r] = t;
+            if (lgrp == 0 && r < m_end) part[static_cast<size_t>(r) * strips] = t;
           }
         }
       }
@@ -1160,15 +1160,17 @@ extern "C" int moe_grouped_gemm_bwd_gather(const moe_bf16* dyp, const moe_bf16* 
 // Backward of a forward pass that folded the gate weights into h (moe_grouped_gemm_fwd_folded).
 namespace {
 // dgate[t, i] = sum over the column strips of the row's partial dot products (0 for a slot without a local row)
-__global__ __launch_bounds__(256) void dgate_finish_kernel(const float* __restrict__ part, int planes, int R_cap,
+__global__ __launch_bounds__(256) void dgate_finish_kernel(const float* __restrict__ part, int strips,
                                                            const int32_t* __restrict__ slot_row, int n,
                                                            float* __restrict__ dgate) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= n) return;
   const int row = slot_row[idx];
   float sum = 0.f;
-  if (row >= 0)
-    for (int p = 0; p < planes; ++p) sum += part[static_cast<size_t>(p) * R_cap + row];
+  if (row >= 0) {
+    const float* p = part + static_cast<size_t>(row) * strips;
+    for (int c = 0; c < strips; ++c) sum += p[c];
+  }
   dgate[idx] = sum;
 }
 
@@ -1217,14 +1219,14 @@ extern "C" int moe_grouped_gemm_bwd_folded(const moe_bf16* dout, const moe_bf16*
   // dh0 = dout[token] . Wd; dh = w dh0 -> dg, du; partial dot products of dh0 with h for the gate gradient
   GemmArgs a{};
   a.offsets = expert_offsets; a.E = E; a.m_tiles_cap = m_tiles; a.row_token = row_token; a.row_weight = row_weight;
-  a.dgate_part = part; a.R_cap = R_cap;
+  a.dgate_part = part;
   a.A0 = U16(dout); a.B0 = U16(Wd); a.G = U16(g); a.U = U16(u); a.O0 = dg; a.O1 = du;
   a.K = d; a.N = f; a.n_tiles = (f + BN - 1) / BN;
   int rc = launch_gemm<DGRAD_H_GATE>(a, static_cast<long long>(a.n_tiles) * m_tiles, s, "gemm_dgrad_h");
   if (rc != MOE_OK) return rc;
   const int n = T * k;
   MOE_LAUNCH("dgate_finish", dgate_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, s, static_cast<const float*>(part),
-             f / 64, R_cap, slot_row, n, dgate);
+             f / 64, slot_row, n, dgate);
   // dWg = dg^T x[token] ; dWu = du^T x[token]
   const uint16_t* srcs[2] = {dg, du};
   uint16_t* outs[2] = {dWg, dWu};
