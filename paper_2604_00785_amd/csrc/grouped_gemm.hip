@@ -320,6 +320,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   const int32_t* row_tok = nullptr;     // GATHER_A/B: token of the expert's first reduction row onwards
   uint32_t vcb[4] = {0, 0, 0, 0};       // GATHER_A/B: byte offset of the lane's columns within a token row
   int tokn[4] = {0, 0, 0, 0};           // GATHER_A/B: tokens of the lane's four reduction rows of a coming step
+  int tokn1[4] = {0, 0, 0, 0};          // the same for step 1, while a tile's first loads are set up
   int nk, nk_phase;                     // steps in total / in the first K phase
 
   if constexpr (is_wgrad(MODE)) {
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   // operand is zero there), and their turn into lane offsets of the B loads.  The loads are asynchronous:
   // apply_tok may only run after a wait that covers them.
   const uint32_t tok_voff = static_cast<uint32_t>(((wave * 4) * 2 + (lane >> 5)) * 4);   // row of load 0; load i: + 2 i rows
-  auto fetch_tok = [&](int kt) __attribute__((always_inline)) {
+  auto fetch_tok = [&](int kt, int (&tk)[4]) __attribute__((always_inline)) {
     if constexpr (GATHER_B || GATHER_A) {
       if (k_lo + (kt + 1) * BK > k_hi) {
         const int last = k_hi - k_lo - 1;
@@ -497,24 +498,24 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
         for (int i = 0; i < 4; ++i) {
           int r = kt * BK + (wave * 4 + i) * 2 + (lane >> 5);
           if (r > last) r = last;
-          tokn[i] = load_i32<0>(static_cast<uint32_t>(r) * 4u, row_tok);
+          tk[i] = load_i32<0>(static_cast<uint32_t>(r) * 4u, row_tok);
         }
       } else {
         const int32_t* base = row_tok + static_cast<size_t>(kt) * BK;
-        tokn[0] = load_i32<0>(tok_voff, base);
-        tokn[1] = load_i32<8>(tok_voff, base);
-        tokn[2] = load_i32<16>(tok_voff, base);
-        tokn[3] = load_i32<24>(tok_voff, base);
+        tk[0] = load_i32<0>(tok_voff, base);
+        tk[1] = load_i32<8>(tok_voff, base);
+        tk[2] = load_i32<16>(tok_voff, base);
+        tk[3] = load_i32<24>(tok_voff, base);
       }
     }
   };
-  auto apply_tok = [&]() __attribute__((always_inline)) {
+  auto apply_tok = [&](int (&tk)[4]) __attribute__((always_inline)) {
     if constexpr (GATHER_B || GATHER_A) {
       const uint32_t row_bytes = static_cast<uint32_t>(GATHER_B ? a.N : a.M) * 2u;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        asm volatile("" : "+v"(tokn[i]));   // not before the wait that precedes this call
-        const uint32_t off = static_cast<uint32_t>(tokn[i]) * row_bytes + vcb[i];
+        asm volatile("" : "+v"(tk[i]));   // not before the wait that precedes this call
+        const uint32_t off = static_cast<uint32_t>(tk[i]) * row_bytes + vcb[i];
         if constexpr (GATHER_B) vob[i] = off; else voa[i] = off;
       }
     }
@@ -674,8 +675,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     if constexpr (GATHER_A) {
       // the tokens of A(kt+2) were fetched a step ago and are covered by that step's wait; those of
       // A(kt+3) are requested before the loads of A(kt+2), the only ones this step's wait leaves in flight
-      if (more) apply_tok();
-      if (kt + 3 < nk) fetch_tok(kt + 3);
+      if (more) apply_tok(tokn);
+      if (kt + 3 < nk) fetch_tok(kt + 3, tokn);
     }
     read_frags(SA{}, SB{}, I1{}, I1{}, full_tag);
     lds_wait<nreads(decltype(full_tag)::value)>();  fence();
@@ -707,7 +708,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     fence();
     // B(kt+2) goes into A(kt)'s slot, one load after each MFMA pair
     mma_pair(I1{}, J0{}, full_tag);
-    if (more) { apply_tok(); b_part(kt + 2, SA{}, J0{}); }
+    if (more) { apply_tok(tokn); b_part(kt + 2, SA{}, J0{}); }
     fence();
     mma_pair(I1{}, J1{}, full_tag);
     if (more) b_part(kt + 2, SA{}, J1{});
@@ -720,37 +721,45 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     if constexpr (GATHER_B) {
       // a whole step ahead of their use; the next step's wait for B(kt+2) covers them (they are older
       // than the loads of A(kt+3), the only ones that wait leaves in flight)
-      if (kt + 3 < nk) fetch_tok(kt + 3);
+      if (kt + 3 < nk) fetch_tok(kt + 3, tokn);
     }
     fence();
   };
   auto main_loop = [&](auto full_tag) __attribute__((always_inline)) {
     if (nk > 0) {
       if constexpr (GATHER_B) {
-        fetch_tok(0);
+        // the tokens of steps 0 and 1 are requested first and are older than the eight loads of A(0), A(1):
+        // one wait for both
+        fetch_tok(0, tokn);
+        if (nk > 1) fetch_tok(1, tokn1);
         a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
-        wait_vm<4>();   // the tokens are older than the four loads of A(0)
-        apply_tok();
+        if (nk > 1) {
+          a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
+          wait_vm<8>();
+        } else {
+          wait_vm<4>();
+        }
+        apply_tok(tokn);
         b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
         if (nk > 1) {
-          fetch_tok(1);
-          a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
-          wait_vm<4>();
-          apply_tok();
+          apply_tok(tokn1);
           b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
         }
       } else if constexpr (GATHER_A) {
-        fetch_tok(0);
+        fetch_tok(0, tokn);
+        if (nk > 1) fetch_tok(1, tokn1);
         b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
-        wait_vm<4>();   // the tokens are older than the four loads of B(0)
-        apply_tok();
+        if (nk > 1) {
+          b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
+          wait_vm<8>();
+        } else {
+          wait_vm<4>();
+        }
+        apply_tok(tokn);
         a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
         if (nk > 1) {
-          fetch_tok(1);
-          b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
-          wait_vm<4>();
-          apply_tok();
-          if (nk > 2) fetch_tok(2);   // applied at the start of step 0: older than the loads of A(1)
+          apply_tok(tokn1);
+          if (nk > 2) fetch_tok(2, tokn);   // applied at the start of step 0: older than the loads of A(1)
           a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
         }
       } else {
@@ -763,14 +772,16 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
           if (a_live) a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
         }
       }
-      if constexpr (GATHER_A) {
-        if (nk > 1) wait_vm<4>(); else wait_vm<0>();   // only the loads of A(1) stay in flight: the tokens of A(2) are in
+      if constexpr (GATHER_A || GATHER_B) {
+        // only the last four loads (A(1) or B(1)) stay in flight: both tiles of step 0 are in, and so are
+        // the tokens of A(2)
+        if (nk > 1) wait_vm<4>(); else wait_vm<0>();
       } else {
         if (nk > 1 && a_live) wait_vm<8>(); else if (nk > 1) wait_vm<4>(); else wait_vm<0>();
       }
       wg_barrier();
       if constexpr (GATHER_B) {
-        if (nk > 2) fetch_tok(2);
+        if (nk > 2) fetch_tok(2, tokn);
       }
       read_frags(std::integral_constant<int, slot_of_a(0)>{}, std::integral_constant<int, slot_of_b(0)>{}, I0{}, I0{}, full_tag);
     }
