@@ -218,3 +218,47 @@ def test_layer_entry_point_on_generated_inputs():
         assert np.array_equal(r32["slot_row"], r["slot_row"])
         for n in ("out", "dx", "dWd"):
             assert np.abs(r32[n] - r[n]).max() <= 1e-4 * np.abs(r[n]).max()
+
+
+@pytest.mark.parametrize("EP", [1, 2])
+def test_gate_weights_may_be_folded_into_h(EP):
+    """Stage 5 is linear in the experts' outputs, so the weight of a routed row may multiply h instead of yp.
+    With hw = w h: the unweighted sum of hw.Wd^T rows is `out`; dWd = dout[token]^T hw; dh = w (dout[token].Wd);
+    and the gate gradient is the row dot product of dout[token].Wd with h.  Checked on the oracle's own
+    results (the HIP path has entry points that compute the layer this way)."""
+    rng = np.random.default_rng(17 + EP)
+    T, d, E, k, f = 23, 10, 6, 3, 7
+    p = draw(rng, T, d, E, k, f)
+    nl = E // EP
+    for part in range(EP):
+        eb = part * nl
+        r = oracle_chain(p, eb, nl)
+        off, sr = r["off"], r["sr"]
+        R = int(off[-1])
+        rows = sr[sr >= 0]
+        w_row = np.zeros(R)
+        w_row[rows] = p["w"][sr >= 0]
+        tok = np.zeros(R, dtype=np.int64)
+        tok[rows] = np.nonzero(sr >= 0)[0]
+        Wd = p["Wd"][eb:eb + nl]
+        hw = r["h"] * w_row[:, None]
+        out = np.zeros((T, d))
+        dWd = np.zeros_like(Wd)
+        dgate_rows = np.zeros(R)
+        for e in range(nl):
+            a, b = int(off[e]), int(off[e + 1])
+            ypw = hw[a:b] @ Wd[e].T
+            np.testing.assert_allclose(ypw, r["yp"][a:b] * w_row[a:b, None], rtol=1e-12, atol=1e-14)
+            np.add.at(out, tok[a:b], ypw)
+            dg_rows = p["dout"][tok[a:b]]
+            dWd[e] = dg_rows.T @ hw[a:b]
+            dh0 = dg_rows @ Wd[e]
+            dgate_rows[a:b] = (dh0 * r["h"][a:b]).sum(1)
+            # dh = w dh0 is what the SwiGLU derivative starts from: compare through du = dh silu(g)
+            silu = r["g"][a:b] / (1.0 + np.exp(-r["g"][a:b]))
+            np.testing.assert_allclose(r["du"][a:b], (w_row[a:b, None] * dh0) * silu, rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(out, r["out"], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(dWd, r["dWd"], rtol=1e-11, atol=1e-13)
+        dgate = np.zeros((T, k))
+        dgate[sr >= 0] = dgate_rows[rows]
+        np.testing.assert_allclose(dgate, r["dgate"], rtol=1e-10, atol=1e-13)
