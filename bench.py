@@ -40,8 +40,7 @@ def kernel_work(cfg, R):
         "gemm_dgrad_h": ("mfma", 2 * rdf),
         "gemm_dgrad_x": ("mfma", 4 * rdf),
         "gemm_wgrad_down": ("mfma", 2 * rdf),
-        "gemm_wgrad_gate": ("mfma", 2 * rdf),
-        "gemm_wgrad_up": ("mfma", 2 * rdf),
+        "gemm_wgrad_gate_up": ("mfma", 4 * rdf),
         "permute_rows": ("hbm", row * (T + R)),
         "combine": ("hbm", row * (R + T)),
         "combine_bwd": ("hbm", row * (T + R) + row * R),
@@ -58,7 +57,7 @@ def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` (fetch + write) from the committed rocprofv3 counter summary,
     or None when there is none for this workload."""
     path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
-    key = "gemm_wgrad" if kernel.startswith("gemm_wgrad") else kernel
+    key = {"gemm_wgrad_gate_up": "gemm_wgrad_gate_up", "gemm_wgrad_down": "gemm_wgrad"}.get(kernel, kernel)
     try:
         for line in open(path):
             p = line.split()

@@ -254,8 +254,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   // consecutive tiles (same expert, neighbouring panels) that share its L2.
   int total;
   int lo0 = 0, hi0 = 0;   // this lane's expert's row range, kept for the whole kernel when E <= 64
+  // WGRAD / WGRAD_GATHER with a second A operand (A1 -> O1): two weight gradients that share their B
+  // operand in one launch; an expert's tiles of the first come before its tiles of the second
+  int wpair = 1;
+  if constexpr (MODE == WGRAD_GATHER || MODE == WGRAD) wpair = a.A1 != nullptr ? 2 : 1;
   if constexpr (is_wgrad(MODE)) {
-    total = a.E * a.m_tiles_cap * a.n_tiles;
+    total = a.E * a.m_tiles_cap * a.n_tiles * wpair;
   } else {
     total = count_row_tiles(a.offsets, a.E, tid0 & 63) * a.n_tiles;
     if (a.E <= 64 && (tid0 & 63) < a.E) { lo0 = a.offsets[tid0 & 63]; hi0 = a.offsets[(tid0 & 63) + 1]; }
@@ -270,11 +274,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   int e, m0, m_end, nt;
+  bool second = false;                  // tile of the second weight gradient of a pair
   if constexpr (is_wgrad(MODE)) {
     nt = tile % a.n_tiles;
     const int rest = tile / a.n_tiles;
-    e = rest / a.m_tiles_cap;
-    m0 = (rest % a.m_tiles_cap) * BM;   // output row of dW
+    const int per_expert = a.m_tiles_cap * wpair;
+    e = rest / per_expert;
+    int mi = rest % per_expert;
+    if (mi >= a.m_tiles_cap) { mi -= a.m_tiles_cap; second = true; }
+    m0 = mi * BM;                       // output row of dW
     m_end = a.M;
   } else {
     find_tile(a.offsets, a.E, lo0, hi0, a.n_tiles, tile, lane, e, m0, m_end, nt);
@@ -333,7 +341,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
       a_step = 0;
       row_tok = a.row_token + k_lo;
     } else {
-      abase = reinterpret_cast<const char*>(a.A0 + static_cast<size_t>(k_lo) * a.M + m0);
+      abase = reinterpret_cast<const char*>((second ? a.A1 : a.A0) + static_cast<size_t>(k_lo) * a.M + m0);
       a_step = static_cast<size_t>(BK) * a.M * 2;
     }
     if constexpr (GATHER_B) {
@@ -972,7 +980,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
         for (int q = 0; q < 4; ++q)
           put_quad(i * 32 + lrow, j * 4 + q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
     __builtin_amdgcn_wave_barrier();
-    uint16_t* out = ae->O0;
+    uint16_t* out = second ? ae->O1 : ae->O0;
     if constexpr (is_wgrad(MODE)) out += static_cast<size_t>(e) * ae->M * ae->N;
     flush(out, ae->N, grow0, 128, 0, 8, gcol0, ae->N);
   }
@@ -1118,18 +1126,18 @@ int gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, const int32_t* row_token, 
   a.K = d; a.N = f; a.n_tiles = (f + BN - 1) / BN;
   int rc = launch_gemm<DGRAD_H>(a, static_cast<long long>(a.n_tiles) * m_tiles, s, "gemm_dgrad_h");
   if (rc != MOE_OK) return rc;
-  // weight gradients: dWg = dg^T xp ; dWu = du^T xp (dg, du still warm) ; dWd = dyp^T h
-  struct W { const uint16_t* A; const uint16_t* B; uint16_t* O; int M, N; bool gather; const char* name; };
-  const W jobs[3] = {{dg, U16(xp), dWg, f, d, row_token != nullptr, "gemm_wgrad_gate"},
-                     {du, U16(xp), dWu, f, d, row_token != nullptr, "gemm_wgrad_up"},
-                     {U16(dyp), U16(h), dWd, d, f, false, "gemm_wgrad_down"}};
+  // weight gradients: dWg = dg^T xp and dWu = du^T xp in one launch (dg, du still warm; both read the same
+  // rows of xp) ; dWd = dyp^T h
+  struct W { const uint16_t* A; const uint16_t* A1; const uint16_t* B; uint16_t* O; uint16_t* O1; int M, N; bool gather; const char* name; };
+  const W jobs[2] = {{dg, du, U16(xp), dWg, dWu, f, d, row_token != nullptr, "gemm_wgrad_gate_up"},
+                     {U16(dyp), nullptr, U16(h), dWd, nullptr, d, f, false, "gemm_wgrad_down"}};
   for (const W& j : jobs) {
     GemmArgs w{};
     w.offsets = expert_offsets; w.E = E;
-    w.A0 = j.A; w.B0 = j.B; w.O0 = j.O; w.M = j.M; w.N = j.N;
+    w.A0 = j.A; w.A1 = j.A1; w.B0 = j.B; w.O0 = j.O; w.O1 = j.O1; w.M = j.M; w.N = j.N;
     w.n_tiles = (j.N + BN - 1) / BN;
     w.m_tiles_cap = (j.M + BM - 1) / BM;   // row tiles of one expert's dW
-    const long long tiles = static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E;
+    const long long tiles = static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E * (j.A1 ? 2 : 1);
     if (j.gather) {
       w.row_token = row_token;
       rc = launch_gemm<WGRAD_GATHER>(w, tiles, s, j.name);
@@ -1238,17 +1246,14 @@ extern "C" int moe_grouped_gemm_bwd_folded(const moe_bf16* dout, const moe_bf16*
   const int n = T * k;
   MOE_LAUNCH("dgate_finish", dgate_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, s, static_cast<const float*>(part),
              f / 64, slot_row, n, dgate);
-  // dWg = dg^T x[token] ; dWu = du^T x[token]
-  const uint16_t* srcs[2] = {dg, du};
-  uint16_t* outs[2] = {dWg, dWu};
-  const char* names[2] = {"gemm_wgrad_gate", "gemm_wgrad_up"};
-  for (int j = 0; j < 2; ++j) {
+  // dWg = dg^T x[token] ; dWu = du^T x[token]: one launch, both read the same gathered rows of x
+  {
     GemmArgs w{};
     w.offsets = expert_offsets; w.E = E; w.row_token = row_token;
-    w.A0 = srcs[j]; w.B0 = U16(x); w.O0 = outs[j]; w.M = f; w.N = d;
+    w.A0 = dg; w.A1 = du; w.B0 = U16(x); w.O0 = dWg; w.O1 = dWu; w.M = f; w.N = d;
     w.n_tiles = (d + BN - 1) / BN;
     w.m_tiles_cap = (f + BM - 1) / BM;
-    rc = launch_gemm<WGRAD_GATHER>(w, static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E, s, names[j]);
+    rc = launch_gemm<WGRAD_GATHER>(w, 2ll * w.n_tiles * w.m_tiles_cap * E, s, "gemm_wgrad_gate_up");
     if (rc != MOE_OK) return rc;
   }
   GemmArgs b{};
