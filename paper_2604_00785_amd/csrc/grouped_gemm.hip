@@ -234,24 +234,23 @@ __device__ __forceinline__ void find_tile(const int32_t* offsets, int E, int lo0
 // it is loaded afresh (scalar loads from the argument segment) instead of being kept in scalar
 // registers across the main loop, which needs them for itself.
 typedef const __attribute__((address_space(4))) GemmArgs* ArgPtr;
-__device__ __forceinline__ ArgPtr reload_args() {
-  ArgPtr p = (ArgPtr)__builtin_amdgcn_kernarg_segment_ptr();
+template <int ARG> __device__ __forceinline__ ArgPtr reload_args() {   // ARG: which of the kernel's GemmArgs
+  ArgPtr p = (ArgPtr)__builtin_amdgcn_kernarg_segment_ptr() + ARG;
   asm volatile("" : "+s"(p));
   return p;
 }
 
-template <int MODE>
-__global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) {
+// One product's tile list, walked by this workgroup from list position first_tile in steps of
+// gridDim.x.  Returns the position at which the workgroup left the list, counted from its end:
+// where it enters a list that follows in the same launch.
+template <int MODE, int ARG>
+__device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid0 = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
   const int wm = wave >> 2, wn = wave & 3;
 
   // ---------------- tile list ---------------------------------------------------
-  // The launch is persistent: gridDim.x workgroups (one per compute unit) walk the tile list.
-  // Workgroups are dealt to the 8 XCDs round-robin, so workgroup b takes position
-  // (b % 8) * (gridDim.x / 8) + b / 8 of every round: each XCD then works on a run of
-  // consecutive tiles (same expert, neighbouring panels) that share its L2.
   int total;
   int lo0 = 0, hi0 = 0;   // this lane's expert's row range, kept for the whole kernel when E <= 64
   // WGRAD / WGRAD_GATHER with a second A operand (A1 -> O1): two weight gradients that share their B
@@ -264,10 +263,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     total = count_row_tiles(a.offsets, a.E, tid0 & 63) * a.n_tiles;
     if (a.E <= 64 && (tid0 & 63) < a.E) { lo0 = a.offsets[tid0 & 63]; hi0 = a.offsets[(tid0 & 63) + 1]; }
   }
-  const int per_xcd = gridDim.x >> 3;
-  const int first_tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-
-  for (int tile = first_tile; tile < total; tile += gridDim.x) {
+  int tile = first_tile;
+  for (; tile < total; tile += gridDim.x) {
   // the thread id is laundered per tile so that lane-dependent address pieces are recomputed for
   // every tile instead of staying live (and spilling) across the whole loop
   int tid = tid0;
@@ -810,7 +807,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
     case 1: main_loop(std::integral_constant<int, 1>{}); break;
     default: main_loop(std::integral_constant<int, 0>{}); break;
   }
-  const ArgPtr ae = reload_args();          // the epilogue reads its arguments afresh
+  const ArgPtr ae = reload_args<ARG>();     // the epilogue reads its arguments afresh
   gu_load(0, ae);
   wg_barrier();                             // every wave is done with the operand tiles
 
@@ -987,6 +984,30 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) 
   __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's staging reads are done
   wg_barrier();      // the staging area becomes operand stages again
   }  // tile loop
+  return tile - total;
+}
+
+// The launch is persistent: gridDim.x workgroups (one per compute unit) walk the tile list.
+// Workgroups are dealt to the 8 XCDs round-robin, so workgroup b takes position
+// (b % 8) * (gridDim.x / 8) + b / 8 of every round: each XCD then works on a run of
+// consecutive tiles (same expert, neighbouring panels) that share its L2.
+__device__ __forceinline__ int first_list_position() {
+  const int per_xcd = gridDim.x >> 3;
+  return (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs a) {
+  gemm_tile_list<MODE, 0>(a, first_list_position());
+}
+
+// Two products that do not depend on each other in one launch: the tile list of the second follows
+// that of the first, so the workgroups that run out of tiles of the first go on with the second
+// instead of idling until the next launch (one tail and one start-up instead of two).
+template <int MODE_A, int MODE_B>
+__global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_pair_kernel(GemmArgs a, GemmArgs b) {
+  const int next = gemm_tile_list<MODE_A, 0>(a, first_list_position());
+  gemm_tile_list<MODE_B, 1>(b, next);
 }
 
 // Workgroups of the persistent launch: one per compute unit (the 160 KB of LDS allow no more),
@@ -1020,6 +1041,22 @@ int launch_gemm(const GemmArgs& a, long long max_tiles, hipStream_t s, const cha
     configured = true;
   }
   MOE_LAUNCH(name, grouped_gemm_kernel<MODE>, grid, dim3(GEMM_THREADS), LDS_BYTES, s, a);
+  return moe_check_launch();
+}
+
+template <int MODE_A, int MODE_B>
+int launch_gemm_pair(const GemmArgs& a, const GemmArgs& b, long long max_tiles, hipStream_t s, const char* name) {
+  const dim3 grid(persistent_grid(max_tiles));
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_gemm_pair_kernel<MODE_A, MODE_B>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
+      (void)hipGetLastError();
+      return MOE_ERR_LAUNCH;
+    }
+    configured = true;
+  }
+  MOE_LAUNCH(name, (grouped_gemm_pair_kernel<MODE_A, MODE_B>), grid, dim3(GEMM_THREADS), LDS_BYTES, s, a, b);
   return moe_check_launch();
 }
 
@@ -1119,39 +1156,36 @@ int gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, const int32_t* row_token, 
   uint16_t* dg = static_cast<uint16_t*>(ws);
   uint16_t* du = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + moe_grouped_gemm_bwd_workspace_bytes(R_cap, f) / 2);
 
-  // dh = dyp . Wd, then the SwiGLU derivative -> dg, du
+  // Two launches of two independent products each (the second list of a launch takes over the workgroups
+  // that the first leaves idle at its end).
+  // dWd = dyp^T h ; dh = dyp . Wd, then the SwiGLU derivative -> dg, du
+  GemmArgs wd{};
+  wd.offsets = expert_offsets; wd.E = E;
+  wd.A0 = U16(dyp); wd.B0 = U16(h); wd.O0 = dWd; wd.M = d; wd.N = f;
+  wd.n_tiles = (f + BN - 1) / BN;
+  wd.m_tiles_cap = (d + BM - 1) / BM;   // row tiles of one expert's dW
   GemmArgs a{};
   a.offsets = expert_offsets; a.E = E; a.m_tiles_cap = m_tiles;
   a.A0 = U16(dyp); a.B0 = U16(Wd); a.G = U16(g); a.U = U16(u); a.O0 = dg; a.O1 = du;
   a.K = d; a.N = f; a.n_tiles = (f + BN - 1) / BN;
-  int rc = launch_gemm<DGRAD_H>(a, static_cast<long long>(a.n_tiles) * m_tiles, s, "gemm_dgrad_h");
+  int rc = launch_gemm_pair<WGRAD, DGRAD_H>(wd, a, static_cast<long long>(wd.n_tiles) * wd.m_tiles_cap * E +
+                                                       static_cast<long long>(a.n_tiles) * m_tiles,
+                                            s, "gemm_wgrad_down+dgrad_h");
   if (rc != MOE_OK) return rc;
-  // weight gradients: dWg = dg^T xp and dWu = du^T xp in one launch (dg, du still warm; both read the same
-  // rows of xp) ; dWd = dyp^T h
-  struct W { const uint16_t* A; const uint16_t* A1; const uint16_t* B; uint16_t* O; uint16_t* O1; int M, N; bool gather; const char* name; };
-  const W jobs[2] = {{dg, du, U16(xp), dWg, dWu, f, d, row_token != nullptr, "gemm_wgrad_gate_up"},
-                     {U16(dyp), nullptr, U16(h), dWd, nullptr, d, f, false, "gemm_wgrad_down"}};
-  for (const W& j : jobs) {
-    GemmArgs w{};
-    w.offsets = expert_offsets; w.E = E;
-    w.A0 = j.A; w.A1 = j.A1; w.B0 = j.B; w.O0 = j.O; w.O1 = j.O1; w.M = j.M; w.N = j.N;
-    w.n_tiles = (j.N + BN - 1) / BN;
-    w.m_tiles_cap = (j.M + BM - 1) / BM;   // row tiles of one expert's dW
-    const long long tiles = static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E * (j.A1 ? 2 : 1);
-    if (j.gather) {
-      w.row_token = row_token;
-      rc = launch_gemm<WGRAD_GATHER>(w, tiles, s, j.name);
-    } else {
-      rc = launch_gemm<WGRAD>(w, tiles, s, j.name);
-    }
-    if (rc != MOE_OK) return rc;
-  }
-  // dxp = dg . Wg + du . Wu  (last, so that the dx reduction that follows finds dxp in the last-level cache)
+  // dWg = dg^T xp and dWu = du^T xp (one list: both read the same rows of xp) ; dxp = dg . Wg + du . Wu
+  // (last, so that the dx reduction that follows finds dxp in the last-level cache)
+  GemmArgs w{};
+  w.offsets = expert_offsets; w.E = E; w.row_token = row_token;
+  w.A0 = dg; w.A1 = du; w.B0 = U16(xp); w.O0 = dWg; w.O1 = dWu; w.M = f; w.N = d;
+  w.n_tiles = (d + BN - 1) / BN;
+  w.m_tiles_cap = (f + BM - 1) / BM;
   GemmArgs b{};
   b.offsets = expert_offsets; b.E = E; b.m_tiles_cap = m_tiles;
   b.A0 = dg; b.A1 = du; b.B0 = U16(Wg); b.B1 = U16(Wu); b.O0 = dxp;
   b.K = f; b.N = d; b.n_tiles = (d + BN - 1) / BN;
-  return launch_gemm<DGRAD_X>(b, static_cast<long long>(b.n_tiles) * m_tiles, s, "gemm_dgrad_x");
+  const long long tiles = 2ll * w.n_tiles * w.m_tiles_cap * E + static_cast<long long>(b.n_tiles) * m_tiles;
+  if (row_token != nullptr) return launch_gemm_pair<WGRAD_GATHER, DGRAD_X>(w, b, tiles, s, "gemm_wgrad_gate_up+dgrad_x");
+  return launch_gemm_pair<WGRAD, DGRAD_X>(w, b, tiles, s, "gemm_wgrad_gate_up+dgrad_x");
 }
 }  // namespace
 
@@ -1225,40 +1259,38 @@ extern "C" int moe_grouped_gemm_bwd_folded(const moe_bf16* dout, const moe_bf16*
   uint16_t* du = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + one);
   float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + 2 * one);
 
-  // dWd = (w dout[token])^T h = dout[token]^T hw: rows of dout gathered by the loads of the A operand
-  {
-    GemmArgs w{};
-    w.offsets = expert_offsets; w.E = E; w.row_token = row_token;
-    w.A0 = U16(dout); w.B0 = U16(hw); w.O0 = dWd; w.M = d; w.N = f;
-    w.n_tiles = (f + BN - 1) / BN;
-    w.m_tiles_cap = (d + BM - 1) / BM;
-    int rc = launch_gemm<WGRAD_GATHER_A>(w, static_cast<long long>(w.n_tiles) * w.m_tiles_cap * E, s, "gemm_wgrad_down");
-    if (rc != MOE_OK) return rc;
-  }
+  // Two launches of two independent products each (the second list of a launch takes over the workgroups
+  // that the first leaves idle at its end).
+  // dWd = (w dout[token])^T h = dout[token]^T hw: rows of dout gathered by the loads of the A operand;
   // dh0 = dout[token] . Wd; dh = w dh0 -> dg, du; partial dot products of dh0 with h for the gate gradient
+  GemmArgs wd{};
+  wd.offsets = expert_offsets; wd.E = E; wd.row_token = row_token;
+  wd.A0 = U16(dout); wd.B0 = U16(hw); wd.O0 = dWd; wd.M = d; wd.N = f;
+  wd.n_tiles = (f + BN - 1) / BN;
+  wd.m_tiles_cap = (d + BM - 1) / BM;
+  const long long wd_tiles = static_cast<long long>(wd.n_tiles) * wd.m_tiles_cap * E;
   GemmArgs a{};
   a.offsets = expert_offsets; a.E = E; a.m_tiles_cap = m_tiles; a.row_token = row_token; a.row_weight = row_weight;
   a.dgate_part = part;
   a.A0 = U16(dout); a.B0 = U16(Wd); a.G = U16(g); a.U = U16(u); a.O0 = dg; a.O1 = du;
   a.K = d; a.N = f; a.n_tiles = (f + BN - 1) / BN;
-  int rc = launch_gemm<DGRAD_H_GATE>(a, static_cast<long long>(a.n_tiles) * m_tiles, s, "gemm_dgrad_h");
+  int rc = launch_gemm_pair<WGRAD_GATHER_A, DGRAD_H_GATE>(wd, a, wd_tiles + static_cast<long long>(a.n_tiles) * m_tiles, s,
+                                                          "gemm_wgrad_down+dgrad_h");
   if (rc != MOE_OK) return rc;
   const int n = T * k;
   MOE_LAUNCH("dgate_finish", dgate_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, s, static_cast<const float*>(part),
              f / 64, slot_row, n, dgate);
-  // dWg = dg^T x[token] ; dWu = du^T x[token]: one launch, both read the same gathered rows of x
-  {
-    GemmArgs w{};
-    w.offsets = expert_offsets; w.E = E; w.row_token = row_token;
-    w.A0 = dg; w.A1 = du; w.B0 = U16(x); w.O0 = dWg; w.O1 = dWu; w.M = f; w.N = d;
-    w.n_tiles = (d + BN - 1) / BN;
-    w.m_tiles_cap = (f + BM - 1) / BM;
-    rc = launch_gemm<WGRAD_GATHER>(w, 2ll * w.n_tiles * w.m_tiles_cap * E, s, "gemm_wgrad_gate_up");
-    if (rc != MOE_OK) return rc;
-  }
+  // dWg = dg^T x[token] and dWu = du^T x[token] (one list: both read the same gathered rows of x), then
+  // dxp = dg . Wg + du . Wu
+  GemmArgs w{};
+  w.offsets = expert_offsets; w.E = E; w.row_token = row_token;
+  w.A0 = dg; w.A1 = du; w.B0 = U16(x); w.O0 = dWg; w.O1 = dWu; w.M = f; w.N = d;
+  w.n_tiles = (d + BN - 1) / BN;
+  w.m_tiles_cap = (f + BM - 1) / BM;
   GemmArgs b{};
   b.offsets = expert_offsets; b.E = E; b.m_tiles_cap = m_tiles;
   b.A0 = dg; b.A1 = du; b.B0 = U16(Wg); b.B1 = U16(Wu); b.O0 = dxp;
   b.K = f; b.N = d; b.n_tiles = (d + BN - 1) / BN;
-  return launch_gemm<DGRAD_X>(b, static_cast<long long>(b.n_tiles) * m_tiles, s, "gemm_dgrad_x");
+  return launch_gemm_pair<WGRAD_GATHER, DGRAD_X>(w, b, 2ll * w.n_tiles * w.m_tiles_cap * E + static_cast<long long>(b.n_tiles) * m_tiles,
+                                                 s, "gemm_wgrad_gate_up+dgrad_x");
 }
