@@ -59,7 +59,7 @@ def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` (fetch + write) from the committed rocprofv3 counter summary,
     or None when there is none for this workload."""
     path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
-    key = {"gemm_wgrad_gate_up": "gemm_wgrad_gate_up", "gemm_wgrad_down": "gemm_wgrad"}.get(kernel, kernel)
+    key = kernel
     try:
         for line in open(path):
             p = line.split()
