@@ -130,8 +130,8 @@ extern "C" int moe_route(const float* logits, int T, int E, int k, int renormali
   if (E <= 8) launch_route<8, 1>(logits, T, E, k, r, topk_idx, topk_w, s);
   else if (E <= 16) launch_route<16, 1>(logits, T, E, k, r, topk_idx, topk_w, s);
   else if (E <= 32) launch_route<32, 1>(logits, T, E, k, r, topk_idx, topk_w, s);
-  else if (E <= 64) launch_route<64, 1>(logits, T, E, k, r, topk_idx, topk_w, s);
-  else if (E <= 128) launch_route<64, 2>(logits, T, E, k, r, topk_idx, topk_w, s);
+  else if (E <= 64) launch_route<16, 4>(logits, T, E, k, r, topk_idx, topk_w, s);
+  else if (E <= 128) launch_route<32, 4>(logits, T, E, k, r, topk_idx, topk_w, s);
   else if (E <= 256) launch_route<64, 4>(logits, T, E, k, r, topk_idx, topk_w, s);
   else launch_route<64, 8>(logits, T, E, k, r, topk_idx, topk_w, s);
   return moe_check_launch();
