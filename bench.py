@@ -41,7 +41,7 @@ def kernel_work(cfg, R):
         "gemm_dgrad_x": ("mfma", 4 * rdf),
         "gemm_wgrad_down": ("mfma", 2 * rdf),
         "gemm_wgrad_gate_up": ("mfma", 4 * rdf),
-        "gemm_wgrad_down+dgrad_h": ("mfma", 4 * rdf),          # two independent products in one launch
+        "gemm_dgrad_h+wgrad_down": ("mfma", 4 * rdf),          # two independent products in one launch
         "gemm_wgrad_gate_up+dgrad_x": ("mfma", 8 * rdf),       # three
         "permute_rows": ("hbm", row * (T + R)),
         "combine": ("hbm", row * (R + T)),

@@ -1158,7 +1158,7 @@ int gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, const int32_t* row_token, 
 
   // Two launches of two independent products each (the second list of a launch takes over the workgroups
   // that the first leaves idle at its end).
-  // dWd = dyp^T h ; dh = dyp . Wd, then the SwiGLU derivative -> dg, du
+  // dh = dyp . Wd, then the SwiGLU derivative -> dg, du (first: its tiles are the long ones) ; dWd = dyp^T h
   GemmArgs wd{};
   wd.offsets = expert_offsets; wd.E = E;
   wd.A0 = U16(dyp); wd.B0 = U16(h); wd.O0 = dWd; wd.M = d; wd.N = f;
@@ -1168,9 +1168,9 @@ int gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, const int32_t* row_token, 
   a.offsets = expert_offsets; a.E = E; a.m_tiles_cap = m_tiles;
   a.A0 = U16(dyp); a.B0 = U16(Wd); a.G = U16(g); a.U = U16(u); a.O0 = dg; a.O1 = du;
   a.K = d; a.N = f; a.n_tiles = (f + BN - 1) / BN;
-  int rc = launch_gemm_pair<WGRAD, DGRAD_H>(wd, a, static_cast<long long>(wd.n_tiles) * wd.m_tiles_cap * E +
+  int rc = launch_gemm_pair<DGRAD_H, WGRAD>(a, wd, static_cast<long long>(wd.n_tiles) * wd.m_tiles_cap * E +
                                                        static_cast<long long>(a.n_tiles) * m_tiles,
-                                            s, "gemm_wgrad_down+dgrad_h");
+                                            s, "gemm_dgrad_h+wgrad_down");
   if (rc != MOE_OK) return rc;
   // dWg = dg^T xp and dWu = du^T xp (one list: both read the same rows of xp) ; dxp = dg . Wg + du . Wu
   // (last, so that the dx reduction that follows finds dxp in the last-level cache)
@@ -1261,8 +1261,9 @@ extern "C" int moe_grouped_gemm_bwd_folded(const moe_bf16* dout, const moe_bf16*
 
   // Two launches of two independent products each (the second list of a launch takes over the workgroups
   // that the first leaves idle at its end).
-  // dWd = (w dout[token])^T h = dout[token]^T hw: rows of dout gathered by the loads of the A operand;
   // dh0 = dout[token] . Wd; dh = w dh0 -> dg, du; partial dot products of dh0 with h for the gate gradient
+  // (first: its tiles are the long ones);
+  // dWd = (w dout[token])^T h = dout[token]^T hw: rows of dout gathered by the loads of the A operand
   GemmArgs wd{};
   wd.offsets = expert_offsets; wd.E = E; wd.row_token = row_token;
   wd.A0 = U16(dout); wd.B0 = U16(hw); wd.O0 = dWd; wd.M = d; wd.N = f;
@@ -1274,8 +1275,8 @@ extern "C" int moe_grouped_gemm_bwd_folded(const moe_bf16* dout, const moe_bf16*
   a.dgate_part = part;
   a.A0 = U16(dout); a.B0 = U16(Wd); a.G = U16(g); a.U = U16(u); a.O0 = dg; a.O1 = du;
   a.K = d; a.N = f; a.n_tiles = (f + BN - 1) / BN;
-  int rc = launch_gemm_pair<WGRAD_GATHER_A, DGRAD_H_GATE>(wd, a, wd_tiles + static_cast<long long>(a.n_tiles) * m_tiles, s,
-                                                          "gemm_wgrad_down+dgrad_h");
+  int rc = launch_gemm_pair<DGRAD_H_GATE, WGRAD_GATHER_A>(a, wd, wd_tiles + static_cast<long long>(a.n_tiles) * m_tiles, s,
+                                                          "gemm_dgrad_h+wgrad_down");
   if (rc != MOE_OK) return rc;
   const int n = T * k;
   MOE_LAUNCH("dgate_finish", dgate_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, s, static_cast<const float*>(part),
