@@ -105,7 +105,7 @@ def main():
                          "instead of folding them into h, which takes dgate out of the backward product of the "
                          "down projection and needs no backward pass over the [R, d] rows")
     ap.add_argument("--graph", action="store_true",
-                    help="time the step as one HIP graph replay instead of fifteen stream launches "
+                    help="time the step as one HIP graph replay instead of a dozen stream launches "
                          "(measured: no faster, the launches already queue ahead of the GPU)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 "
@@ -141,7 +141,7 @@ def main():
     def eager_step():
         buf.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
 
-    if args.graph:   # the same fifteen launches, recorded once into a HIP graph and replayed
+    if args.graph:   # the same launches, recorded once into a HIP graph and replayed
         graph = buf.capture_fwd_bwd(x, logits, dout, Wg, Wu, Wd)
         step = graph.replay
     else:

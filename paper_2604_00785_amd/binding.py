@@ -484,7 +484,7 @@ class MoELayerBuffers:
 
         The entry points only launch kernels (no allocation, no memset, no host
         synchronisation), so the whole step can be captured; ``replay()`` then
-        runs it again with one submission instead of fifteen launches.  Profiling
+        runs it again with one submission instead of a dozen launches.  Profiling
         (``moe_prof_enable``) must be off while capturing.
         """
         self.run_fwd_bwd(x, logits, dout, Wg, Wu, Wd)   # loads every kernel before the capture
