@@ -14,6 +14,12 @@
  *   moe_grouped_gemm_bwd      derivative of Stage 4 (dgrad + wgrad; left to autograd in the paper)
  *   moe_permute_bwd           derivative of the Stage-4 gather
  *
+ * Fused variants of the same stages: moe_grouped_gemm_fwd_gather / _bwd_gather (the products read the routed
+ * rows of x themselves, no permuted copy), and moe_permute_gate, moe_grouped_gemm_fwd_folded,
+ * moe_unpermute_sum, moe_grouped_gemm_bwd_folded (gate weights folded into the expert MLP: Stage 5 becomes a
+ * plain sum and needs no backward pass of its own).  Stage 1's Router layer and the derivatives of Stage 1:
+ * moe_router_fwd, moe_route_bwd, moe_router_bwd.
+ *
  * Conventions, valid for every function below
  * -------------------------------------------
  * - Every pointer except `stream` is a DEVICE pointer to memory the caller owns,
