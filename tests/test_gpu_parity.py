@@ -241,6 +241,9 @@ def test_layer_gathered_rows(T, d, E, k, f, eb, ec, renorm):
     (64, 64, 300, 9, 64, 100, 150, 1),    # most experts empty, experts with a single row
     (3000, 512, 3, 1, 192, 0, 3, 1),      # about 1000 rows per expert: many reduction steps in the weight gradients
     (1, 64, 4, 2, 64, 0, 4, 1),           # a single token
+    (300, 64, 130, 5, 64, 0, 130, 1),     # more than 64 local experts (tile lookup in two passes), one column strip
+    (513, 320, 70, 6, 192, 3, 67, 0),     # odd sizes, a local slice of more than 64 experts, no renormalisation
+    (2000, 256, 2, 2, 448, 0, 2, 1),      # two big experts: many row tiles each, seven column strips
 ])
 def test_layer_folded_gate_weights(T, d, E, k, f, eb, ec, renorm):
     """The path that folds the gate weights into h and takes dgate from the backward product of the down
