@@ -26,7 +26,10 @@
  *   16-byte aligned, dense and row-major.  The library allocates nothing, frees
  *   nothing and never synchronises: all work is enqueued on `stream`
  *   (a hipStream_t passed as void*; NULL is the default stream).  Results are
- *   ready when the stream reaches them.
+ *   ready when the stream reaches them.  The only state the library keeps between
+ *   calls is, per device, what it has looked up or configured once there (number of
+ *   compute units, the kernels' LDS limit) and the benchmark facility at the end
+ *   of this file.
  * - Outputs are overwritten, never accumulated into (weight gradients of
  *   experts without rows are written as zeros).
  * - Group sizes stay on the device (`expert_offsets`); no call reads them back.
@@ -72,7 +75,10 @@ const char* moe_version(void);
 /* Workspace sizes in bytes (host computation only). */
 size_t moe_permute_workspace_bytes(int T, int k, int e_count);
 size_t moe_grouped_gemm_bwd_workspace_bytes(int R_cap, int f);
-/* Upper bound that is enough for any call on a layer of this shape. */
+/* Upper bound that is enough for any call on a layer of this shape with R_cap <= T*k and at most E local
+ * experts: the largest of moe_permute_workspace_bytes(T, k, E), moe_grouped_gemm_bwd_workspace_bytes(T*k, f),
+ * moe_grouped_gemm_bwd_folded_workspace_bytes(T*k, f) and moe_router_bwd_workspace_bytes(T, d, E).
+ * 0 for a non-positive size or when T*k does not fit an int. */
 size_t moe_workspace_bytes(int T, int E, int k, int d, int f);
 
 /*

@@ -417,10 +417,8 @@ class MoELayerBuffers:
         self.out, self.dx = z(T, d), z(T, d)
         self.dgate = z(T, k, dt=torch.float32)
         self.dWg, self.dWu, self.dWd = z(nl, f, d), z(nl, f, d), z(nl, d, f)
-        ws_bytes = max(moe_permute_workspace_bytes(T, k, nl), moe_grouped_gemm_bwd_workspace_bytes(R, f), 256)
-        if fold:
-            ws_bytes = max(ws_bytes, moe_grouped_gemm_bwd_folded_workspace_bytes(R, f))
-        self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
+        # one workspace for every call of the layer (the router's backward included)
+        self.ws = torch.zeros(max(moe_workspace_bytes(T, E, k, d, f), 256), dtype=torch.uint8, device=dev)
 
     def run_fwd(self, x, logits, Wg, Wu, Wd) -> None:
         moe_route(logits, self.k, self.renormalize, self.topk_idx, self.topk_w)
@@ -466,18 +464,16 @@ class MoELayerBuffers:
         """The layer as a drop-in block: the router's Linear layer in front (logits from ``x`` and
         ``Wr``), and behind the expert path the gradient of the gates pushed back to the logits, to
         ``dWr`` and into ``dx`` (which then holds the expert path's and the router's share).  The
-        buffers ``logits``, ``dlogits``, ``dWr`` and the router workspace are created on first use."""
+        buffers ``logits``, ``dlogits`` and ``dWr`` are created on first use."""
         if getattr(self, "logits", None) is None:
             dev = x.device
             self.logits = torch.zeros(self.T, self.E, dtype=torch.float32, device=dev)
             self.dlogits = torch.zeros(self.T, self.E, dtype=torch.float32, device=dev)
             self.dWr = torch.zeros(self.E, self.d, dtype=torch.float32, device=dev)
-            self.router_ws = torch.zeros(max(moe_router_bwd_workspace_bytes(self.T, self.d, self.E), 256),
-                                         dtype=torch.uint8, device=dev)
         moe_router_fwd(x, Wr, self.logits)
         self.run_fwd_bwd(x, self.logits, dout, Wg, Wu, Wd)
         moe_route_bwd(self.logits, self.topk_idx, self.dgate, self.renormalize, self.dlogits)
-        moe_router_bwd(x, Wr, self.dlogits, self.dx, self.dWr, self.router_ws)
+        moe_router_bwd(x, Wr, self.dlogits, self.dx, self.dWr, self.ws)   # the layer's one workspace is free again here
 
     def capture_fwd_bwd(self, x, logits, dout, Wg, Wu, Wd) -> "torch.cuda.CUDAGraph":
         """Record ``run_fwd_bwd`` on these buffers and arguments into a HIP graph.

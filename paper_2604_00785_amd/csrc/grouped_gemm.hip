@@ -1012,34 +1012,51 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_pair_kernel(GemmArg
 
 // Workgroups of the persistent launch: one per compute unit (the 160 KB of LDS allow no more),
 // a multiple of 8 so that every XCD gets the same share, and no more than there can be tiles.
+// Per-device facts, looked up once per device: HIP keeps function attributes and the number of compute
+// units per device, and a process may drive several.  Races between host threads are benign (both write
+// the same values).
+constexpr int MAX_DEVICES = 64;
+int current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = 0; }
+  return dev >= 0 && dev < MAX_DEVICES ? dev : 0;
+}
 int persistent_grid(long long max_tiles) {
-  static int cus = 0;
+  static int cus_of[MAX_DEVICES] = {};
+  const int dev = current_device();
+  int cus = cus_of[dev];
   if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) {
       (void)hipGetLastError();
       n = 256;
     }
-    cus = n & ~7;
+    cus = cus_of[dev] = n & ~7;
   }
   long long g = (max_tiles + 7) & ~7ll;
   if (g > cus) g = cus;
   if (g < 8) g = 8;
   return static_cast<int>(g);
 }
+// Raises the kernel's dynamic-LDS limit on the current device, once per device.
+template <typename K>
+int configure_lds(K kernel, bool (&done)[MAX_DEVICES]) {
+  const int dev = current_device();
+  if (done[dev]) return MOE_OK;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) !=
+      hipSuccess) {
+    (void)hipGetLastError();
+    return MOE_ERR_LAUNCH;
+  }
+  done[dev] = true;
+  return MOE_OK;
+}
 
 template <int MODE>
 int launch_gemm(const GemmArgs& a, long long max_tiles, hipStream_t s, const char* name) {
   const dim3 grid(persistent_grid(max_tiles));
-  static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_gemm_kernel<MODE>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
-      (void)hipGetLastError();
-      return MOE_ERR_LAUNCH;
-    }
-    configured = true;
-  }
+  static bool configured[MAX_DEVICES] = {};
+  if (configure_lds(&grouped_gemm_kernel<MODE>, configured) != MOE_OK) return MOE_ERR_LAUNCH;
   MOE_LAUNCH(name, grouped_gemm_kernel<MODE>, grid, dim3(GEMM_THREADS), LDS_BYTES, s, a);
   return moe_check_launch();
 }
@@ -1047,15 +1064,8 @@ int launch_gemm(const GemmArgs& a, long long max_tiles, hipStream_t s, const cha
 template <int MODE_A, int MODE_B>
 int launch_gemm_pair(const GemmArgs& a, const GemmArgs& b, long long max_tiles, hipStream_t s, const char* name) {
   const dim3 grid(persistent_grid(max_tiles));
-  static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_gemm_pair_kernel<MODE_A, MODE_B>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
-      (void)hipGetLastError();
-      return MOE_ERR_LAUNCH;
-    }
-    configured = true;
-  }
+  static bool configured[MAX_DEVICES] = {};
+  if (configure_lds(&grouped_gemm_pair_kernel<MODE_A, MODE_B>, configured) != MOE_OK) return MOE_ERR_LAUNCH;
   MOE_LAUNCH(name, (grouped_gemm_pair_kernel<MODE_A, MODE_B>), grid, dim3(GEMM_THREADS), LDS_BYTES, s, a, b);
   return moe_check_launch();
 }
@@ -1075,11 +1085,16 @@ extern "C" size_t moe_grouped_gemm_bwd_workspace_bytes(int R_cap, int f) {
 }
 
 extern "C" size_t moe_workspace_bytes(int T, int E, int k, int d, int f) {
-  (void)d;
-  if (T <= 0 || k <= 0 || E <= 0) return 0;
-  const size_t p = moe_permute_workspace_bytes(T, k, E);
-  const size_t b = moe_grouped_gemm_bwd_workspace_bytes(T * k, f);
-  return p > b ? p : b;
+  if (T <= 0 || k <= 0 || E <= 0 || d <= 0 || f <= 0) return 0;
+  const unsigned long long rows = static_cast<unsigned long long>(T) * static_cast<unsigned long long>(k);
+  if (rows > 0x7FFFFFFFull) return 0;   // no call takes that many routed rows
+  const int R_cap = static_cast<int>(rows);
+  // the largest of every workspace any call may ask for on a layer of this shape
+  const size_t sizes[] = {moe_permute_workspace_bytes(T, k, E), moe_grouped_gemm_bwd_workspace_bytes(R_cap, f),
+                          moe_grouped_gemm_bwd_folded_workspace_bytes(R_cap, f), moe_router_bwd_workspace_bytes(T, d, E)};
+  size_t m = 0;
+  for (size_t v : sizes) m = v > m ? v : m;
+  return m;
 }
 
 namespace {

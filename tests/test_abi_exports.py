@@ -29,6 +29,7 @@ def test_host_only_calls():
     assert B.moe_grouped_gemm_bwd_workspace_bytes(65536, 1024) >= 2 * 65536 * 1024 * 2
     assert B.moe_workspace_bytes(8192, 64, 8, 2048, 1024) >= B.moe_grouped_gemm_bwd_workspace_bytes(65536, 1024)
     assert B.moe_workspace_bytes(0, 64, 8, 2048, 1024) == 0
+    assert B.moe_workspace_bytes(1 << 30, 64, 8, 2048, 1024) == 0     # T*k does not fit an int
     # null pointers are rejected on the host before any GPU work
     lib = B.load()
     assert lib.moe_route(None, 1, 1, 1, 1, None, None, None) == -1
@@ -93,3 +94,27 @@ def test_host_only_calls_folded_gate_weights():
                                            None, None, None, None, None) == -1
     assert lib.moe_grouped_gemm_bwd_folded(None, None, 64, 2, None, None, None, None, None, None, None, None, None,
                                            None, 1, 64, 64, 64, None, None, None, None, None, None, 0, None) == -1
+
+
+def test_moe_workspace_bytes_covers_every_call():
+    """The one-size-fits-all bound is at least every specific workspace size, over a grid of shapes
+    (among them one where the router's partial sums are the largest, and the headline shape, where
+    the folded backward product's are)."""
+    import itertools
+    shapes = list(itertools.product((1, 256, 8192, 16384), (1, 8, 64, 512), (1, 2, 8), (64, 2048, 4096), (64, 512, 1024)))
+    shapes += [(8192, 64, 1, 4096, 64), (8192, 64, 8, 2048, 1024), (32768, 64, 8, 4096, 2048)]
+    for T, E, k, d, f in shapes:
+        if k > E:
+            continue
+        total = B.moe_workspace_bytes(T, E, k, d, f)
+        parts = {
+            "permute": B.moe_permute_workspace_bytes(T, k, E),
+            "bwd": B.moe_grouped_gemm_bwd_workspace_bytes(T * k, f),
+            "bwd_folded": B.moe_grouped_gemm_bwd_folded_workspace_bytes(T * k, f),
+            "router_bwd": B.moe_router_bwd_workspace_bytes(T, d, E),
+        }
+        for name, v in parts.items():
+            assert total >= v, (name, (T, E, k, d, f), total, v)
+        assert total == max(parts.values())
+    assert B.moe_workspace_bytes(8192, 64, 8, 2048, 1024) == B.moe_grouped_gemm_bwd_folded_workspace_bytes(65536, 1024)
+    assert B.moe_workspace_bytes(8192, 64, 1, 4096, 64) == B.moe_router_bwd_workspace_bytes(8192, 4096, 64)

@@ -29,55 +29,38 @@ def brute_permute(topk_idx, e_begin, e_count):
 
 
 def blockwise_index_generation(indices, n_start, NR, TBS=8):
-    """The paper's two-kernel scheme (Algorithm 1, Stages 2 and 3), written out
-    from its description: token blocks of TBS tokens each own a column of a
-    [local expert, block] count table; one prefix sum over that table in
-    expert-major order gives every (expert, block) its first row; a second
-    sweep hands out rows inside each (expert, block) in token order.  A CSR
-    over tokens (cum_expert_counts) addresses each token's local picks.
-    Readings: the block's token is computed before it is used; the count table
-    is indexed by block id (it has NR*TH entries); n_end is inclusive;
-    '[1:] = PrefixSum' is the inclusive scan stored from position 1.
+    """Second, independent definition of the index structures, after the scheme of Algorithm 1,
+    Stages 2 and 3, as the text describes it (not its listing): tokens are cut into blocks of TBS;
+    a [local expert, block] table counts the picks; ONE running sum over that table, read expert by
+    expert, gives every (expert, block) cell its first grouped row; inside a cell the rows go out in
+    token order.  A CSR over tokens addresses each token's local picks in slot order.
+    Readings taken: the local range is [n_start, n_start + NR) (the paper's n_end is inclusive); the
+    count table has one column per block; the stored prefix sums start with a zero.
+    Built here from whole-array operations (histogram, cumulative sum, rank inside a cell).
     """
     T, K = indices.shape
     assert T % TBS == 0
-    TH = T // TBS
-    n_end = n_start + NR - 1
-    partial = np.zeros(NR * TH, dtype=np.int64)
-    expert_counts = np.zeros(T, dtype=np.int64)
-    for tid in range(TH):
-        for i in range(TBS):
-            t = tid * TBS + i
-            for k in range(K):
-                n = indices[t, k]
-                if n_start <= n <= n_end:
-                    partial[(n - n_start) * TH + tid] += 1
-                    expert_counts[t] += 1
-    partial_cum = np.zeros(NR * TH + 1, dtype=np.int64)
-    partial_cum[1:] = np.cumsum(partial)
-    cum_expert = np.zeros(T + 1, dtype=np.int64)
-    cum_expert[1:] = np.cumsum(expert_counts)
-    cum_token = np.array([partial_cum[n * TH] for n in range(NR + 1)])
-    RT = cum_token[-1]
-    sel = np.zeros(RT, dtype=np.int64)
-    inp = np.zeros(RT, dtype=np.int64)
-    outp = np.zeros(RT, dtype=np.int64)
-    counter = np.zeros((NR, TH), dtype=np.int64)
-    for tid in range(TH):
-        for i in range(TBS):
-            t = tid * TBS + i
-            o = cum_expert[t]
-            for k in range(K):
-                n = indices[t, k]
-                if n_start <= n <= n_end:
-                    ln = n - n_start
-                    row = partial_cum[ln * TH + tid] + counter[ln, tid]
-                    inp[row] = t
-                    outp[o] = row
-                    sel[o] = k
-                    counter[ln, tid] += 1
-                    o += 1
-    return cum_token, cum_expert, inp, outp, sel
+    blocks = T // TBS
+    tok, slot = np.divmod(np.arange(T * K), K)               # flat pair p = t*K + slot
+    local_e = indices.reshape(-1).astype(np.int64) - n_start
+    keep = (local_e >= 0) & (local_e < NR)
+    tok, slot, local_e = tok[keep], slot[keep], local_e[keep]      # local picks, in (token, slot) order
+    cell = local_e * blocks + tok // TBS                           # expert-major cell id
+    table = np.bincount(cell, minlength=NR * blocks)               # Stage 2: counts per (expert, block)
+    first_row = np.concatenate(([0], np.cumsum(table)))            # one prefix sum, expert-major
+    cum_token = first_row[np.arange(NR + 1) * blocks]              # first row of every expert (+ total)
+    # Stage 3: rank of each pick among the earlier picks of its own cell (picks are in token order):
+    # a running count per cell, read off at each pick's own cell.
+    onehot = np.zeros((len(cell), NR * blocks), dtype=np.int64)
+    onehot[np.arange(len(cell)), cell] = 1
+    rank = (np.cumsum(onehot, axis=0) - onehot)[np.arange(len(cell)), cell]
+    start_of_cell = first_row[:-1]
+    row = start_of_cell[cell] + rank
+    inp = np.empty(len(cell), dtype=np.int64)
+    inp[row] = tok                                                  # input_indices
+    per_token = np.bincount(tok, minlength=T)
+    cum_expert = np.concatenate(([0], np.cumsum(per_token)))        # CSR row pointers over tokens
+    return cum_token, cum_expert, inp, row, slot                   # picks are stored in CSR order already
 
 
 def _parse_rows(tokens):
