@@ -118,6 +118,24 @@ int moe_permute(const moe_bf16* x, const int32_t* topk_idx,
                 int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row,
                 moe_bf16* xp, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * moe_permute without a workspace argument, for callers that cannot allocate device memory at all
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the histogram
+ * table lives in a device array inside the library image, moe_permute_static_ws_capacity() bytes
+ * (1 MiB) on every GPU the library is used on, held until the process ends.  Arguments and results are
+ * exactly those of moe_permute.  A shape whose table does not fit
+ * (moe_permute_workspace_bytes(T, k, e_count) > capacity) is refused with MOE_ERR_WORKSPACE and nothing
+ * is enqueued.  The call allocates nothing and frees nothing.  Its first call on a device looks the
+ * array's address up (no allocation, but do it before a graph capture begins).  All calls on one GPU
+ * share that GPU's array: two such calls that overlap in time on one GPU (different streams) race;
+ * calls on one stream, or ordered by events, are fine.
+ */
+size_t moe_permute_static_ws_capacity(void);
+int moe_permute_static_ws(const moe_bf16* x, const int32_t* topk_idx,
+                          int T, int d, int E_total, int k, int e_begin, int e_count,
+                          int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row,
+                          moe_bf16* xp, void* stream);
+
 /* dx[t] = sum over the local slots i of token t of dxp[slot_row[t, i]] (fp32 sum
  * in slot order, rounded once); a token without local slot gets zeros.
  *   dxp [R_cap, d] bf16, slot_row [T, k] int32, dx [T, d] bf16 */

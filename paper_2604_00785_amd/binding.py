@@ -24,6 +24,7 @@ EXPORTS = [
     "moe_grouped_gemm_bwd_folded_workspace_bytes", "moe_grouped_gemm_bwd_folded",
     "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_prof_enable", "moe_prof_count", "moe_prof_read", "moe_prof_mfma_ceiling",
     "moe_router_fwd", "moe_route_bwd", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
+    "moe_permute_static_ws_capacity", "moe_permute_static_ws",
 ]
 
 _ERR = {-1: "MOE_ERR_INVALID (bad pointer, alignment or size)", -2: "MOE_ERR_WORKSPACE (workspace too small)",
@@ -60,9 +61,12 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.moe_grouped_gemm_bwd_folded_workspace_bytes.argtypes = [c_int] * 2
     lib.moe_router_bwd_workspace_bytes.restype = c_sz
     lib.moe_router_bwd_workspace_bytes.argtypes = [c_int] * 3
+    lib.moe_permute_static_ws_capacity.restype = c_sz
+    lib.moe_permute_static_ws_capacity.argtypes = []
     sigs = {
         "moe_route": [vp, c_int, c_int, c_int, c_int, vp, vp, vp],
         "moe_permute": [vp, vp, c_int, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, c_sz, vp],
+        "moe_permute_static_ws": [vp, vp, c_int, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp],
         "moe_permute_bwd": [vp, vp, c_int, c_int, c_int, vp, vp],
         "moe_grouped_gemm_fwd": [vp, vp, vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp],
         "moe_grouped_gemm_bwd": [vp] * 9 + [c_int] * 4 + [vp] * 4 + [vp, c_sz, vp],
@@ -156,6 +160,26 @@ def moe_permute(x, topk_idx, E_total: int, e_begin: int, e_count: int,
     _check(load().moe_permute(_p(x), _p(topk_idx), T, d, E_total, k, e_begin, e_count, _p(expert_offsets),
                               _p(row_token), _p(slot_row), _p(xp), _p(ws), ws.numel() * ws.element_size(),
                               _stream()), "moe_permute")
+
+
+def moe_permute_static_ws_capacity() -> int:
+    return int(load().moe_permute_static_ws_capacity())
+
+
+def moe_permute_static_ws(x, topk_idx, E_total: int, e_begin: int, e_count: int,
+                          expert_offsets, row_token, slot_row, xp) -> None:
+    """``moe_permute`` with the histogram table in the library's own device array (no workspace)."""
+    T, d = x.shape
+    k = topk_idx.shape[1]
+    _want(x, BF16, name="x")
+    _want(topk_idx, torch.int32, (T, k), "topk_idx")
+    _want(expert_offsets, torch.int32, (e_count + 1,), "expert_offsets")
+    _want(row_token, torch.int32, (T * k,), "row_token")
+    _want(slot_row, torch.int32, (T, k), "slot_row")
+    if xp is not None:
+        _want(xp, BF16, (T * k, d), "xp")
+    _check(load().moe_permute_static_ws(_p(x), _p(topk_idx), T, d, E_total, k, e_begin, e_count, _p(expert_offsets),
+                                        _p(row_token), _p(slot_row), _p(xp), _stream()), "moe_permute_static_ws")
 
 
 def moe_permute_bwd(dxp, slot_row, dx) -> None:

@@ -280,3 +280,51 @@ extern "C" int moe_permute_gate(const int32_t* topk_idx, const float* topk_w, in
   return permute_impl(nullptr, topk_idx, topk_w, T, 8, E_total, k, e_begin, e_count, expert_offsets, row_token,
                       slot_row, row_weight, nullptr, ws, ws_bytes, stream);
 }
+
+// ---------------------------------------------------------------------------------------------
+// moe_permute for callers that cannot provide a workspace: the [expert][workgroup] histogram table
+// lives in a device array that is part of the library image (every GPU the library runs on holds
+// its own copy until the process ends).
+namespace {
+constexpr size_t STATIC_WS_BYTES = 1u << 20;       // 262144 table cells (the headline shape needs 16384)
+static __device__ __align__(256) unsigned char scratch[STATIC_WS_BYTES];
+
+constexpr int STATIC_WS_MAX_DEVICES = 64;
+void* g_scratch_addr[STATIC_WS_MAX_DEVICES];        // device address of `scratch` on each device, once looked up
+
+// Device address of this device's copy of `scratch` (the array's name is only a host-side handle).
+// Looked up on the first call on a device, with that device current; concurrent first calls store
+// the same value.
+void* scratch_address() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_WS_MAX_DEVICES) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  void* p = __atomic_load_n(&g_scratch_addr[dev], __ATOMIC_ACQUIRE);
+  if (p != nullptr) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  __atomic_store_n(&g_scratch_addr[dev], p, __ATOMIC_RELEASE);
+  return p;
+}
+}  // namespace
+
+extern "C" size_t moe_permute_static_ws_capacity(void) { return STATIC_WS_BYTES; }
+
+extern "C" int moe_permute_static_ws(const moe_bf16* x, const int32_t* topk_idx, int T, int d, int E_total, int k,
+                                     int e_begin, int e_count, int32_t* expert_offsets, int32_t* row_token,
+                                     int32_t* slot_row, moe_bf16* xp, void* stream) {
+  // sizes first: a shape whose table does not fit is refused before anything else is looked at
+  if (T <= 0 || k <= 0 || e_count <= 0 || e_count > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
+  if (static_cast<long long>(T) * k > 0x7FFFFFFFll / 2) return MOE_ERR_INVALID;
+  if (moe_permute_workspace_bytes(T, k, e_count) > STATIC_WS_BYTES) return MOE_ERR_WORKSPACE;
+  void* ws = scratch_address();
+  if (ws == nullptr) return MOE_ERR_LAUNCH;
+  // every table cell the scan reads is written by the counting kernel of the same call first, so
+  // nothing has to be cleared between calls
+  return permute_impl(x, topk_idx, nullptr, T, d, E_total, k, e_begin, e_count, expert_offsets, row_token, slot_row,
+                      nullptr, xp, ws, STATIC_WS_BYTES, stream);
+}
