@@ -15,7 +15,7 @@ LIB = os.path.join(PKG, "libmoe_hotpath.so")
 
 # Packed-fp32 VALU forms are switched off on purpose for every HIP source.
 HIP_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]

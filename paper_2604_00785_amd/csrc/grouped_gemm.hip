@@ -1,68 +1,76 @@
 // Stage 4 of Algorithm 1 (the three Grouped_mm calls around Silu(gate)*up) and
 // its derivative, as grouped bf16 MFMA GEMMs: one launch covers every expert.
 //
-// One workgroup (8 waves) computes one 256x256 output tile with a 64-deep K step.  The two
-// operand tiles of a step (32 KB each) live in LDS, in a ring of five tile slots (160 KB, all
-// there is): A(t) sits in slot 2t mod 5, B(t) in slot (2t+1) mod 5.  All operand traffic is
-// direct-to-LDS (global_load_lds_dwordx4, eight per wave and step).  Two and a half steps fit,
-// so after the barrier of step t the loads of B(t+2) go out first (they are needed one step
-// later) and those of A(t+3) follow between the MFMAs (needed two steps later): the urgent
-// half of a step's loads is then small enough for the texture path to deliver within the step.
-// The waves form a 2 (M) x 4 (N) grid; each owns a 128x64
-// piece = 4x2 v_mfma_f32_32x32x16_bf16 accumulators (128 fp32 registers per lane).
+// One workgroup of FOUR waves (one per SIMD, 512 registers each) computes one 256x256 output tile
+// with a 64-deep K step; the waves form a 2 x 2 grid and each owns a 128x128 piece = 8x8
+// v_mfma_f32_16x16x32_bf16 accumulators, which live in the 256 accumulation registers.  Against
+// eight waves with 128x64 pieces this reads a third less operand data out of LDS per FLOP, and the
+// 16x16x32 form draws less power per FLOP than the 32x32x16 form (the chip is power-limited on
+// real data), but with one wave per SIMD nothing covers a wave's own stalls, so the main loop is
+// written instruction by instruction:
+//   * MFMAs, LDS fragment reads and direct-to-LDS loads are inline assembly in program order; the
+//     accumulators are pinned to accumulation registers, so the compiler has nothing to move;
+//   * between two MFMAs there is at most one other instruction (a fragment read, or a load);
+//   * no vector-ALU instruction and no branch inside a K step: loads use a scalar base that is
+//     advanced by scalar adds plus a 32-bit lane offset computed once per tile; the eight loads a
+//     wave issues per operand tile share one M0 value (the instruction's immediate offset moves
+//     the LDS address; the lane offset takes the same amount out of the global address again);
+//   * the last two K steps of a tile (which load nothing) are separate copies of the step, and a
+//     tile enters the ring of LDS slots at the phase that makes those two steps phases 0 and 1.
 //
-// What the main loop is built around: while the matrix pipe of a SIMD is saturated, vector-ALU
-// instructions of either wave on that SIMD (address arithmetic for loads and LDS reads) are
-// served very slowly, and everything queued behind them stalls.  So the loop contains no
-// vector-ALU instruction at all: global loads use the scalar-base form (SGPR base that is
-// advanced by scalar adds + a 32-bit per-lane offset computed once per tile), LDS fragment
-// reads use per-lane addresses computed once per tile + immediate offsets (the K loop is
-// unrolled by five, the period of the slot pattern, so that slots are compile-time constants).  MFMA fragments are
-// double-buffered in registers: the LDS reads of the next 16-deep sub-step are issued before
-// the MFMAs of the current one.  One s_barrier per step, placed before the last MFMA group,
-// publishes the tiles that were awaited and frees the two slots that were just read.
+// The two operand tiles of a step (32 KB each) live in a ring of five LDS slots (160 KB, all
+// there is): A(t) in slot 2t mod 5, B(t) in slot (2t+1) mod 5.  The barrier of step t comes
+// after its first 32-deep sub-step: behind it the tiles of step t+1 are complete and the two
+// slots of step t are free; B(t+2) is then loaded into A(t)'s slot, and A(t+3) into B(t)'s slot
+// during the first sub-step of step t+1.  Fragments are double-buffered in registers: the reads
+// of the next sub-step are issued between the MFMAs of the current one.
 //
 // Tile layouts.  An operand that is contiguous along K in memory (activations [rows, K],
 // forward weights [N, K]) is kept as [256 rows][64 k] with 128-byte rows whose eight 16-byte
-// pieces are XOR-swizzled by the row, so that fragment reads (one ds_read_b128 per lane) spread
-// over all banks; the swizzle is applied on the global side of the fill (which piece a lane
-// fetches), since a direct-to-LDS load writes LDS linearly.  An operand that is contiguous
-// along its other dimension (weights in dgrad, both operands in wgrad) is kept as it lies in
-// memory, [64 k][256 n] with 512-byte rows, and read with the transposing LDS load
-// ds_read_b64_tr_b16, two per fragment.
+// pieces are XOR-swizzled by the row (fragment = one ds_read_b128 per lane); the swizzle is
+// applied on the global side of the fill, since a direct-to-LDS load writes LDS linearly.  An
+// operand that is contiguous along its other dimension (weights in dgrad, both operands in
+// wgrad) is kept as it lies in memory, [64 k][256 n] with 512-byte rows, and read with the
+// transposing LDS load ds_read_b64_tr_b16, two per fragment.
 //
-// The MFMAs are issued as (weight fragment) x (activation fragment), so a lane
-// ends up with four consecutive output COLUMNS of one row.  The epilogue rounds
-// to bf16, stages each wave's 128x64 piece in that wave's own 16 KB of LDS and
-// writes it out in full 128-byte row segments; the SwiGLU forward and backward
-// formulas are applied on the way, on the fp32 accumulators.
+// The MFMAs are issued as (weight fragment) x (activation fragment), so a lane ends up with
+// four consecutive output COLUMNS of one row.  The epilogue rounds to bf16, stages each wave's
+// 128x128 piece in that wave's own 32 KB of LDS and writes it out in full 256-byte row segments;
+// the SwiGLU forward and backward formulas are applied on the way, on the fp32 accumulators.
 //
-// Tiles of the row-grouped products are found on the device from
-// expert_offsets: every wave turns the tile number into (expert, first row, column tile)
-// with a wave-wide prefix sum over ceil(rows_e / 256) * column tiles (no LDS is left for a table);
-// inside an expert the row tiles are innermost; experts without rows own no tile; rows past an
-// expert's end are clamped on load and masked on store.
+// Tiles of the row-grouped products are found on the device from expert_offsets: every wave
+// turns the tile number into (expert, first row, column tile) with a wave-wide prefix sum over
+// ceil(rows_e / 256) * column tiles; inside an expert the row tiles are innermost; experts
+// without rows own no tile; rows past an expert's end are clamped on load and masked on store,
+// and 32-row groups without a valid row issue no MFMA.
 #include <type_traits>
+#include <utility>
 #include "common.h"
-
-
 
 namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int GEMM_THREADS = 512;
+constexpr int GEMM_THREADS = 256;
 constexpr int TILE_BYTES = BM * BK * 2;               // one operand tile (32 KB)
 constexpr int NSLOT = 5;                              // ring of operand tile slots
 constexpr int LDS_BYTES = NSLOT * TILE_BYTES;         // 160 KB: everything a workgroup can have
-constexpr int WAVE_STAGE_BYTES = 16384;               // epilogue staging per wave
-constexpr int slot_of_a(int p) { return (2 * p) % NSLOT; }       // p = step mod 5
+constexpr int WAVE_STAGE_BYTES = 32768;               // epilogue staging per wave: 128 rows of 256 bytes
+constexpr int LOAD_BIAS = 4096;                       // see dma16_imm
+constexpr int slot_of_a(int p) { return (2 * p) % NSLOT; }       // p = ring phase of the step
 constexpr int slot_of_b(int p) { return (2 * p + 1) % NSLOT; }
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+template <int N> using IC = std::integral_constant<int, N>;
+template <typename F, int... I> __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(IC<I>{}), ...);
+}
+template <int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
 
 enum GemmMode { GATE_UP = 0, DOWN = 1, DGRAD_H = 2, DGRAD_X = 3, WGRAD = 4, WGRAD_GATHER = 5, DGRAD_H_GATE = 6,
                 WGRAD_GATHER_A = 7 };
@@ -74,11 +82,11 @@ constexpr bool is_wgrad(int mode) { return mode == WGRAD || mode == WGRAD_GATHER
 constexpr bool is_dgrad_h(int mode) { return mode == DGRAD_H || mode == DGRAD_H_GATE; }
 
 struct GemmArgs {
-  // row-grouped products (modes 0-3)
+  // row-grouped products (modes 0-3, 6)
   const uint16_t* A0;   // [R_cap, K]   activations (phase 0)
   const uint16_t* A1;   // second K phase of DGRAD_X (du), else unused
   const uint16_t* B0;   // weights, stacked over experts
-  const uint16_t* B1;   // Wu (GATE_UP: second half of the N tile; DGRAD_X: second K phase)
+  const uint16_t* B1;   // Wu (GATE_UP: the up half of the column tile; DGRAD_X: second K phase)
   const uint16_t* G;    // DGRAD_H epilogue inputs
   const uint16_t* U;
   uint16_t* O0;         // g | yp | dg | dxp | dW
@@ -90,10 +98,10 @@ struct GemmArgs {
   const float* row_weight;    // GATE_UP: not null = h is scaled by the row's gate weight; DGRAD_H_GATE: required
   float* dgate_part;          // DGRAD_H_GATE: [R_cap][N / 64] partial dot products, one per row and 64-column strip
   int E;
-  int K;                // reduction length of one phase (modes 0-3)
+  int K;                // reduction length of one phase (row-grouped products)
   int N;                // output columns (per half for GATE_UP)
   int n_tiles;          // column tiles
-  int m_tiles_cap;      // upper bound on row tiles (modes 0-3); row tiles of one dW (WGRAD)
+  int m_tiles_cap;      // upper bound on row tiles (row-grouped products); row tiles of one dW (WGRAD)
   // WGRAD: out[e][M][N] = sum over the expert's rows of A[r][M] * B[r][N]
   int M;
 };
@@ -109,9 +117,9 @@ __device__ __forceinline__ int kc_off(int row, int chunk) {
 // four k rows that 16 lanes of a transposing read touch over four different 64-byte bank groups.
 __device__ __forceinline__ int kn_piece(int krow, int piece) { return piece ^ ((krow & 3) << 2); }
 
-// LDS fragment reads are written as inline assembly with immediate offsets and awaited by hand
-// (lds_wait): the fragments are read one sub-step ahead, across the loop back edge, and the
-// compiler's own wait insertion would drain the LDS queue completely at the first use.
+// Everything the main loop issues is inline assembly in program order (asm volatile statements keep
+// their order), with immediate offsets, and is awaited by hand: fragments are read one sub-step
+// ahead and loads several steps ahead, which the compiler's own wait insertion cannot express.
 template <int OFF> __device__ __forceinline__ bf16x8_t lds_read_b128(uint32_t addr) {
   bf16x8_t v;
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
@@ -122,44 +130,41 @@ template <int OFF> __device__ __forceinline__ s16x4 lds_read_tr_b64(uint32_t add
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
   return v;
 }
-// Direct-to-LDS loads (16 bytes per lane, lane l lands at lds_addr + 16 l) are written as inline
-// assembly too, so that the (scalar base) + (32-bit lane offset) form is certain: with 64-bit lane
-// addresses every load needs vector-ALU work.  M0 carries the LDS address; nothing else in this
-// file uses M0.
-template <int OFF> __device__ __forceinline__ void dma16(uint32_t lds_base, uint32_t voff, const char* sbase) {
-  asm volatile("s_add_i32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_base), "v"(voff), "s"(sbase), "n"(OFF) : "memory", "scc");
+// Direct-to-LDS loads, 16 bytes per lane: lane l lands at M0 + OFF + 16 l, and reads global address
+// (scalar base) + (32-bit lane offset) + OFF.  The immediate moves both addresses: a wave's eight loads
+// of a tile use OFF = (i - 4) * 1024 with one M0 value, their lane offsets carry -OFF, and LOAD_BIAS
+// (subtracted from the scalar base, added to every lane offset) keeps the lane offsets non-negative.
+// Nothing else in this file uses M0.
+template <int OFF> __device__ __forceinline__ void set_m0(uint32_t lds_base) {
+  asm volatile("s_add_i32 m0, %0, %1" :: "s"(lds_base), "n"(OFF) : "memory", "scc");
 }
-template <int OFF> __device__ __forceinline__ void dma16_lane(uint32_t lds_base, const char* p) {
-  asm volatile("s_add_i32 m0, %0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-               :: "s"(lds_base), "v"(p), "n"(OFF) : "memory", "scc");
+__device__ __forceinline__ void set_m0_rt(uint32_t lds_addr) { asm volatile("s_mov_b32 m0, %0" :: "s"(lds_addr) : "memory"); }
+template <int OFF> __device__ __forceinline__ void dma16_imm(uint32_t voff, const char* sbase) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" :: "v"(voff), "s"(sbase), "n"(OFF) : "memory");
 }
-// A 4-byte load as (scalar base) + (32-bit lane offset) + immediate, awaited by hand like the loads
-// above (the compiler's own wait would count only the loads it knows of and so drain the whole queue).
+// the same with a 64-bit address per lane (used once per tile at most, for rows past an expert's end)
+template <int OFF> __device__ __forceinline__ void dma16_lane_imm(const char* p) {
+  asm volatile("global_load_lds_dwordx4 %0, off offset:%1" :: "v"(p), "n"(OFF) : "memory");
+}
+// A 4-byte load as (scalar base) + (32-bit lane offset) + immediate, awaited by hand like the loads above.
 template <int OFF> __device__ __forceinline__ int load_i32(uint32_t voff, const int32_t* sbase) {
   int v;
   asm volatile("global_load_dword %0, %1, %2 offset:%3" : "=v"(v) : "v"(voff), "s"(sbase), "n"(OFF) : "memory");
   return v;
 }
 template <int N> __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
+template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ void wg_barrier() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+}
 
-// Per-lane address of a fragment (32 tile columns starting at col0) of a [64 k][256 n] tile at
-// LDS address `tile`, K sub-step 0, first half.  Within 16 lanes, lane i supplies the address of
-// four consecutive n of k row i/4, n block i%4, and lane l receives k rows 0..3 of column l; two
-// such loads (the second 4 k rows = 2048 bytes further) give the eight consecutive k of a column,
-// and sub-step ks lies ks * 8192 bytes further.
-__device__ __forceinline__ uint32_t kn_frag_addr(uint32_t tile, int col0, int lane) {
-  const int i = lane & 15, kg = lane >> 5;
-  const int n = col0 + ((lane >> 4) & 1) * 16 + 4 * (i & 3);
-  const int krow = kg * 8 + (i >> 2);
-  return tile + krow * 512 + kn_piece(krow, n >> 3) * 16 + (n & 7) * 2;
-}
-template <int OFF> __device__ __forceinline__ bf16x8_t lds_read_kn(uint32_t addr) {
-  union { s16x4 h[2]; bf16x8_t v; } u;
-  u.h[0] = lds_read_tr_b64<OFF>(addr);
-  u.h[1] = lds_read_tr_b64<OFF + 2048>(addr);
-  return u.v;
-}
+// A fragment of a [64 k][256 n] tile: two transposing reads (k rows +0..3 and +4..7 of the lane's column).
+union KnFrag {
+  s16x4 h[2];
+  bf16x8_t v;
+};
 
 // sigmoid through the hardware exp2 and reciprocal (each about 1 ulp): far inside bf16 rounding.
 // exp2 overflows to +inf for very negative g and the reciprocal then returns 0, as it should.
@@ -167,13 +172,6 @@ __device__ __forceinline__ float sigmoid_f(float g) {
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
 }
 __device__ __forceinline__ float silu_f(float g) { return g * sigmoid_f(g); }
-
-template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-__device__ __forceinline__ void wg_barrier() {
-  __builtin_amdgcn_sched_barrier(0);
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_sched_barrier(0);
-}
 
 // Row tiles of the grouped products: expert e owns ceil(rows_e / 256) consecutive tile numbers.
 // Both functions are evaluated by a whole wave (64 experts per pass) and return wave-uniform values.
@@ -232,12 +230,21 @@ __device__ __forceinline__ void find_tile(const int32_t* offsets, int E, int lo0
 
 // The kernel arguments again, through a pointer the compiler cannot see through: what is read from
 // it is loaded afresh (scalar loads from the argument segment) instead of being kept in scalar
-// registers across the main loop, which needs them for itself.
+// registers across the main loop.
 typedef const __attribute__((address_space(4))) GemmArgs* ArgPtr;
 template <int ARG> __device__ __forceinline__ ArgPtr reload_args() {   // ARG: which of the kernel's GemmArgs
   ArgPtr p = (ArgPtr)__builtin_amdgcn_kernarg_segment_ptr() + ARG;
   asm volatile("" : "+s"(p));
   return p;
+}
+
+// A wave-uniform pointer as two scalar registers.  readfirstlane returns a signed int: it is widened
+// through uint32_t, or a set bit 31 of the low half would smear into the high half.
+__device__ __forceinline__ const char* scalarize(const char* p) {
+  const uint64_t u = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u)));
+  const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32)));
+  return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | static_cast<uint64_t>(lo));
 }
 
 // One product's tile list, walked by this workgroup from list position first_tile in steps of
@@ -248,7 +255,12 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid0 = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  constexpr bool A_KN = is_wgrad(MODE);                                           // stored [k][m]
+  constexpr bool B_KN = (is_wgrad(MODE) || is_dgrad_h(MODE) || MODE == DGRAD_X);  // stored [k][n]
+  constexpr bool GATHER_B = (MODE == WGRAD_GATHER);
+  constexpr bool GATHER_A = (MODE == WGRAD_GATHER_A);
 
   // ---------------- tile list ---------------------------------------------------
   int total;
@@ -263,6 +275,10 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     total = count_row_tiles(a.offsets, a.E, tid0 & 63) * a.n_tiles;
     if (a.E <= 64 && (tid0 & 63) < a.E) { lo0 = a.offsets[tid0 & 63]; hi0 = a.offsets[(tid0 & 63) + 1]; }
   }
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<size_t>(LDS_PTR(lds)));
+  // M0 base of this wave's loads: the middle of its 8 KB share of tile slot 0 (immediates reach -4096 .. +3072)
+  const uint32_t lds_fill = __builtin_amdgcn_readfirstlane(lds0 + wave * 8192 + 4096);
+
   int tile = first_tile;
   for (; tile < total; tile += gridDim.x) {
   // the thread id is laundered per tile so that lane-dependent address pieces are recomputed for
@@ -291,41 +307,33 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   m0 = __builtin_amdgcn_readfirstlane(m0);
   m_end = __builtin_amdgcn_readfirstlane(m_end);
   const int n0 = nt * (MODE == GATE_UP ? BN / 2 : BN);
-  // 32-row fragments of this wave that hold at least one valid row (the others are skipped)
-  int nfa = (m_end - m0 - wm * 128 + 31) >> 5;
-  nfa = nfa < 0 ? 0 : (nfa > 4 ? 4 : nfa);
-  nfa = __builtin_amdgcn_readfirstlane(nfa);
-
-  // The 32 tile rows this wave loads of every activation tile (rows 32 * wave ..) are one fragment of
-  // some wave; if none of them is a valid row nobody reads them, and the wave skips those loads
-  // (a row tile with few rows is bound by its loads, not by its MFMAs).
-  bool a_live = true;
-  if constexpr (!is_wgrad(MODE)) a_live = wave * 32 < m_end - m0;
-
-  constexpr bool A_KN = is_wgrad(MODE);                                       // stored [k][m]
-  constexpr bool B_KN = (is_wgrad(MODE) || is_dgrad_h(MODE) || MODE == DGRAD_X);  // stored [k][n]
+  // 32-row groups of this wave's 128 rows that hold at least one valid row (the others issue no MFMA)
+  int nv = 4;
+  if constexpr (!is_wgrad(MODE)) {
+    nv = (m_end - m0 - wm * 128 + 31) >> 5;
+    nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
+    nv = __builtin_amdgcn_readfirstlane(nv);
+  }
 
   // ---------------- operand sources -------------------------------------------
-  // A tile <-> output rows m0 + r ; B tile <-> output columns.  Per step and operand a wave issues
-  // four direct-to-LDS loads of 1 KB each, as (scalar base) + (32-bit lane offset):
-  //  K-contiguous source ([row][k]): load i of wave w fills LDS rows (4w+i)*8 .. +8 of the tile;
+  // Per K step and operand tile a wave issues eight direct-to-LDS loads of 1 KB each:
+  //  K-contiguous source ([row][k]): load i of wave w fills tile rows 64 w + 8 i .. + 8;
   //    lane l -> row + l/8, physical piece l%8, i.e. the logical piece that kc_off maps there.
   //    The base advances by 64 elements per step.
-  //  n-contiguous source ([k][n]): load i of wave w fills k rows (4w+i)*2, +1 of the tile;
+  //  n-contiguous source ([k][n]): load i of wave w fills k rows 2 (8 w + i), + 1;
   //    lane l -> k row + l/32, physical piece l%32 = logical piece kn_piece(k row, l%32).
   //    The base advances by 64 rows per step.
-  uint32_t voa[4], vob[4];              // lane offsets in bytes
-  const char* abase;                    // step 0 of phase 0
+  // Lane offsets carry LOAD_BIAS - (i - 4) * 1024 (see dma16_imm); the scalar bases lie LOAD_BIAS low.
+  uint32_t voa[8], vob[8];              // lane offsets in bytes
+  const char* abase;                    // step 0 of phase 0, without the bias
   const char* bbase;
   ptrdiff_t a_phase = 0, b_phase = 0;   // byte offset of the second K phase (DGRAD_X)
   size_t a_step, b_step;                // bytes per step
   int k_lo = 0, k_hi = 0;               // WGRAD: the expert's row range is the reduction
-  constexpr bool GATHER_B = (MODE == WGRAD_GATHER);
-  constexpr bool GATHER_A = (MODE == WGRAD_GATHER_A);
   const int32_t* row_tok = nullptr;     // GATHER_A/B: token of the expert's first reduction row onwards
-  uint32_t vcb[4] = {0, 0, 0, 0};       // GATHER_A/B: byte offset of the lane's columns within a token row
-  int tokn[4] = {0, 0, 0, 0};           // GATHER_A/B: tokens of the lane's four reduction rows of a coming step
-  int tokn1[4] = {0, 0, 0, 0};          // the same for step 1, while a tile's first loads are set up
+  uint32_t vcb[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // GATHER_A/B: lane offset of a load without its token row
+  int tokn[8] = {0, 0, 0, 0, 0, 0, 0, 0};       // GATHER_A/B: tokens of the lane's eight reduction rows of a coming step
+  int tokn1[8] = {0, 0, 0, 0, 0, 0, 0, 0};      // the same for step 1, while a tile's first loads are set up
   int nk, nk_phase;                     // steps in total / in the first K phase
 
   if constexpr (is_wgrad(MODE)) {
@@ -351,15 +359,16 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
       b_step = static_cast<size_t>(BK) * a.N * 2;
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int krow = (wave * 4 + i) * 2 + (lane >> 5);
+    for (int i = 0; i < 8; ++i) {
+      const int krow = (wave * 8 + i) * 2 + (lane >> 5);
       const int piece = kn_piece(krow, lane & 31);
       int ca = piece * 8;  if (m0 + ca > a.M - 8) ca = a.M - 8 - m0;
       int cb = piece * 8;  if (n0 + cb > a.N - 8) cb = a.N - 8 - n0;
-      voa[i] = static_cast<uint32_t>((krow * a.M + ca) * 2);
-      vob[i] = static_cast<uint32_t>((krow * a.N + cb) * 2);
-      if constexpr (GATHER_B) vcb[i] = static_cast<uint32_t>(cb * 2);
-      if constexpr (GATHER_A) vcb[i] = static_cast<uint32_t>(ca * 2);
+      const uint32_t fix = static_cast<uint32_t>(LOAD_BIAS - (i - 4) * 1024);
+      voa[i] = static_cast<uint32_t>((krow * a.M + ca) * 2) + fix;
+      vob[i] = static_cast<uint32_t>((krow * a.N + cb) * 2) + fix;
+      if constexpr (GATHER_B) vcb[i] = static_cast<uint32_t>(cb * 2) + fix;
+      if constexpr (GATHER_A) vcb[i] = static_cast<uint32_t>(ca * 2) + fix;
     }
   } else {
     nk = a.K / BK;
@@ -371,112 +380,93 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     if constexpr (MODE == DGRAD_H_GATE) gathered = true;
     if (gathered) abase = reinterpret_cast<const char*>(a.A0);   // lane offsets carry the token row
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = (wave * 4 + i) * 8 + (lane >> 3);
+    for (int i = 0; i < 8; ++i) {
+      const int row = (wave * 8 + i) * 8 + (lane >> 3);
       const int chunk = (kc_off(row, lane & 7) >> 4) & 7;   // the swizzle is its own inverse
       int r = row;
       if (m0 + r > m_end - 1) r = m_end - 1 - m0;
-      if (gathered) voa[i] = (static_cast<uint32_t>(a.row_token[m0 + r]) * a.K + chunk * 8) * 2u;
-      else voa[i] = static_cast<uint32_t>((r * a.K + chunk * 8) * 2);
+      const uint32_t fix = static_cast<uint32_t>(LOAD_BIAS - (i - 4) * 1024);
+      if (gathered) voa[i] = (static_cast<uint32_t>(a.row_token[m0 + r]) * a.K + chunk * 8) * 2u + fix;
+      else voa[i] = static_cast<uint32_t>((r * a.K + chunk * 8) * 2) + fix;
     }
     if constexpr (MODE == DGRAD_X) { a_phase = (a.A1 - a.A0) * 2; nk *= 2; }
     const size_t wsz = static_cast<size_t>(a.N) * a.K;
     if constexpr (!B_KN) {
-      // GATE_UP: LDS rows 0..127 hold Wg rows n0.., rows 128..255 hold Wu rows n0.. (waves 4-7 fill those)
+      // GATE_UP: a wave's 128 tile rows are 64 rows of Wg and the same 64 rows of Wu: tile rows
+      // [0,64) Wg n0.., [64,128) Wu n0.., [128,192) Wg n0+64.., [192,256) Wu n0+64.. (wave w fills its own 64)
       const uint16_t* w = a.B0;
-      int rsub = 0;
+      int first_col = wave * 64;
       if constexpr (MODE == GATE_UP) {
-        if (wave >= 4) { w = a.B1; rsub = BN / 2; }
+        if (wave & 1) w = a.B1;
+        first_col = (wave >> 1) * 64;
       }
       bbase = reinterpret_cast<const char*>(w + static_cast<size_t>(e) * wsz + static_cast<size_t>(n0) * a.K);
       b_step = BK * 2;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = (wave * 4 + i) * 8 + (lane >> 3);   // LDS row of the B tile
+      for (int i = 0; i < 8; ++i) {
+        const int row = (wave * 8 + i) * 8 + (lane >> 3);   // LDS row of the B tile
         const int chunk = (kc_off(row, lane & 7) >> 4) & 7;
-        int col = row - rsub;
+        int col = first_col + i * 8 + (lane >> 3);
         if (n0 + col > a.N - 1) col = a.N - 1 - n0;
-        vob[i] = static_cast<uint32_t>((col * a.K + chunk * 8) * 2);
+        vob[i] = static_cast<uint32_t>((col * a.K + chunk * 8) * 2) + static_cast<uint32_t>(LOAD_BIAS - (i - 4) * 1024);
       }
     } else {  // DGRAD_H / DGRAD_X: weights stored [K][N]
       bbase = reinterpret_cast<const char*>(a.B0 + static_cast<size_t>(e) * wsz + n0);
       b_step = static_cast<size_t>(BK) * a.N * 2;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int krow = (wave * 4 + i) * 2 + (lane >> 5);
+      for (int i = 0; i < 8; ++i) {
+        const int krow = (wave * 8 + i) * 2 + (lane >> 5);
         int cb = kn_piece(krow, lane & 31) * 8;
         if (n0 + cb > a.N - 8) cb = a.N - 8 - n0;
-        vob[i] = static_cast<uint32_t>((krow * a.N + cb) * 2);
+        vob[i] = static_cast<uint32_t>((krow * a.N + cb) * 2) + static_cast<uint32_t>(LOAD_BIAS - (i - 4) * 1024);
       }
       if constexpr (MODE == DGRAD_X) b_phase = (a.B1 - a.B0) * 2;
     }
   }
 
   // Both bases live in scalar registers and are advanced by scalar adds: steps are loaded in order.
-  auto scalarize = [](const char* p) __attribute__((always_inline)) {
-    const uint64_t u = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32));
-    return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
-  };
-  const uint32_t lds_fill = __builtin_amdgcn_readfirstlane(
-      static_cast<uint32_t>(reinterpret_cast<size_t>(LDS_PTR(lds))) + wave * 4096);   // this wave's share of a tile
-  const char* sa_next = scalarize(abase);
-  const char* sb_next = scalarize(bbase);
+  const char* sa_next = scalarize(abase - LOAD_BIAS);
+  const char* sb_next = scalarize(bbase - LOAD_BIAS);
   const char* sa_phase1 = nullptr;
   const char* sb_phase1 = nullptr;
-  if constexpr (MODE == DGRAD_X) { sa_phase1 = scalarize(abase + a_phase); sb_phase1 = scalarize(bbase + b_phase); }
+  if constexpr (MODE == DGRAD_X) { sa_phase1 = scalarize(abase + a_phase - LOAD_BIAS); sb_phase1 = scalarize(bbase + b_phase - LOAD_BIAS); }
 
-  // Loads come per operand tile ("unit"), in order of the steps: part i of a unit is this wave's
-  // i-th load of it, unit_end advances the operand's running base.
-  using J0 = std::integral_constant<int, 0>;
-  using J1 = std::integral_constant<int, 1>;
-  using J2 = std::integral_constant<int, 2>;
-  using J3 = std::integral_constant<int, 3>;
-  auto a_part = [&](int kt, auto slot_tag, auto i_tag) __attribute__((always_inline)) {
-    constexpr int SLOT = decltype(slot_tag)::value, i = decltype(i_tag)::value;
-    constexpr int OFF = SLOT * TILE_BYTES + i * 1024;
-    if constexpr (GATHER_A) {
-      dma16<OFF>(lds_fill, voa[i], sa_next);   // rows past the expert's end were clamped when their tokens were fetched
-    } else if constexpr (is_wgrad(MODE)) {
+  // Load i of the A / B tile of step kt (M0 must point at the tile's slot already).
+  auto a_part = [&](int kt, auto i_tag) __attribute__((always_inline)) {
+    constexpr int i = decltype(i_tag)::value;
+    constexpr int OFF = (i - 4) * 1024;
+    if constexpr (is_wgrad(MODE) && !GATHER_A) {
       if (k_lo + (kt + 1) * BK > k_hi) {
         // last, partial step of the expert: reduction rows at or past its end read zeros
         // (per-lane 64-bit addresses; once per tile)
-        const int krow = k_lo + kt * BK + (wave * 4 + i) * 2 + (lane >> 5);
-        dma16_lane<OFF>(lds_fill, krow < k_hi ? sa_next + voa[i]
-                                   : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16);
-      } else {
-        dma16<OFF>(lds_fill, voa[i], sa_next);
+        const int krow = k_lo + kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
+        dma16_lane_imm<OFF>(krow < k_hi ? sa_next + voa[i]
+                                        : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16 - OFF);
+        return;
       }
-    } else {
-      dma16<OFF>(lds_fill, voa[i], sa_next);
     }
+    dma16_imm<OFF>(voa[i], sa_next);   // GATHER_A: rows past the expert's end were clamped when their tokens were fetched
   };
-  auto b_part = [&](int kt, auto slot_tag, auto i_tag) __attribute__((always_inline)) {
-    constexpr int SLOT = decltype(slot_tag)::value, i = decltype(i_tag)::value;
-    constexpr int OFF = SLOT * TILE_BYTES + i * 1024;
-    if constexpr (GATHER_B) {
-      dma16<OFF>(lds_fill, vob[i], sb_next);   // rows past the expert's end were clamped when their tokens were fetched
-    } else if constexpr (GATHER_A) {
+  auto b_part = [&](int kt, auto i_tag) __attribute__((always_inline)) {
+    constexpr int i = decltype(i_tag)::value;
+    constexpr int OFF = (i - 4) * 1024;
+    if constexpr (GATHER_A) {
       if (k_lo + (kt + 1) * BK > k_hi) {
         // the gathered operand repeats the expert's last row past its end: this one reads zeros there
-        const int krow = k_lo + kt * BK + (wave * 4 + i) * 2 + (lane >> 5);
-        dma16_lane<OFF>(lds_fill, krow < k_hi ? sb_next + vob[i]
-                                   : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16);
-      } else {
-        dma16<OFF>(lds_fill, vob[i], sb_next);
+        const int krow = k_lo + kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
+        dma16_lane_imm<OFF>(krow < k_hi ? sb_next + vob[i]
+                                        : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16 - OFF);
+        return;
       }
     } else if constexpr (MODE == WGRAD) {
       if (k_lo + (kt + 1) * BK > k_hi) {
         // ... and the other operand reads its last valid row there, so that zero times it is zero
-        const int krow = k_lo + kt * BK + (wave * 4 + i) * 2 + (lane >> 5);
-        dma16_lane<OFF>(lds_fill, sb_next + vob[i] - (krow < k_hi ? 0 : static_cast<size_t>(krow - (k_hi - 1)) * a.N * 2));
-      } else {
-        dma16<OFF>(lds_fill, vob[i], sb_next);
+        const int krow = k_lo + kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
+        dma16_lane_imm<OFF>(sb_next + vob[i] - (krow < k_hi ? 0 : static_cast<size_t>(krow - (k_hi - 1)) * a.N * 2));
+        return;
       }
-    } else {
-      dma16<OFF>(lds_fill, vob[i], sb_next);
     }
+    dma16_imm<OFF>(vob[i], sb_next);   // GATHER_B: rows past the expert's end were clamped when their tokens were fetched
   };
   auto a_end = [&](int kt) __attribute__((always_inline)) {
     sa_next += a_step;
@@ -490,18 +480,18 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
       if (kt + 1 == nk_phase) sb_next = sb_phase1;
     }
   };
-  // GATHER_B: the tokens of the lane's four reduction rows of step kt, loaded without any vector-ALU
-  // work except in an expert's last, partial step (rows past its end repeat its last row: the other
-  // operand is zero there), and their turn into lane offsets of the B loads.  The loads are asynchronous:
-  // apply_tok may only run after a wait that covers them.
-  const uint32_t tok_voff = static_cast<uint32_t>(((wave * 4) * 2 + (lane >> 5)) * 4);   // row of load 0; load i: + 2 i rows
-  auto fetch_tok = [&](int kt, int (&tk)[4]) __attribute__((always_inline)) {
+  // GATHER_A/B: the tokens of the lane's eight reduction rows of step kt (rows 2 (8 w + i) + lane / 32), loaded
+  // without any vector-ALU work except in an expert's last, partial step (rows past its end repeat its last
+  // row: the other operand is zero there), and their turn into lane offsets of the gathered operand's loads.
+  // The loads are asynchronous: apply_tok may only run after a wait that covers them.
+  const uint32_t tok_voff = static_cast<uint32_t>(((wave * 8) * 2 + (lane >> 5)) * 4);   // row of load 0; load i: + 2 i rows
+  auto fetch_tok = [&](int kt, int (&tk)[8]) __attribute__((always_inline)) {
     if constexpr (GATHER_B || GATHER_A) {
       if (k_lo + (kt + 1) * BK > k_hi) {
         const int last = k_hi - k_lo - 1;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          int r = kt * BK + (wave * 4 + i) * 2 + (lane >> 5);
+        for (int i = 0; i < 8; ++i) {
+          int r = kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
           if (r > last) r = last;
           tk[i] = load_i32<0>(static_cast<uint32_t>(r) * 4u, row_tok);
         }
@@ -511,454 +501,448 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
         tk[1] = load_i32<8>(tok_voff, base);
         tk[2] = load_i32<16>(tok_voff, base);
         tk[3] = load_i32<24>(tok_voff, base);
+        tk[4] = load_i32<32>(tok_voff, base);
+        tk[5] = load_i32<40>(tok_voff, base);
+        tk[6] = load_i32<48>(tok_voff, base);
+        tk[7] = load_i32<56>(tok_voff, base);
       }
     }
   };
-  auto apply_tok = [&](int (&tk)[4]) __attribute__((always_inline)) {
+  auto apply_tok = [&](int (&tk)[8]) __attribute__((always_inline)) {
     if constexpr (GATHER_B || GATHER_A) {
       const uint32_t row_bytes = static_cast<uint32_t>(GATHER_B ? a.N : a.M) * 2u;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < 8; ++i) {
         asm volatile("" : "+v"(tk[i]));   // not before the wait that precedes this call
         const uint32_t off = static_cast<uint32_t>(tk[i]) * row_bytes + vcb[i];
         if constexpr (GATHER_B) vob[i] = off; else voa[i] = off;
       }
     }
   };
-  auto a_unit = [&](int kt, auto slot_tag) __attribute__((always_inline)) {
-    a_part(kt, slot_tag, J0{}); a_part(kt, slot_tag, J1{}); a_part(kt, slot_tag, J2{}); a_part(kt, slot_tag, J3{});
-    a_end(kt);
-  };
-  auto b_unit = [&](int kt, auto slot_tag) __attribute__((always_inline)) {
-    b_part(kt, slot_tag, J0{}); b_part(kt, slot_tag, J1{}); b_part(kt, slot_tag, J2{}); b_part(kt, slot_tag, J3{});
-    b_end(kt);
-  };
 
-  // ---------------- main loop ----------------------------------------------------
-  f32x16_t acc[4][2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  const int lrow = lane & 31, lgrp = lane >> 5;
-  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<size_t>(LDS_PTR(lds)));
-  // Per-lane fragment addresses.  Slot, fragment and sub-step are immediate offsets of the LDS
-  // reads, which reach 64 KB: one set of addresses serves slots 0-1, one slots 2-3, one slot 4.
-  //  [row][k] tile: an address per sub-step, for the wave's first fragment.  Fragment i lies
-  //    32 i rows = 4096 i bytes further, and an odd i flips bit 2 of the row swizzle, which is the
-  //    same as taking sub-step ks ^ 2.
-  //  [k][n] tile: an address per fragment (its swizzle depends on the column block); sub-step and
-  //    half are immediates.
-  const int b_row0 = (MODE == GATE_UP) ? wn * 32 : wn * 64;
-  uint32_t fa_base[3][4], fb_base[3][B_KN ? 2 : 4];
+  // ---------------- fragment addresses ------------------------------------------
+  // Slot, block and sub-step are immediate offsets of the LDS reads, which reach 64 KB: one set of
+  // per-lane addresses serves slots 0-1, one slots 2-3, one slot 4; four addresses per set and operand.
+  //  [row][k] tile: block b = rows 16 b + (lane & 15), sub-step s (32 k) = logical piece 4 s + lane / 16.
+  //    The row swizzle is (lane & 7) ^ (lane bit 3) ^ (2 b & 6), so the address of (b, s) is
+  //    base[((2 b & 6) ^ 4 s) / 2] + 2048 b.
+  //  [k][n] tile: block b = columns 16 b + (lane & 15); within 16 lanes, lane i supplies the address of four
+  //    consecutive n of k row i / 4, n group i % 4, and lane l receives k rows 0..3 of column l; lanes
+  //    16 g .. 16 g + 15 take k rows 8 g .. of the sub-step.  The k-row swizzle XORs bits 1-2 of the block
+  //    number, so the address of block b is base[b / 2] + 32 (b & 1); the second half of a fragment lies
+  //    4 k rows = 2048 bytes further, sub-step 1 32 k rows = 16384 bytes further.
+  uint32_t fa_base[3][4], fb_base[3][4];
 #pragma unroll
   for (int st = 0; st < 3; ++st) {
     const uint32_t org = lds0 + st * 2 * TILE_BYTES;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if constexpr (A_KN) fa_base[st][q] = kn_frag_addr(org, wm * 128 + q * 32, lane);
-      else fa_base[st][q] = org + kc_off(wm * 128 + lrow, q * 2 + lgrp);
-    }
-    if constexpr (B_KN) {
-      fb_base[st][0] = kn_frag_addr(org, b_row0, lane);
-      fb_base[st][1] = kn_frag_addr(org, b_row0 + 32, lane);
-    } else {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) fb_base[st][q] = org + kc_off(b_row0 + lrow, q * 2 + lgrp);
+    for (int x = 0; x < 4; ++x) {
+      const int i16 = lane & 15;
+      // [row][k]
+      const int pc = ((lane >> 4) ^ (lane & 7) ^ ((lane >> 3) & 1) ^ (2 * x)) & 7;
+      const uint32_t kc_a = org + (wm * 128 + i16) * 128 + pc * 16;
+      const uint32_t kc_b = org + (wn * 128 + i16) * 128 + pc * 16;
+      // [k][n]
+      const int krow = (lane >> 4) * 8 + (i16 >> 2);
+      const int sw = krow & 3;
+      const uint32_t kn_lane = krow * 512 + ((x ^ sw) << 6) + ((i16 >> 1) & 1) * 16 + (i16 & 1) * 8;
+      const uint32_t kn_a = org + wm * 256 + kn_lane;
+      const uint32_t kn_b = org + wn * 256 + kn_lane;
+      fa_base[st][x] = A_KN ? kn_a : kc_a;
+      fb_base[st][x] = B_KN ? kn_b : kc_b;
     }
   }
 
-  bf16x8_t fa[2][4], fb[2][2];   // two fragment sets: one feeds the MFMAs while the other is being read
-  // LDS read instructions per fragment set when NFA activation fragments are live (none at all for NFA = 0)
-  constexpr auto nreads = [](int nfa) { return nfa == 0 ? 0 : (A_KN ? 2 : 1) * nfa + (B_KN ? 4 : 2); };
-  // Reads sub-step KS of the tiles in slots SA (A) and SB (B) into fragment set SET.  Activation
-  // fragments without a valid row are not read: nothing would keep their registers reserved until
-  // the data lands.
-  auto read_frags = [&](auto sa_tag, auto sb_tag, auto ks_tag, auto set_tag, auto full_tag) __attribute__((always_inline)) {
-    constexpr int NFA = decltype(full_tag)::value;
-    if constexpr (NFA == 0) return;
-    constexpr int SA = decltype(sa_tag)::value, SB = decltype(sb_tag)::value;
-    constexpr int KS = decltype(ks_tag)::value, SET = decltype(set_tag)::value;
-    constexpr int OA = (SA & 1) * TILE_BYTES, OB = (SB & 1) * TILE_BYTES;
-    if constexpr (B_KN) {
-      fb[SET][0] = lds_read_kn<OB + KS * 8192>(fb_base[SB >> 1][0]);
-      fb[SET][1] = lds_read_kn<OB + KS * 8192>(fb_base[SB >> 1][1]);
-    } else if constexpr (MODE == GATE_UP) {   // second fragment: the up half, 128 tile rows further
-      fb[SET][0] = lds_read_b128<OB>(fb_base[SB >> 1][KS]);
-      fb[SET][1] = lds_read_b128<OB + 128 * 128>(fb_base[SB >> 1][KS]);
-    } else {
-      fb[SET][0] = lds_read_b128<OB>(fb_base[SB >> 1][KS]);
-      fb[SET][1] = lds_read_b128<OB + 4096>(fb_base[SB >> 1][KS ^ 2]);
-    }
-    if constexpr (A_KN) {
-      if constexpr (NFA > 0) fa[SET][0] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][0]);
-      if constexpr (NFA > 1) fa[SET][1] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][1]);
-      if constexpr (NFA > 2) fa[SET][2] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][2]);
-      if constexpr (NFA > 3) fa[SET][3] = lds_read_kn<OA + KS * 8192>(fa_base[SA >> 1][3]);
-    } else {
-      if constexpr (NFA > 0) fa[SET][0] = lds_read_b128<OA>(fa_base[SA >> 1][KS]);
-      if constexpr (NFA > 1) fa[SET][1] = lds_read_b128<OA + 4096>(fa_base[SA >> 1][KS ^ 2]);
-      if constexpr (NFA > 2) fa[SET][2] = lds_read_b128<OA + 8192>(fa_base[SA >> 1][KS]);
-      if constexpr (NFA > 3) fa[SET][3] = lds_read_b128<OA + 12288>(fa_base[SA >> 1][KS ^ 2]);
-    }
-  };
-  // weight fragment first: the lane then holds 4 consecutive output columns of one row.
-  // the tag is the number of 32-row fragments of the wave that hold a valid row; the others issue no MFMA
-  auto mma = [&](auto set_tag, auto full_tag) __attribute__((always_inline)) {
-    constexpr int NFA = decltype(full_tag)::value;
-    constexpr int set = decltype(set_tag)::value;
+  // ---------------- main loop ----------------------------------------------------
+  f32x4_t acc[8][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (i < NFA) {
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+
+  // two fragment sets: one feeds the MFMAs while the other is being read
+  KnFrag fa[2][8], fb[2][8];
+  constexpr int A_OPS_PER_BLK = A_KN ? 2 : 1, B_OPS_PER_BLK = B_KN ? 2 : 1;
+  // Read instruction number `op` of a sub-step: the A blocks first (only the live ones), then the B blocks.
+  auto read_op = [&](auto slot_a_tag, auto slot_b_tag, auto s_tag, auto set_tag, auto nv_tag, auto op_tag) __attribute__((always_inline)) {
+    constexpr int SA = decltype(slot_a_tag)::value, SB = decltype(slot_b_tag)::value, S = decltype(s_tag)::value;
+    constexpr int SET = decltype(set_tag)::value, NV = decltype(nv_tag)::value, OP = decltype(op_tag)::value;
+    constexpr int A_OPS = 2 * NV * A_OPS_PER_BLK;
+    if constexpr (OP < A_OPS) {
+      constexpr int blk = OP / A_OPS_PER_BLK;
+      if constexpr (A_KN) {
+        constexpr int half = OP % 2;
+        fa[SET][blk].h[half] = lds_read_tr_b64<(SA & 1) * TILE_BYTES + S * 16384 + half * 2048 + (blk & 1) * 32>(fa_base[SA >> 1][blk >> 1]);
+      } else {
+        constexpr int X = (((2 * blk) & 6) ^ (4 * S)) >> 1;
+        fa[SET][blk].v = lds_read_b128<(SA & 1) * TILE_BYTES + blk * 2048>(fa_base[SA >> 1][X]);
       }
-  };
-
-  // One quarter of an MFMA group: the two MFMAs that share activation fragment i.  The loads of a
-  // step are issued between such pairs, never in a burst: a wave whose load has to queue for the
-  // texture path issues nothing else meanwhile, its MFMAs included.
-  auto mma_pair = [&](auto set_tag, auto i_tag, auto full_tag) __attribute__((always_inline)) {
-    constexpr int NFA = decltype(full_tag)::value;
-    constexpr int set = decltype(set_tag)::value, i = decltype(i_tag)::value;
-    if constexpr (i < NFA) {
-      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][0], fa[set][i], acc[i][0], 0, 0, 0);
-      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][1], fa[set][i], acc[i][1], 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  };
-
-  const int grow0 = m0 + wm * 128;                                   // wave's first output row
-  const int gcol0 = n0 + wn * (MODE == GATE_UP ? 32 : 64);           // wave's first output column
-  // DGRAD_H: saved g / u rows of one part of the wave's 128 rows (a 64-row half; a 32-row quarter for
-  // DGRAD_H_GATE, whose epilogue needs more registers for itself), 16 bytes per lane and pass
-  constexpr int GU_PARTS = (MODE == DGRAD_H_GATE) ? 4 : 2;
-  constexpr int GU_ROWS = 128 / GU_PARTS;
-  constexpr int GU_PASSES = GU_ROWS / 8;
-  u32x4 pg[GU_PASSES], pu[GU_PASSES];
-  auto gu_load = [&](int hh, ArgPtr ap) __attribute__((always_inline)) {
-    if constexpr (is_dgrad_h(MODE)) {
-      const int ncol = ap->N;
-      const uint16_t* gsrc = ap->G;
-      const uint16_t* usrc = ap->U;
-#pragma unroll
-      for (int p = 0; p < GU_PASSES; ++p) {
-        const int row = p * 8 + (lane >> 3), piece = lane & 7;
-        int gr = grow0 + hh * GU_ROWS + row;  if (gr > m_end - 1) gr = m_end - 1;
-        int gc = gcol0 + piece * 8;  if (gc > ncol - 8) gc = ncol - 8;
-        const size_t o = static_cast<size_t>(gr) * ncol + gc;
-        pg[p] = *reinterpret_cast<const u32x4*>(gsrc + o);
-        pu[p] = *reinterpret_cast<const u32x4*>(usrc + o);
+    } else {
+      constexpr int OB = OP - A_OPS;
+      constexpr int blk = OB / B_OPS_PER_BLK;
+      if constexpr (B_KN) {
+        constexpr int half = OB % 2;
+        fb[SET][blk].h[half] = lds_read_tr_b64<(SB & 1) * TILE_BYTES + S * 16384 + half * 2048 + (blk & 1) * 32>(fb_base[SB >> 1][blk >> 1]);
+      } else {
+        constexpr int X = (((2 * blk) & 6) ^ (4 * S)) >> 1;
+        fb[SET][blk].v = lds_read_b128<(SB & 1) * TILE_BYTES + blk * 2048>(fb_base[SB >> 1][X]);
       }
     }
   };
+  // weight fragment first: the lane then holds 4 consecutive output columns of one row
+  auto mma = [&](auto set_tag, auto i_tag, auto j_tag) __attribute__((always_inline)) {
+    constexpr int SET = decltype(set_tag)::value, i = decltype(i_tag)::value, j = decltype(j_tag)::value;
+    f32x4_t& c = acc[i][j];
+    const bf16x8_t& wfrag = fb[SET][j].v;
+    const bf16x8_t& afrag = fa[SET][i].v;
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(wfrag), "v"(afrag));
+  };
 
-  // Step kt (phase P = kt mod 5) reads A from slot 2P mod 5 and B from slot (2P+1) mod 5.  Its
-  // barrier comes before its last MFMA group, after every wave has (a) seen its own loads of
-  // A(kt+1) and B(kt+1) land (the four loads of A(kt+2), issued last, may still be in flight) and
-  // (b) received its last fragments of step kt.  Behind it the tiles of step kt+1 are complete and
-  // the two slots of step kt are free: B(kt+2) goes into A's slot at once, A(kt+3) into B's slot
-  // between the MFMAs.
-  using I0 = std::integral_constant<int, 0>;
-  using I1 = std::integral_constant<int, 1>;
-  using I2 = std::integral_constant<int, 2>;
-  using I3 = std::integral_constant<int, 3>;
-  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
-  auto step = [&](int kt, auto phase_tag, auto full_tag) __attribute__((always_inline)) {
-    constexpr int P = decltype(phase_tag)::value;
-    using SA = std::integral_constant<int, slot_of_a(P)>;
-    using SB = std::integral_constant<int, slot_of_b(P)>;
-    using NA = std::integral_constant<int, slot_of_a((P + 1) % NSLOT)>;
-    using NB = std::integral_constant<int, slot_of_b((P + 1) % NSLOT)>;
-    using LA = std::integral_constant<int, slot_of_a((P + 2) % NSLOT)>;   // where A(kt+2) goes: B(kt-1)'s slot
-    const bool more = kt + 2 < nk;
-    const bool more_a = more && a_live;
-    if constexpr (GATHER_A) {
-      // the tokens of A(kt+2) were fetched a step ago and are covered by that step's wait; those of
-      // A(kt+3) are requested before the loads of A(kt+2), the only ones this step's wait leaves in flight
-      if (more) apply_tok(tokn);
+  // One 32-deep sub-step: the live MFMAs of fragment set SET, and between them (one per gap) the read
+  // instructions of the next sub-step and, in a step that loads (LOADS), the wave's eight loads of one
+  // tile.  Gap g is the place after MFMA g: reads take the even gaps 0, 2, .. (every gap when both operands
+  // need two reads per block), M0 is set in gap 1, loads take gaps 3, 7, .., 31; what does not fit behind
+  // the last live MFMA follows it.
+  auto sub_step = [&](auto set_tag, auto nv_tag, auto nreads_tag, auto reader, auto loads_tag, auto set_m0_fn, auto loader)
+      __attribute__((always_inline)) {
+    constexpr int SET = decltype(set_tag)::value, NV = decltype(nv_tag)::value;
+    constexpr int NREADS = decltype(nreads_tag)::value;
+    constexpr bool LOADS = decltype(loads_tag)::value != 0;
+    constexpr int ML = 16 * NV;                         // live MFMAs: blocks i < 2 NV, all j
+    constexpr int RSTRIDE = NREADS > 32 ? 1 : 2;
+    constexpr int LAST_GAP = (NREADS - 1) * RSTRIDE > 31 ? (NREADS - 1) * RSTRIDE : 31;
+    constexpr int SLOTS = ML > LAST_GAP + 1 ? ML : LAST_GAP + 1;
+    static_for<SLOTS>([&](auto g_tag) {
+      constexpr int g = decltype(g_tag)::value;
+      if constexpr (g < ML) mma(IC<SET>{}, IC<g / 8>{}, IC<g % 8>{});
+      if constexpr (g % RSTRIDE == 0 && g / RSTRIDE < NREADS) reader(IC<g / RSTRIDE>{});
+      if constexpr (LOADS) {
+        if constexpr (g == 1) set_m0_fn();
+        if constexpr (g >= 3 && g <= 31 && (g - 3) % 4 == 0) loader(IC<(g - 3) / 4>{});
+      }
+    });
+  };
+
+  // Step kt at ring phase P.  KIND 2: a step that loads A(kt+2) (before its barrier, into B(kt-1)'s old slot) and
+  // B(kt+2) (behind it, into A(kt)'s slot); KIND 1: the second to last step (nothing left to load); KIND 0: the
+  // last step (no barrier, no next fragments).
+  auto step = [&](int kt, auto phase_tag, auto kind_tag, auto nv_tag) __attribute__((always_inline)) {
+    constexpr int P = decltype(phase_tag)::value, KIND = decltype(kind_tag)::value, NV = decltype(nv_tag)::value;
+    using SA = IC<slot_of_a(P)>;
+    using SB = IC<slot_of_b(P)>;
+    using NA = IC<slot_of_a((P + 1) % NSLOT)>;
+    using NB = IC<slot_of_b((P + 1) % NSLOT)>;
+    constexpr int LA = slot_of_a((P + 2) % NSLOT);
+    constexpr int NREADS = NV == 0 ? 0 : 2 * NV * A_OPS_PER_BLK + 8 * B_OPS_PER_BLK;
+    if constexpr (KIND == 2 && GATHER_A) {
+      // the tokens of A(kt+2) were fetched a step ago and are covered by that step's wait; those of A(kt+3)
+      // are requested before the loads of A(kt+2), the only ones this step's wait leaves in flight
+      apply_tok(tokn);
       if (kt + 3 < nk) fetch_tok(kt + 3, tokn);
     }
-    read_frags(SA{}, SB{}, I1{}, I1{}, full_tag);
-    lds_wait<nreads(decltype(full_tag)::value)>();  fence();
-    mma_pair(I0{}, J0{}, full_tag);  mma_pair(I0{}, J1{}, full_tag);
-    if (more_a) a_part(kt + 2, LA{}, J0{});
-    fence();
-    mma_pair(I0{}, J2{}, full_tag);  mma_pair(I0{}, J3{}, full_tag);
-    if (more_a) a_part(kt + 2, LA{}, J1{});
-    fence();
-    read_frags(SA{}, SB{}, I2{}, I0{}, full_tag);
-    lds_wait<nreads(decltype(full_tag)::value)>();  fence();
-    mma_pair(I1{}, J0{}, full_tag);  mma_pair(I1{}, J1{}, full_tag);
-    if (more_a) a_part(kt + 2, LA{}, J2{});
-    fence();
-    mma_pair(I1{}, J2{}, full_tag);  mma_pair(I1{}, J3{}, full_tag);
-    if (more_a) { a_part(kt + 2, LA{}, J3{}); a_end(kt + 2); }
-    fence();
-    read_frags(SA{}, SB{}, I3{}, I1{}, full_tag);
-    lds_wait<nreads(decltype(full_tag)::value)>();  fence();
-    mma(I0{}, full_tag);  fence();
-    if (kt + 1 < nk) {
-      if (more_a) wait_vm<4>(); else wait_vm<0>();   // this wave's loads of A(kt+2), if it has any, may stay in flight
-      lds_wait<0>();
+    sub_step(IC<0>{}, nv_tag, IC<NREADS>{},
+             [&](auto op) __attribute__((always_inline)) { read_op(SA{}, SB{}, IC<1>{}, IC<1>{}, nv_tag, op); },
+             IC<KIND == 2 ? 1 : 0>{},
+             [&]() __attribute__((always_inline)) { set_m0<LA * TILE_BYTES>(lds_fill); },
+             [&](auto i) __attribute__((always_inline)) { a_part(kt + 2, i); });
+    if constexpr (KIND == 2) a_end(kt + 2);
+    lds_wait<0>();
+    if constexpr (KIND >= 1) {
+      if constexpr (KIND == 2) wait_vm<8>(); else wait_vm<0>();   // this wave's loads of A(kt+2) may stay in flight
       wg_barrier();
-      read_frags(NA{}, NB{}, I0{}, I0{}, full_tag);
-    } else {
-      lds_wait<0>();
     }
-    fence();
-    // B(kt+2) goes into A(kt)'s slot, one load after each MFMA pair
-    mma_pair(I1{}, J0{}, full_tag);
-    if (more) { apply_tok(tokn); b_part(kt + 2, SA{}, J0{}); }
-    fence();
-    mma_pair(I1{}, J1{}, full_tag);
-    if (more) b_part(kt + 2, SA{}, J1{});
-    fence();
-    mma_pair(I1{}, J2{}, full_tag);
-    if (more) b_part(kt + 2, SA{}, J2{});
-    fence();
-    mma_pair(I1{}, J3{}, full_tag);
-    if (more) { b_part(kt + 2, SA{}, J3{}); b_end(kt + 2); }
+    if constexpr (KIND == 2 && GATHER_B) apply_tok(tokn);   // fetched a step ago, older than the loads of A(kt+2)
+    sub_step(IC<1>{}, nv_tag, IC<KIND >= 1 ? NREADS : 0>{},
+             [&](auto op) __attribute__((always_inline)) { read_op(NA{}, NB{}, IC<0>{}, IC<0>{}, nv_tag, op); },
+             IC<KIND == 2 ? 1 : 0>{},
+             [&]() __attribute__((always_inline)) { set_m0<SA::value * TILE_BYTES>(lds_fill); },
+             [&](auto i) __attribute__((always_inline)) { b_part(kt + 2, i); });
+    if constexpr (KIND == 2) {
+      b_end(kt + 2);
+      if constexpr (GATHER_B) {
+        // a whole step ahead of their use; the next step's wait covers them (they are older than its A loads)
+        if (kt + 3 < nk) fetch_tok(kt + 3, tokn);
+      }
+    }
+    lds_wait<0>();
+  };
+
+  // The tile enters the ring at phase p0 such that its second to last step is phase 0 and its last step
+  // phase 1: the steps that load (all but those two) then end on a round of the five phases.
+  const int nmain = nk >= 2 ? nk - 2 : 0;
+  const int p0 = nk >= 2 ? (NSLOT - nmain % NSLOT) % NSLOT : 1;
+  auto main_loop = [&](auto nv_tag) __attribute__((always_inline)) {
+    if (nk <= 0) return;
+    // ---- first loads: steps 0 and 1 into the slots of phases p0 and p0 + 1
+    const int p1 = (p0 + 1) % NSLOT;
+    const uint32_t m_a0 = lds_fill + ((2 * p0) % NSLOT) * TILE_BYTES, m_b0 = lds_fill + ((2 * p0 + 1) % NSLOT) * TILE_BYTES;
+    const uint32_t m_a1 = lds_fill + ((2 * p1) % NSLOT) * TILE_BYTES, m_b1 = lds_fill + ((2 * p1 + 1) % NSLOT) * TILE_BYTES;
+    auto a_unit = [&](int kt, uint32_t m) __attribute__((always_inline)) {
+      set_m0_rt(m);
+      asm volatile("s_nop 0" ::: "memory");
+      static_for<8>([&](auto i) { a_part(kt, i); });
+      a_end(kt);
+    };
+    auto b_unit = [&](int kt, uint32_t m) __attribute__((always_inline)) {
+      set_m0_rt(m);
+      asm volatile("s_nop 0" ::: "memory");
+      static_for<8>([&](auto i) { b_part(kt, i); });
+      b_end(kt);
+    };
     if constexpr (GATHER_B) {
-      // a whole step ahead of their use; the next step's wait for B(kt+2) covers them (they are older
-      // than the loads of A(kt+3), the only ones that wait leaves in flight)
-      if (kt + 3 < nk) fetch_tok(kt + 3, tokn);
+      // the tokens of steps 0 and 1 are requested first and are older than the loads of A(0), A(1): one wait for both
+      fetch_tok(0, tokn);
+      if (nk > 1) fetch_tok(1, tokn1);
+      a_unit(0, m_a0);
+      if (nk > 1) { a_unit(1, m_a1); wait_vm<16>(); } else { wait_vm<8>(); }
+      apply_tok(tokn);
+      b_unit(0, m_b0);
+      if (nk > 1) { apply_tok(tokn1); b_unit(1, m_b1); }
+      if (nk > 1) wait_vm<8>(); else wait_vm<0>();     // only B(1) may stay in flight
+    } else if constexpr (GATHER_A) {
+      fetch_tok(0, tokn);
+      if (nk > 1) fetch_tok(1, tokn1);
+      b_unit(0, m_b0);
+      if (nk > 1) { b_unit(1, m_b1); wait_vm<16>(); } else { wait_vm<8>(); }
+      apply_tok(tokn);
+      a_unit(0, m_a0);
+      if (nk > 1) {
+        apply_tok(tokn1);
+        if (nk > 2) fetch_tok(2, tokn);   // applied at the start of step 0: older than the loads of A(1)
+        a_unit(1, m_a1);
+      }
+      if (nk > 1) wait_vm<8>(); else wait_vm<0>();     // only A(1) may stay in flight
+    } else {
+      b_unit(0, m_b0);
+      a_unit(0, m_a0);
+      if (nk > 1) { b_unit(1, m_b1); a_unit(1, m_a1); wait_vm<16>(); } else { wait_vm<0>(); }
     }
-    fence();
+    wg_barrier();
+    if constexpr (GATHER_B) {
+      if (nk > 2) fetch_tok(2, tokn);   // applied behind step 0's barrier, whose wait covers it
+    }
+    // ---- first fragments: sub-step 0 of step 0, from the slots of phase p0
+    constexpr int NV = decltype(nv_tag)::value;
+    constexpr int NREADS = NV == 0 ? 0 : 2 * NV * A_OPS_PER_BLK + 8 * B_OPS_PER_BLK;
+    auto first_reads = [&](auto phase_tag) __attribute__((always_inline)) {
+      constexpr int P = decltype(phase_tag)::value;
+      static_for<NREADS>([&](auto op) { read_op(IC<slot_of_a(P)>{}, IC<slot_of_b(P)>{}, IC<0>{}, IC<0>{}, nv_tag, op); });
+    };
+    switch (p0) {
+      case 0: first_reads(IC<0>{}); break;
+      case 1: first_reads(IC<1>{}); break;
+      case 2: first_reads(IC<2>{}); break;
+      case 3: first_reads(IC<3>{}); break;
+      default: first_reads(IC<4>{}); break;
+    }
+    lds_wait<0>();
+    asm volatile("s_nop 7" ::: "memory");   // the accumulators were cleared by vector-ALU writes: keep the first MFMA clear of them
+    // ---- the steps that load, in rounds of the five phases (the first round starts at p0)
+    int kt = 0;
+    int skip = p0;
+    while (kt < nmain) {
+      if (skip <= 0) { step(kt, IC<0>{}, IC<2>{}, nv_tag); ++kt; }
+      if (skip <= 1) { step(kt, IC<1>{}, IC<2>{}, nv_tag); ++kt; }
+      if (skip <= 2) { step(kt, IC<2>{}, IC<2>{}, nv_tag); ++kt; }
+      if (skip <= 3) { step(kt, IC<3>{}, IC<2>{}, nv_tag); ++kt; }
+      step(kt, IC<4>{}, IC<2>{}, nv_tag); ++kt;
+      skip = 0;
+    }
+    // ---- the last two steps
+    if (nk >= 2) step(nk - 2, IC<0>{}, IC<1>{}, nv_tag);
+    step(nk - 1, IC<1>{}, IC<0>{}, nv_tag);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs have written before the accumulators are read
   };
-  auto main_loop = [&](auto full_tag) __attribute__((always_inline)) {
-    if (nk > 0) {
-      if constexpr (GATHER_B) {
-        // the tokens of steps 0 and 1 are requested first and are older than the eight loads of A(0), A(1):
-        // one wait for both
-        fetch_tok(0, tokn);
-        if (nk > 1) fetch_tok(1, tokn1);
-        a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
-        if (nk > 1) {
-          a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
-          wait_vm<8>();
-        } else {
-          wait_vm<4>();
-        }
-        apply_tok(tokn);
-        b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
-        if (nk > 1) {
-          apply_tok(tokn1);
-          b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
-        }
-      } else if constexpr (GATHER_A) {
-        fetch_tok(0, tokn);
-        if (nk > 1) fetch_tok(1, tokn1);
-        b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
-        if (nk > 1) {
-          b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
-          wait_vm<8>();
-        } else {
-          wait_vm<4>();
-        }
-        apply_tok(tokn);
-        a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
-        if (nk > 1) {
-          apply_tok(tokn1);
-          if (nk > 2) fetch_tok(2, tokn);   // applied at the start of step 0: older than the loads of A(1)
-          a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
-        }
-      } else {
-        // the weight tile first: its addresses are ready, while those of the activation tile may still
-        // wait for the tokens of the tile's rows (gathered rows)
-        b_unit(0, std::integral_constant<int, slot_of_b(0)>{});
-        if (a_live) a_unit(0, std::integral_constant<int, slot_of_a(0)>{});
-        if (nk > 1) {
-          b_unit(1, std::integral_constant<int, slot_of_b(1)>{});
-          if (a_live) a_unit(1, std::integral_constant<int, slot_of_a(1)>{});
-        }
-      }
-      if constexpr (GATHER_A || GATHER_B) {
-        // only the last four loads (A(1) or B(1)) stay in flight: both tiles of step 0 are in, and so are
-        // the tokens of A(2)
-        if (nk > 1) wait_vm<4>(); else wait_vm<0>();
-      } else {
-        if (nk > 1 && a_live) wait_vm<8>(); else if (nk > 1) wait_vm<4>(); else wait_vm<0>();
-      }
-      wg_barrier();
-      if constexpr (GATHER_B) {
-        if (nk > 2) fetch_tok(2, tokn);
-      }
-      read_frags(std::integral_constant<int, slot_of_a(0)>{}, std::integral_constant<int, slot_of_b(0)>{}, I0{}, I0{}, full_tag);
-    }
-    for (int kt = 0; kt < nk; kt += NSLOT) {
-      step(kt, I0{}, full_tag);
-      if (kt + 1 < nk) step(kt + 1, I1{}, full_tag);
-      if (kt + 2 < nk) step(kt + 2, I2{}, full_tag);
-      if (kt + 3 < nk) step(kt + 3, I3{}, full_tag);
-      if (kt + 4 < nk) step(kt + 4, std::integral_constant<int, 4>{}, full_tag);
-    }
-  };
-  // one copy of the loop per number of live fragments: a wave whose 128 rows all lie past the
+  // one copy of the loop per number of live 32-row groups: a wave whose 128 rows all lie past the
   // expert's end only keeps the loads and barriers going
-  switch (nfa) {
-    case 4: main_loop(std::integral_constant<int, 4>{}); break;
-    case 3: main_loop(std::integral_constant<int, 3>{}); break;
-    case 2: main_loop(std::integral_constant<int, 2>{}); break;
-    case 1: main_loop(std::integral_constant<int, 1>{}); break;
-    default: main_loop(std::integral_constant<int, 0>{}); break;
+  if constexpr (is_wgrad(MODE)) {
+    main_loop(IC<4>{});
+  } else {
+    switch (nv) {
+      case 4: main_loop(IC<4>{}); break;
+      case 3: main_loop(IC<3>{}); break;
+      case 2: main_loop(IC<2>{}); break;
+      case 1: main_loop(IC<1>{}); break;
+      default: main_loop(IC<0>{}); break;
+    }
   }
   const ArgPtr ae = reload_args<ARG>();     // the epilogue reads its arguments afresh
-  gu_load(0, ae);
   wg_barrier();                             // every wave is done with the operand tiles
 
   // ---------------- epilogue -----------------------------------------------------
-  // acc[i][j][4q+c] is the wave's element (row, col) with row = i*32 + lrow and
-  // col = j*32 + q*8 + lgrp*4 + c.  The wave stages bf16 rows of 128 bytes in its own
-  // 16 KB of LDS (16-byte pieces swizzled by row & 7) and stores 16 bytes per lane.
+  // acc[i][j][c] is the wave's element (row, col) with row = 16 i + (lane & 15) and
+  // col = 16 j + 4 (lane / 16) + c.  The wave stages bf16 rows of 256 bytes in its own
+  // 32 KB of LDS (16-byte pieces swizzled by row & 15) and stores 16 bytes per lane.
+  const int l16 = lane & 15, lq = lane >> 4;
+  const int grow0 = m0 + wm * 128;                                     // wave's first output row
+  const int gcol0 = n0 + wn * (MODE == GATE_UP ? 64 : 128);            // wave's first output column
   char* stage = lds + wave * WAVE_STAGE_BYTES;
-  auto quad_addr = [&](int row, int piece) __attribute__((always_inline)) -> char* {
-    return stage + row * 128 + ((piece ^ (row & 7)) << 4) + lgrp * 8;
+  // address of the 8 bytes of columns 4 lq .. + 3 of 16-column block `blk` in staged row `row`
+  auto quad_addr = [&](int row, int blk) __attribute__((always_inline)) -> char* {
+    return stage + row * 256 + (((2 * blk + (lq >> 1)) ^ (row & 15)) << 4) + (lq & 1) * 8;
   };
-  auto put_quad = [&](int row, int piece, float v0, float v1, float v2, float v3) __attribute__((always_inline)) {
+  auto put_quad = [&](int row, int blk, const f32x4_t& v) __attribute__((always_inline)) {
     u32x2 o;
-    o.x = pack_bf16(v0, v1);
-    o.y = pack_bf16(v2, v3);
-    *reinterpret_cast<u32x2*>(quad_addr(row, piece)) = o;
+    o.x = pack_bf16(v[0], v[1]);
+    o.y = pack_bf16(v[2], v[3]);
+    *reinterpret_cast<u32x2*>(quad_addr(row, blk)) = o;
   };
-  // stores `rows` staged rows starting at staged row 0 to out (row stride ld); the first
-  // `pieces` 16-byte pieces of each row go to columns col0 + piece*8 (pieces = 4 or 8)
-  auto flush = [&](uint16_t* out, size_t ld, int first_row, int rows, int piece0, int pieces, int col0, int ncols) __attribute__((always_inline)) {
+  // stores `rows` staged rows (from staged row srow0) to out rows first_row .. (row stride ld); each row's
+  // `pieces` 16-byte pieces from piece0 on go to columns col0 + 8 piece (pieces = 8 or 16)
+  auto flush = [&](uint16_t* out, size_t ld, int srow0, int first_row, int rows, int piece0, int pieces, int col0, int ncols)
+      __attribute__((always_inline)) {
     const int rpp = 64 / pieces;                    // rows per pass
     for (int p = 0; p < rows / rpp; ++p) {
       const int row = p * rpp + lane / pieces;
       const int piece = lane % pieces;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * 128 + (((piece0 + piece) ^ (row & 7)) << 4));
+      const int srow = srow0 + row;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(stage + srow * 256 + (((piece0 + piece) ^ (srow & 15)) << 4));
       const int gr = first_row + row, gc = col0 + piece * 8;
       if (gr < m_end && gc < ncols) *reinterpret_cast<u32x4*>(out + static_cast<size_t>(gr) * ld + gc) = v;
     }
   };
 
   if constexpr (MODE == GATE_UP) {
-    // gate weight of the lane's four rows (1 unless the caller folds the weights into h)
-    float wv[4] = {1.f, 1.f, 1.f, 1.f};
+    // blocks 0-3 are g, blocks 4-7 the same columns of u.
+    // gate weight of the lane's eight rows (1 unless the caller folds the weights into h)
+    float wv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) wv[i] = 1.f;
     if (ae->row_weight != nullptr) {
       const float* rw = ae->row_weight;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        int r = grow0 + i * 32 + lrow;  if (r > m_end - 1) r = m_end - 1;
+      for (int i = 0; i < 8; ++i) {
+        int r = grow0 + i * 16 + l16;  if (r > m_end - 1) r = m_end - 1;
         wv[i] = rw[r];
       }
     }
-    // pass 1: g in pieces 0-3, u in pieces 4-7
+    // pass 1: g in pieces 0-7, u in pieces 8-15
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          put_quad(i * 32 + lrow, j * 4 + q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+      for (int j = 0; j < 8; ++j) put_quad(i * 16 + l16, j, acc[i][j]);
     __builtin_amdgcn_wave_barrier();
-    flush(ae->O0, ae->N, grow0, 128, 0, 4, gcol0, ae->N);
-    flush(ae->O1, ae->N, grow0, 128, 4, 4, gcol0, ae->N);
+    flush(ae->O0, ae->N, 0, grow0, 128, 0, 8, gcol0, ae->N);
+    flush(ae->O1, ae->N, 0, grow0, 128, 8, 8, gcol0, ae->N);
     __builtin_amdgcn_wave_barrier();
     // pass 2: h = silu(g) * u from the fp32 accumulators
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float h[4];
+      for (int j = 0; j < 4; ++j) {
+        f32x4_t h;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) h[c] = silu_f(acc[i][0][4 * q + c]) * acc[i][1][4 * q + c] * wv[i];
-        put_quad(i * 32 + lrow, q, h[0], h[1], h[2], h[3]);
+        for (int c = 0; c < 4; ++c) h[c] = silu_f(acc[i][j][c]) * acc[i][j + 4][c] * wv[i];
+        put_quad(i * 16 + l16, j, h);
       }
     __builtin_amdgcn_wave_barrier();
-    flush(ae->O2, ae->N, grow0, 128, 0, 4, gcol0, ae->N);
+    flush(ae->O2, ae->N, 0, grow0, 128, 0, 8, gcol0, ae->N);
   } else if constexpr (is_dgrad_h(MODE)) {
-    // in parts of GU_ROWS rows: g rows at stage[0, 8K), u rows at stage[8K, 16K).  The g/u rows of
-    // the first part were requested at the end of the main loop, those of the next part are
-    // requested before a part is processed, so their latency stays hidden.
+    // in four parts of 32 rows: g rows at stage[0, 8K), u rows at stage[8K, 16K).  The g/u rows of a part are
+    // requested before the previous part is processed, so their latency stays hidden.
     // DGRAD_H_GATE: the accumulators hold dh0 = dout[token] . Wd; the row's gate weight w turns them into
-    // dh = w dh0, and sum over the wave's 64 columns of dh0 * silu(g) * u is the wave's share of the
-    // gradient of w (a lane holds 32 of the columns of its row, lane ^ 32 the other 32).
+    // dh = w dh0, and the sum over a 64-column strip of dh0 * silu(g) * u is the strip's share of the
+    // gradient of w (a lane holds 16 of the strip's columns of its row, lanes ^ 16, ^ 32 the others).
     constexpr bool GATE = (MODE == DGRAD_H_GATE);
-    char* ustage = stage + WAVE_STAGE_BYTES / 2;
-    constexpr int NI = GU_ROWS / 32;    // 32-row accumulator blocks per part
+    constexpr int GU_PASSES = 8;   // 32 rows x 16 pieces = 512 pieces of 16 bytes, 64 per pass
+    u32x4 pg[GU_PASSES], pu[GU_PASSES];
+    auto gu_load = [&](int part) __attribute__((always_inline)) {
+      const int ncol = ae->N;
+      const uint16_t* gsrc = ae->G;
+      const uint16_t* usrc = ae->U;
 #pragma unroll
-    for (int hh = 0; hh < GU_PARTS; ++hh) {
-      const int first = grow0 + hh * GU_ROWS;
-      float wrow[2] = {1.f, 1.f}, dsum[2] = {0.f, 0.f};
+      for (int p = 0; p < GU_PASSES; ++p) {
+        const int row = p * 4 + (lane >> 4), piece = lane & 15;
+        int gr = grow0 + part * 32 + row;  if (gr > m_end - 1) gr = m_end - 1;
+        int gc = gcol0 + piece * 8;  if (gc > ncol - 8) gc = ncol - 8;
+        const size_t o = static_cast<size_t>(gr) * ncol + gc;
+        pg[p] = *reinterpret_cast<const u32x4*>(gsrc + o);
+        pu[p] = *reinterpret_cast<const u32x4*>(usrc + o);
+      }
+    };
+    gu_load(0);
+    constexpr int UOFF = 8192;
+#pragma unroll
+    for (int part = 0; part < 4; ++part) {
+      const int first = grow0 + part * 32;
+      float wrow[2] = {1.f, 1.f}, dsum[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
       if constexpr (GATE) {
         const float* rw = ae->row_weight;
 #pragma unroll
-        for (int i2 = 0; i2 < NI; ++i2) {
-          int r = first + i2 * 32 + lrow;  if (r > m_end - 1) r = m_end - 1;
+        for (int i2 = 0; i2 < 2; ++i2) {
+          int r = first + i2 * 16 + l16;  if (r > m_end - 1) r = m_end - 1;
           wrow[i2] = rw[r];
         }
       }
 #pragma unroll
       for (int p = 0; p < GU_PASSES; ++p) {
-        const int row = p * 8 + (lane >> 3), piece = lane & 7;
-        const int so = row * 128 + ((piece ^ (row & 7)) << 4);
+        const int row = p * 4 + (lane >> 4), piece = lane & 15;
+        const int so = row * 256 + ((piece ^ (row & 15)) << 4);
         *reinterpret_cast<u32x4*>(stage + so) = pg[p];
-        *reinterpret_cast<u32x4*>(ustage + so) = pu[p];
+        *reinterpret_cast<u32x4*>(stage + UOFF + so) = pu[p];
       }
-      if (hh + 1 < GU_PARTS) gu_load(hh + 1, ae);
+      if (part + 1 < 4) gu_load(part + 1);
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int i2 = 0; i2 < NI; ++i2)
+      for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 8; ++j) {
+          const int row = i2 * 16 + l16;
+          char* ga = quad_addr(row, j);
+          char* ua = ga + UOFF;
+          const u32x2 gq = *reinterpret_cast<const u32x2*>(ga);
+          const u32x2 uq = *reinterpret_cast<const u32x2*>(ua);
+          const float g4[4] = {bf16lo(gq.x), bf16hi(gq.x), bf16lo(gq.y), bf16hi(gq.y)};
+          const float u4[4] = {bf16lo(uq.x), bf16hi(uq.x), bf16lo(uq.y), bf16hi(uq.y)};
+          float dg[4], du[4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int row = i2 * 32 + lrow;
-            char* ga = quad_addr(row, j * 4 + q);
-            char* ua = ga + WAVE_STAGE_BYTES / 2;
-            const u32x2 gq = *reinterpret_cast<const u32x2*>(ga);
-            const u32x2 uq = *reinterpret_cast<const u32x2*>(ua);
-            const float g4[4] = {bf16lo(gq.x), bf16hi(gq.x), bf16lo(gq.y), bf16hi(gq.y)};
-            const float u4[4] = {bf16lo(uq.x), bf16hi(uq.x), bf16lo(uq.y), bf16hi(uq.y)};
-            float dg[4], du[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              const float sg = sigmoid_f(g4[c]);
-              if constexpr (GATE) {
-                const float dh0 = acc[hh * NI + i2][j][4 * q + c];
-                const float sl = g4[c] * sg;                 // silu(g)
-                const float t0 = dh0 * u4[c];
-                dsum[i2] = __builtin_fmaf(t0, sl, dsum[i2]);
-                du[c] = (dh0 * wrow[i2]) * sl;
-                dg[c] = (t0 * wrow[i2]) * (sg * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f));
-              } else {
-                const float dh = acc[hh * NI + i2][j][4 * q + c];
-                const float a = dh * sg;                     // shared by both derivatives
-                du[c] = a * g4[c];
-                dg[c] = (a * u4[c]) * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f);
-              }
+          for (int c = 0; c < 4; ++c) {
+            const float sg = sigmoid_f(g4[c]);
+            if constexpr (GATE) {
+              const float dh0 = acc[part * 2 + i2][j][c];
+              const float sl = g4[c] * sg;                 // silu(g)
+              const float t0 = dh0 * u4[c];
+              dsum[i2][j >> 2] = __builtin_fmaf(t0, sl, dsum[i2][j >> 2]);
+              du[c] = (dh0 * wrow[i2]) * sl;
+              dg[c] = (t0 * wrow[i2]) * (sg * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f));
+            } else {
+              const float dh = acc[part * 2 + i2][j][c];
+              const float t = dh * sg;                     // shared by both derivatives
+              du[c] = t * g4[c];
+              dg[c] = (t * u4[c]) * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f);
             }
-            u32x2 o;
-            o.x = pack_bf16(dg[0], dg[1]);  o.y = pack_bf16(dg[2], dg[3]);
-            *reinterpret_cast<u32x2*>(ga) = o;
-            o.x = pack_bf16(du[0], du[1]);  o.y = pack_bf16(du[2], du[3]);
-            *reinterpret_cast<u32x2*>(ua) = o;
           }
+          u32x2 o;
+          o.x = pack_bf16(dg[0], dg[1]);  o.y = pack_bf16(dg[2], dg[3]);
+          *reinterpret_cast<u32x2*>(ga) = o;
+          o.x = pack_bf16(du[0], du[1]);  o.y = pack_bf16(du[2], du[3]);
+          *reinterpret_cast<u32x2*>(ua) = o;
+        }
       if constexpr (GATE) {
-        if (gcol0 < ae->N) {     // a strip past the last column holds repeated columns: no share
-          const int strips = ae->N >> 6;
-          float* part = ae->dgate_part + (gcol0 >> 6);
+        const int strips = ae->N >> 6;
 #pragma unroll
-          for (int i2 = 0; i2 < NI; ++i2) {
-            const float t = dsum[i2] + __shfl_xor(dsum[i2], 32, 64);
-            const int r = first + i2 * 32 + lrow;
-            if (lgrp == 0 && r < m_end) part[static_cast<size_t>(r) * strips] = t;
+        for (int s2 = 0; s2 < 2; ++s2) {
+          if (gcol0 + s2 * 64 < ae->N) {     // a strip past the last column holds repeated columns: no share
+            float* part_out = ae->dgate_part + ((gcol0 >> 6) + s2);
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2) {
+              float t = dsum[i2][s2];
+              t += __shfl_xor(t, 16, 64);
+              t += __shfl_xor(t, 32, 64);
+              const int r = first + i2 * 16 + l16;
+              if (lq == 0 && r < m_end) part_out[static_cast<size_t>(r) * strips] = t;
+            }
           }
         }
       }
       __builtin_amdgcn_wave_barrier();
       for (int p = 0; p < GU_PASSES; ++p) {
-        const int row = p * 8 + (lane >> 3), piece = lane & 7;
-        const int so = row * 128 + ((piece ^ (row & 7)) << 4);
+        const int row = p * 4 + (lane >> 4), piece = lane & 15;
+        const int so = row * 256 + ((piece ^ (row & 15)) << 4);
         const u32x4 dgv = *reinterpret_cast<const u32x4*>(stage + so);
-        const u32x4 duv = *reinterpret_cast<const u32x4*>(ustage + so);
+        const u32x4 duv = *reinterpret_cast<const u32x4*>(stage + UOFF + so);
         const int gr = first + row, gc = gcol0 + piece * 8;
         if (gr < m_end && gc < ae->N) {
           const size_t o = static_cast<size_t>(gr) * ae->N + gc;
@@ -970,16 +954,13 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          put_quad(i * 32 + lrow, j * 4 + q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+      for (int j = 0; j < 8; ++j) put_quad(i * 16 + l16, j, acc[i][j]);
     __builtin_amdgcn_wave_barrier();
     uint16_t* out = second ? ae->O1 : ae->O0;
     if constexpr (is_wgrad(MODE)) out += static_cast<size_t>(e) * ae->M * ae->N;
-    flush(out, ae->N, grow0, 128, 0, 8, gcol0, ae->N);
+    flush(out, ae->N, 0, grow0, 128, 0, 16, gcol0, ae->N);
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's staging reads are done
   wg_barrier();      // the staging area becomes operand stages again
@@ -1010,8 +991,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_pair_kernel(GemmArg
   gemm_tile_list<MODE_B, 1>(b, next);
 }
 
-// Workgroups of the persistent launch: one per compute unit (the 160 KB of LDS allow no more),
-// a multiple of 8 so that every XCD gets the same share, and no more than there can be tiles.
 // Per-device facts, looked up once per device: HIP keeps function attributes and the number of compute
 // units per device, and a process may drive several.  Races between host threads are benign (both write
 // the same values).
@@ -1021,6 +1000,8 @@ int current_device() {
   if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = 0; }
   return dev >= 0 && dev < MAX_DEVICES ? dev : 0;
 }
+// Workgroups of the persistent launch: one per compute unit (the 160 KB of LDS allow no more),
+// a multiple of 8 so that every XCD gets the same share, and no more than there can be tiles.
 int persistent_grid(long long max_tiles) {
   static int cus_of[MAX_DEVICES] = {};
   const int dev = current_device();
@@ -1124,10 +1105,10 @@ int gemm_fwd(const moe_bf16* xp, const int32_t* row_token, const float* row_weig
   return launch_gemm<DOWN>(b, static_cast<long long>(b.n_tiles) * m_tiles, s, "gemm_down");
 }
 
-// byte offsets of gathered rows are 32-bit lane offsets from the start of x
+// byte offsets of gathered rows are 32-bit lane offsets from the start of x (T*width*2 bytes just under 4 GiB at most)
 bool bad_gather(const moe_bf16* x, int T, const int32_t* row_token, int width) {
   return !x || !row_token || T <= 0 || !moe_aligned16(row_token) ||
-         static_cast<unsigned long long>(T) * width * sizeof(moe_bf16) > 0xFFFFFFFFull;
+         static_cast<unsigned long long>(T) * width * sizeof(moe_bf16) > 0xFFFFFFFFull - 65536;   // lane offsets carry a small bias on top
 }
 }  // namespace
 
