@@ -431,14 +431,16 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   const char* sb_phase1 = nullptr;
   if constexpr (MODE == DGRAD_X) { sa_phase1 = scalarize(abase + a_phase - LOAD_BIAS); sb_phase1 = scalarize(bbase + b_phase - LOAD_BIAS); }
 
-  // Load i of the A / B tile of step kt (M0 must point at the tile's slot already).
-  auto a_part = [&](int kt, auto i_tag) __attribute__((always_inline)) {
-    constexpr int i = decltype(i_tag)::value;
+  // Load i of the A / B tile of step kt (M0 must point at the tile's slot already).  In the weight gradients the
+  // last step of an expert may be partial (its row count is no multiple of 64): reduction rows at or past the
+  // expert's end then read zeros in one operand (per-lane 64-bit addresses) and a valid row in the other.
+  // SP 0: the step is known to be whole; 1: known to be the partial one; 2: look (first loads of a tile).
+  const bool last_partial = is_wgrad(MODE) && ((k_hi - k_lo) % BK) != 0;
+  auto a_part = [&](int kt, auto i_tag, auto sp_tag) __attribute__((always_inline)) {
+    constexpr int i = decltype(i_tag)::value, SP = decltype(sp_tag)::value;
     constexpr int OFF = (i - 4) * 1024;
-    if constexpr (is_wgrad(MODE) && !GATHER_A) {
-      if (k_lo + (kt + 1) * BK > k_hi) {
-        // last, partial step of the expert: reduction rows at or past its end read zeros
-        // (per-lane 64-bit addresses; once per tile)
+    if constexpr (is_wgrad(MODE) && !GATHER_A && SP != 0) {
+      if (SP == 1 || (last_partial && kt == nk - 1)) {
         const int krow = k_lo + kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
         dma16_lane_imm<OFF>(krow < k_hi ? sa_next + voa[i]
                                         : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16 - OFF);
@@ -447,22 +449,20 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     }
     dma16_imm<OFF>(voa[i], sa_next);   // GATHER_A: rows past the expert's end were clamped when their tokens were fetched
   };
-  auto b_part = [&](int kt, auto i_tag) __attribute__((always_inline)) {
-    constexpr int i = decltype(i_tag)::value;
+  auto b_part = [&](int kt, auto i_tag, auto sp_tag) __attribute__((always_inline)) {
+    constexpr int i = decltype(i_tag)::value, SP = decltype(sp_tag)::value;
     constexpr int OFF = (i - 4) * 1024;
-    if constexpr (GATHER_A) {
-      if (k_lo + (kt + 1) * BK > k_hi) {
-        // the gathered operand repeats the expert's last row past its end: this one reads zeros there
+    if constexpr ((GATHER_A || MODE == WGRAD) && SP != 0) {
+      if (SP == 1 || (last_partial && kt == nk - 1)) {
         const int krow = k_lo + kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
-        dma16_lane_imm<OFF>(krow < k_hi ? sb_next + vob[i]
-                                        : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16 - OFF);
-        return;
-      }
-    } else if constexpr (MODE == WGRAD) {
-      if (k_lo + (kt + 1) * BK > k_hi) {
-        // ... and the other operand reads its last valid row there, so that zero times it is zero
-        const int krow = k_lo + kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
-        dma16_lane_imm<OFF>(sb_next + vob[i] - (krow < k_hi ? 0 : static_cast<size_t>(krow - (k_hi - 1)) * a.N * 2));
+        if constexpr (GATHER_A) {
+          // the gathered operand repeats the expert's last row past its end: this one reads zeros there
+          dma16_lane_imm<OFF>(krow < k_hi ? sb_next + vob[i]
+                                          : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16 - OFF);
+        } else {
+          // ... and the other operand reads its last valid row there, so that zero times it is zero
+          dma16_lane_imm<OFF>(sb_next + vob[i] - (krow < k_hi ? 0 : static_cast<size_t>(krow - (k_hi - 1)) * a.N * 2));
+        }
         return;
       }
     }
@@ -628,7 +628,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   // Step kt at ring phase P.  KIND 2: a step that loads A(kt+2) (before its barrier, into B(kt-1)'s old slot) and
   // B(kt+2) (behind it, into A(kt)'s slot); KIND 1: the second to last step (nothing left to load); KIND 0: the
   // last step (no barrier, no next fragments).
-  auto step = [&](int kt, auto phase_tag, auto kind_tag, auto nv_tag) __attribute__((always_inline)) {
+  auto step = [&](int kt, auto phase_tag, auto kind_tag, auto nv_tag, auto sp_tag) __attribute__((always_inline)) {
     constexpr int P = decltype(phase_tag)::value, KIND = decltype(kind_tag)::value, NV = decltype(nv_tag)::value;
     using SA = IC<slot_of_a(P)>;
     using SB = IC<slot_of_b(P)>;
@@ -646,7 +646,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
              [&](auto op) __attribute__((always_inline)) { read_op(SA{}, SB{}, IC<1>{}, IC<1>{}, nv_tag, op); },
              IC<KIND == 2 ? 1 : 0>{},
              [&]() __attribute__((always_inline)) { set_m0<LA * TILE_BYTES>(lds_fill); },
-             [&](auto i) __attribute__((always_inline)) { a_part(kt + 2, i); });
+             [&](auto i) __attribute__((always_inline)) { a_part(kt + 2, i, sp_tag); });
     if constexpr (KIND == 2) a_end(kt + 2);
     lds_wait<0>();
     if constexpr (KIND >= 1) {
@@ -658,7 +658,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
              [&](auto op) __attribute__((always_inline)) { read_op(NA{}, NB{}, IC<0>{}, IC<0>{}, nv_tag, op); },
              IC<KIND == 2 ? 1 : 0>{},
              [&]() __attribute__((always_inline)) { set_m0<SA::value * TILE_BYTES>(lds_fill); },
-             [&](auto i) __attribute__((always_inline)) { b_part(kt + 2, i); });
+             [&](auto i) __attribute__((always_inline)) { b_part(kt + 2, i, sp_tag); });
     if constexpr (KIND == 2) {
       b_end(kt + 2);
       if constexpr (GATHER_B) {
@@ -669,10 +669,12 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     lds_wait<0>();
   };
 
-  // The tile enters the ring at phase p0 such that its second to last step is phase 0 and its last step
-  // phase 1: the steps that load (all but those two) then end on a round of the five phases.
-  const int nmain = nk >= 2 ? nk - 2 : 0;
-  const int p0 = nk >= 2 ? (NSLOT - nmain % NSLOT) % NSLOT : 1;
+  // The last three steps of a tile are copies of their own: the last step that loads (it loads the tile's last
+  // step, the one that may be partial in a weight gradient: SP 1), the step that only awaits, and the last one.
+  // The tile enters the ring at the phase p0 that puts these three on phases 0, 1 and 2, so that the steps
+  // before them end on a round of the five phases.
+  const int nmain = nk >= 3 ? nk - 3 : 0;
+  const int p0 = nk >= 3 ? (NSLOT - nmain % NSLOT) % NSLOT : (nk == 2 ? 1 : 2);
   auto main_loop = [&](auto nv_tag) __attribute__((always_inline)) {
     if (nk <= 0) return;
     // ---- first loads: steps 0 and 1 into the slots of phases p0 and p0 + 1
@@ -682,13 +684,13 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     auto a_unit = [&](int kt, uint32_t m) __attribute__((always_inline)) {
       set_m0_rt(m);
       asm volatile("s_nop 0" ::: "memory");
-      static_for<8>([&](auto i) { a_part(kt, i); });
+      static_for<8>([&](auto i) { a_part(kt, i, IC<2>{}); });
       a_end(kt);
     };
     auto b_unit = [&](int kt, uint32_t m) __attribute__((always_inline)) {
       set_m0_rt(m);
       asm volatile("s_nop 0" ::: "memory");
-      static_for<8>([&](auto i) { b_part(kt, i); });
+      static_for<8>([&](auto i) { b_part(kt, i, IC<2>{}); });
       b_end(kt);
     };
     if constexpr (GATHER_B) {
@@ -743,16 +745,17 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     int kt = 0;
     int skip = p0;
     while (kt < nmain) {
-      if (skip <= 0) { step(kt, IC<0>{}, IC<2>{}, nv_tag); ++kt; }
-      if (skip <= 1) { step(kt, IC<1>{}, IC<2>{}, nv_tag); ++kt; }
-      if (skip <= 2) { step(kt, IC<2>{}, IC<2>{}, nv_tag); ++kt; }
-      if (skip <= 3) { step(kt, IC<3>{}, IC<2>{}, nv_tag); ++kt; }
-      step(kt, IC<4>{}, IC<2>{}, nv_tag); ++kt;
+      if (skip <= 0) { step(kt, IC<0>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
+      if (skip <= 1) { step(kt, IC<1>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
+      if (skip <= 2) { step(kt, IC<2>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
+      if (skip <= 3) { step(kt, IC<3>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
+      step(kt, IC<4>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt;
       skip = 0;
     }
-    // ---- the last two steps
-    if (nk >= 2) step(nk - 2, IC<0>{}, IC<1>{}, nv_tag);
-    step(nk - 1, IC<1>{}, IC<0>{}, nv_tag);
+    // ---- the last three steps
+    if (nk >= 3) step(nk - 3, IC<0>{}, IC<2>{}, nv_tag, IC<is_wgrad(MODE) ? 1 : 0>{});
+    if (nk >= 2) step(nk - 2, IC<1>{}, IC<1>{}, nv_tag, IC<0>{});
+    step(nk - 1, IC<2>{}, IC<0>{}, nv_tag, IC<0>{});
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs have written before the accumulators are read
   };
   // one copy of the loop per number of live 32-row groups: a wave whose 128 rows all lie past the
@@ -775,6 +778,19 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   // acc[i][j][c] is the wave's element (row, col) with row = 16 i + (lane & 15) and
   // col = 16 j + 4 (lane / 16) + c.  The wave stages bf16 rows of 256 bytes in its own
   // 32 KB of LDS (16-byte pieces swizzled by row & 15) and stores 16 bytes per lane.
+  // The accumulators are read out of the accumulation registers at the point of use, by hand: left to the
+  // compiler they are moved (and spilled) in bulk where the copies of the main loop join.
+  auto accq = [&](auto i_tag, auto j_tag) __attribute__((always_inline)) -> f32x4_t {
+    constexpr int i = decltype(i_tag)::value, j = decltype(j_tag)::value;
+    f32x4_t v;
+    float t;
+    const float c0 = acc[i][j][0], c1 = acc[i][j][1], c2 = acc[i][j][2], c3 = acc[i][j][3];
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(c0));  v[0] = t;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(c1));  v[1] = t;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(c2));  v[2] = t;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(c3));  v[3] = t;
+    return v;
+  };
   const int l16 = lane & 15, lq = lane >> 4;
   const int grow0 = m0 + wm * 128;                                     // wave's first output row
   const int gcol0 = n0 + wn * (MODE == GATE_UP ? 64 : 128);            // wave's first output column
@@ -789,19 +805,32 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     o.y = pack_bf16(v[2], v[3]);
     *reinterpret_cast<u32x2*>(quad_addr(row, blk)) = o;
   };
-  // stores `rows` staged rows (from staged row srow0) to out rows first_row .. (row stride ld); each row's
-  // `pieces` 16-byte pieces from piece0 on go to columns col0 + 8 piece (pieces = 8 or 16)
-  auto flush = [&](uint16_t* out, size_t ld, int srow0, int first_row, int rows, int piece0, int pieces, int col0, int ncols)
-      __attribute__((always_inline)) {
-    const int rpp = 64 / pieces;                    // rows per pass
-    for (int p = 0; p < rows / rpp; ++p) {
-      const int row = p * rpp + lane / pieces;
-      const int piece = lane % pieces;
-      const int srow = srow0 + row;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(stage + srow * 256 + (((piece0 + piece) ^ (srow & 15)) << 4));
-      const int gr = first_row + row, gc = col0 + piece * 8;
-      if (gr < m_end && gc < ncols) *reinterpret_cast<u32x4*>(out + static_cast<size_t>(gr) * ld + gc) = v;
-    }
+  // Stores ROWS staged rows of RB bytes (pieces swizzled by row & (RB / 16 - 1); region at `base`) to out rows
+  // first_row .. (row stride ld): each row's PIECES 16-byte pieces from piece PIECE0 on go to columns
+  // col0 + 8 piece.  Eight passes at a time: their LDS reads are issued together, then their stores (one wave
+  // per SIMD: nothing else would cover the latency of a read-then-store chain).
+  auto flush = [&](const char* base, auto rb_tag, uint16_t* out, size_t ld, int first_row, auto rows_tag, auto piece0_tag,
+                   auto pieces_tag, int col0, int ncols) __attribute__((always_inline)) {
+    constexpr int RB = decltype(rb_tag)::value, ROWS = decltype(rows_tag)::value;
+    constexpr int PIECE0 = decltype(piece0_tag)::value, PIECES = decltype(pieces_tag)::value;
+    constexpr int RPP = 64 / PIECES, PASSES = ROWS / RPP, SWZ = RB / 16 - 1;
+    const int prow = lane / PIECES, piece = lane % PIECES;
+    const int gc = col0 + piece * 8;
+    static_for<(PASSES + 7) / 8>([&](auto b_tag) {
+      constexpr int P0 = decltype(b_tag)::value * 8;
+      constexpr int NB = PASSES - P0 < 8 ? PASSES - P0 : 8;
+      u32x4 v[NB];
+#pragma unroll
+      for (int k = 0; k < NB; ++k) {
+        const int row = (P0 + k) * RPP + prow;
+        v[k] = *reinterpret_cast<const u32x4*>(base + row * RB + (((PIECE0 + piece) ^ (row & SWZ)) << 4));
+      }
+#pragma unroll
+      for (int k = 0; k < NB; ++k) {
+        const int gr = first_row + (P0 + k) * RPP + prow;
+        if (gr < m_end && gc < ncols) *reinterpret_cast<u32x4*>(out + static_cast<size_t>(gr) * ld + gc) = v[k];
+      }
+    });
   };
 
   if constexpr (MODE == GATE_UP) {
@@ -818,27 +847,36 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
         wv[i] = rw[r];
       }
     }
-    // pass 1: g in pieces 0-7, u in pieces 8-15
+    // two halves of 64 rows: g in pieces 0-7 and u in pieces 8-15 of 256-byte rows, h = silu(g) * u (from the fp32
+    // accumulators) in 128-byte rows behind them; the stores of a half are in flight while the next is computed
+    char* hstage = stage + 64 * 256;
+    static_for<2>([&](auto hh_tag) {
+      constexpr int HH = decltype(hh_tag)::value;
+      constexpr int hh = HH;
+      static_for<4>([&](auto i2_tag) {
+        constexpr int i2 = decltype(i2_tag)::value;
+        const int row = i2 * 16 + l16;
+        static_for<4>([&](auto j_tag) {
+          constexpr int j = decltype(j_tag)::value;
+          const f32x4_t gv = accq(IC<HH * 4 + i2>{}, IC<j>{});
+          const f32x4_t uv = accq(IC<HH * 4 + i2>{}, IC<j + 4>{});
+          put_quad(row, j, gv);
+          put_quad(row, j + 4, uv);
+          u32x2 o;
+          float h[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) put_quad(i * 16 + l16, j, acc[i][j]);
-    __builtin_amdgcn_wave_barrier();
-    flush(ae->O0, ae->N, 0, grow0, 128, 0, 8, gcol0, ae->N);
-    flush(ae->O1, ae->N, 0, grow0, 128, 8, 8, gcol0, ae->N);
-    __builtin_amdgcn_wave_barrier();
-    // pass 2: h = silu(g) * u from the fp32 accumulators
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        f32x4_t h;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) h[c] = silu_f(acc[i][j][c]) * acc[i][j + 4][c] * wv[i];
-        put_quad(i * 16 + l16, j, h);
-      }
-    __builtin_amdgcn_wave_barrier();
-    flush(ae->O2, ae->N, 0, grow0, 128, 0, 8, gcol0, ae->N);
+          for (int c = 0; c < 4; ++c) h[c] = silu_f(gv[c]) * uv[c] * wv[HH * 4 + i2];
+          o.x = pack_bf16(h[0], h[1]);
+          o.y = pack_bf16(h[2], h[3]);
+          *reinterpret_cast<u32x2*>(hstage + row * 128 + (((2 * j + (lq >> 1)) ^ (row & 7)) << 4) + (lq & 1) * 8) = o;
+        });
+      });
+      __builtin_amdgcn_wave_barrier();
+      flush(stage, IC<256>{}, ae->O0, ae->N, grow0 + hh * 64, IC<64>{}, IC<0>{}, IC<8>{}, gcol0, ae->N);
+      flush(stage, IC<256>{}, ae->O1, ae->N, grow0 + hh * 64, IC<64>{}, IC<8>{}, IC<8>{}, gcol0, ae->N);
+      flush(hstage, IC<128>{}, ae->O2, ae->N, grow0 + hh * 64, IC<64>{}, IC<0>{}, IC<8>{}, gcol0, ae->N);
+      __builtin_amdgcn_wave_barrier();
+    });
   } else if constexpr (is_dgrad_h(MODE)) {
     // in four parts of 32 rows: g rows at stage[0, 8K), u rows at stage[8K, 16K).  The g/u rows of a part are
     // requested before the previous part is processed, so their latency stays hidden.
@@ -864,8 +902,8 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     };
     gu_load(0);
     constexpr int UOFF = 8192;
-#pragma unroll
-    for (int part = 0; part < 4; ++part) {
+    static_for<4>([&](auto part_tag) {
+      constexpr int part = decltype(part_tag)::value;
       const int first = grow0 + part * 32;
       float wrow[2] = {1.f, 1.f}, dsum[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
       if constexpr (GATE) {
@@ -885,11 +923,12 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
       }
       if (part + 1 < 4) gu_load(part + 1);
       __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
+      static_for<2>([&](auto i2_tag) {
+        constexpr int i2 = decltype(i2_tag)::value;
+        static_for<8>([&](auto j_tag) {
+          constexpr int j = decltype(j_tag)::value;
           const int row = i2 * 16 + l16;
+          const f32x4_t dhv = accq(IC<part * 2 + i2>{}, IC<j>{});
           char* ga = quad_addr(row, j);
           char* ua = ga + UOFF;
           const u32x2 gq = *reinterpret_cast<const u32x2*>(ga);
@@ -901,14 +940,14 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
           for (int c = 0; c < 4; ++c) {
             const float sg = sigmoid_f(g4[c]);
             if constexpr (GATE) {
-              const float dh0 = acc[part * 2 + i2][j][c];
+              const float dh0 = dhv[c];
               const float sl = g4[c] * sg;                 // silu(g)
               const float t0 = dh0 * u4[c];
               dsum[i2][j >> 2] = __builtin_fmaf(t0, sl, dsum[i2][j >> 2]);
               du[c] = (dh0 * wrow[i2]) * sl;
               dg[c] = (t0 * wrow[i2]) * (sg * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f));
             } else {
-              const float dh = acc[part * 2 + i2][j][c];
+              const float dh = dhv[c];
               const float t = dh * sg;                     // shared by both derivatives
               du[c] = t * g4[c];
               dg[c] = (t * u4[c]) * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f);
@@ -919,7 +958,8 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
           *reinterpret_cast<u32x2*>(ga) = o;
           o.x = pack_bf16(du[0], du[1]);  o.y = pack_bf16(du[2], du[3]);
           *reinterpret_cast<u32x2*>(ua) = o;
-        }
+        });
+      });
       if constexpr (GATE) {
         const int strips = ae->N >> 6;
 #pragma unroll
@@ -938,29 +978,18 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
         }
       }
       __builtin_amdgcn_wave_barrier();
-      for (int p = 0; p < GU_PASSES; ++p) {
-        const int row = p * 4 + (lane >> 4), piece = lane & 15;
-        const int so = row * 256 + ((piece ^ (row & 15)) << 4);
-        const u32x4 dgv = *reinterpret_cast<const u32x4*>(stage + so);
-        const u32x4 duv = *reinterpret_cast<const u32x4*>(stage + UOFF + so);
-        const int gr = first + row, gc = gcol0 + piece * 8;
-        if (gr < m_end && gc < ae->N) {
-          const size_t o = static_cast<size_t>(gr) * ae->N + gc;
-          *reinterpret_cast<u32x4*>(ae->O0 + o) = dgv;
-          *reinterpret_cast<u32x4*>(ae->O1 + o) = duv;
-        }
-      }
+      flush(stage, IC<256>{}, ae->O0, ae->N, first, IC<32>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
+      flush(stage + UOFF, IC<256>{}, ae->O1, ae->N, first, IC<32>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
       __builtin_amdgcn_wave_barrier();
-    }
+    });
   } else {
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) put_quad(i * 16 + l16, j, acc[i][j]);
+    static_for<8>([&](auto i_tag) {
+      static_for<8>([&](auto j_tag) { put_quad(decltype(i_tag)::value * 16 + l16, decltype(j_tag)::value, accq(i_tag, j_tag)); });
+    });
     __builtin_amdgcn_wave_barrier();
     uint16_t* out = second ? ae->O1 : ae->O0;
     if constexpr (is_wgrad(MODE)) out += static_cast<size_t>(e) * ae->M * ae->N;
-    flush(out, ae->N, 0, grow0, 128, 0, 16, gcol0, ae->N);
+    flush(stage, IC<256>{}, out, ae->N, grow0, IC<128>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's staging reads are done
   wg_barrier();      // the staging area becomes operand stages again
