@@ -247,6 +247,27 @@ __device__ __forceinline__ const char* scalarize(const char* p) {
   return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | static_cast<uint64_t>(lo));
 }
 
+// What a workgroup knows about one tile: where it lies, where its operand loads come from, how many
+// K steps it has.
+struct TileState {
+  int e, m0, m_end, nt, n0;     // expert, first output row, end of the valid rows, column tile, first output column
+  int nv;                       // 32-row groups of this wave's 128 rows that hold a valid row
+  bool second;                  // tile of the second weight gradient of a pair
+  int nk, nk_phase;             // K steps in total / in the first K phase
+  int nmain, p0;                // steps in front of the last three; ring phase of step 0
+  int k_lo, k_hi;               // weight gradients: the expert's row range is the reduction
+  bool last_partial;            // weight gradients: the last step holds fewer than 64 rows
+  uint32_t voa[8], vob[8];      // lane offsets of the eight loads per operand tile, in bytes
+  uint32_t vcb[8];              // gathered operand: lane offset of a load without its token row
+  int tokn[8], tokn1[8];        // gathered operand: tokens of the lane's eight reduction rows of coming steps
+  const char* sa_next;          // scalar bases of the next A / B tile to load (LOAD_BIAS low)
+  const char* sb_next;
+  const char* sa_phase1;        // DGRAD_X: bases of the second K phase
+  const char* sb_phase1;
+  size_t a_step, b_step;        // bytes per step
+  const int32_t* row_tok;       // gathered operand: token of the expert's first reduction row onwards
+};
+
 // One product's tile list, walked by this workgroup from list position first_tile in steps of
 // gridDim.x.  Returns the position at which the workgroup left the list, counted from its end:
 // where it enters a list that follows in the same launch.
@@ -279,15 +300,16 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   // M0 base of this wave's loads: the middle of its 8 KB share of tile slot 0 (immediates reach -4096 .. +3072)
   const uint32_t lds_fill = __builtin_amdgcn_readfirstlane(lds0 + wave * 8192 + 4096);
 
-  int tile = first_tile;
-  for (; tile < total; tile += gridDim.x) {
-  // the thread id is laundered per tile so that lane-dependent address pieces are recomputed for
-  // every tile instead of staying live (and spilling) across the whole loop
+  const int lane = tid0 & 63;
+  // Everything about tile number `tile` of the list that does not depend on the K step.
+  auto setup_tile = [&](int tile, TileState& t) __attribute__((always_inline)) {
+  // the thread id is laundered per tile so that the lane-dependent pieces of the load offsets are recomputed for
+  // every tile instead of staying live (and spilling) across the main loop
   int tid = tid0;
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   int e, m0, m_end, nt;
-  bool second = false;                  // tile of the second weight gradient of a pair
+  bool second = false;
   if constexpr (is_wgrad(MODE)) {
     nt = tile % a.n_tiles;
     const int rest = tile / a.n_tiles;
@@ -307,6 +329,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   m0 = __builtin_amdgcn_readfirstlane(m0);
   m_end = __builtin_amdgcn_readfirstlane(m_end);
   const int n0 = nt * (MODE == GATE_UP ? BN / 2 : BN);
+  t.e = e; t.m0 = m0; t.m_end = m_end; t.nt = nt; t.n0 = n0; t.second = second;
   // 32-row groups of this wave's 128 rows that hold at least one valid row (the others issue no MFMA)
   int nv = 4;
   if constexpr (!is_wgrad(MODE)) {
@@ -314,6 +337,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
     nv = __builtin_amdgcn_readfirstlane(nv);
   }
+  t.nv = nv;
 
   // ---------------- operand sources -------------------------------------------
   // Per K step and operand tile a wave issues eight direct-to-LDS loads of 1 KB each:
@@ -324,16 +348,17 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   //    lane l -> k row + l/32, physical piece l%32 = logical piece kn_piece(k row, l%32).
   //    The base advances by 64 rows per step.
   // Lane offsets carry LOAD_BIAS - (i - 4) * 1024 (see dma16_imm); the scalar bases lie LOAD_BIAS low.
-  uint32_t voa[8], vob[8];              // lane offsets in bytes
+  uint32_t (&voa)[8] = t.voa;           // lane offsets in bytes
+  uint32_t (&vob)[8] = t.vob;
   const char* abase;                    // step 0 of phase 0, without the bias
   const char* bbase;
   ptrdiff_t a_phase = 0, b_phase = 0;   // byte offset of the second K phase (DGRAD_X)
   size_t a_step, b_step;                // bytes per step
   int k_lo = 0, k_hi = 0;               // WGRAD: the expert's row range is the reduction
   const int32_t* row_tok = nullptr;     // GATHER_A/B: token of the expert's first reduction row onwards
-  uint32_t vcb[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // GATHER_A/B: lane offset of a load without its token row
-  int tokn[8] = {0, 0, 0, 0, 0, 0, 0, 0};       // GATHER_A/B: tokens of the lane's eight reduction rows of a coming step
-  int tokn1[8] = {0, 0, 0, 0, 0, 0, 0, 0};      // the same for step 1, while a tile's first loads are set up
+  uint32_t (&vcb)[8] = t.vcb;           // GATHER_A/B: lane offset of a load without its token row
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { t.vcb[i] = 0; t.tokn[i] = 0; t.tokn1[i] = 0; }
   int nk, nk_phase;                     // steps in total / in the first K phase
 
   if constexpr (is_wgrad(MODE)) {
@@ -425,59 +450,68 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   }
 
   // Both bases live in scalar registers and are advanced by scalar adds: steps are loaded in order.
-  const char* sa_next = scalarize(abase - LOAD_BIAS);
-  const char* sb_next = scalarize(bbase - LOAD_BIAS);
-  const char* sa_phase1 = nullptr;
-  const char* sb_phase1 = nullptr;
-  if constexpr (MODE == DGRAD_X) { sa_phase1 = scalarize(abase + a_phase - LOAD_BIAS); sb_phase1 = scalarize(bbase + b_phase - LOAD_BIAS); }
+  t.sa_next = scalarize(abase - LOAD_BIAS);
+  t.sb_next = scalarize(bbase - LOAD_BIAS);
+  t.sa_phase1 = nullptr;
+  t.sb_phase1 = nullptr;
+  if constexpr (MODE == DGRAD_X) { t.sa_phase1 = scalarize(abase + a_phase - LOAD_BIAS); t.sb_phase1 = scalarize(bbase + b_phase - LOAD_BIAS); }
+  t.a_step = a_step; t.b_step = b_step; t.k_lo = k_lo; t.k_hi = k_hi; t.row_tok = row_tok; t.nk = nk; t.nk_phase = nk_phase;
+  t.last_partial = is_wgrad(MODE) && ((k_hi - k_lo) % BK) != 0;
+  // The last three steps of a tile are copies of their own: the last step that loads (it loads the tile's last
+  // step, the one that may be partial in a weight gradient), the step that only awaits, and the last one.
+  // The tile enters the ring at the phase p0 that puts these three on phases 0, 1 and 2, so that the steps
+  // before them end on a round of the five phases.
+  t.nmain = nk >= 3 ? nk - 3 : 0;
+  t.p0 = nk >= 3 ? (NSLOT - t.nmain % NSLOT) % NSLOT : (nk == 2 ? 1 : 2);
+  };
+
 
   // Load i of the A / B tile of step kt (M0 must point at the tile's slot already).  In the weight gradients the
   // last step of an expert may be partial (its row count is no multiple of 64): reduction rows at or past the
   // expert's end then read zeros in one operand (per-lane 64-bit addresses) and a valid row in the other.
   // SP 0: the step is known to be whole; 1: known to be the partial one; 2: look (first loads of a tile).
-  const bool last_partial = is_wgrad(MODE) && ((k_hi - k_lo) % BK) != 0;
-  auto a_part = [&](int kt, auto i_tag, auto sp_tag) __attribute__((always_inline)) {
+  auto a_part = [&](TileState& t, int kt, auto i_tag, auto sp_tag) __attribute__((always_inline)) {
     constexpr int i = decltype(i_tag)::value, SP = decltype(sp_tag)::value;
     constexpr int OFF = (i - 4) * 1024;
     if constexpr (is_wgrad(MODE) && !GATHER_A && SP != 0) {
-      if (SP == 1 || (last_partial && kt == nk - 1)) {
-        const int krow = k_lo + kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
-        dma16_lane_imm<OFF>(krow < k_hi ? sa_next + voa[i]
+      if (SP == 1 || (t.last_partial && kt == t.nk - 1)) {
+        const int krow = t.k_lo + kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
+        dma16_lane_imm<OFF>(krow < t.k_hi ? t.sa_next + t.voa[i]
                                         : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16 - OFF);
         return;
       }
     }
-    dma16_imm<OFF>(voa[i], sa_next);   // GATHER_A: rows past the expert's end were clamped when their tokens were fetched
+    dma16_imm<OFF>(t.voa[i], t.sa_next);   // GATHER_A: rows past the expert's end were clamped when their tokens were fetched
   };
-  auto b_part = [&](int kt, auto i_tag, auto sp_tag) __attribute__((always_inline)) {
+  auto b_part = [&](TileState& t, int kt, auto i_tag, auto sp_tag) __attribute__((always_inline)) {
     constexpr int i = decltype(i_tag)::value, SP = decltype(sp_tag)::value;
     constexpr int OFF = (i - 4) * 1024;
     if constexpr ((GATHER_A || MODE == WGRAD) && SP != 0) {
-      if (SP == 1 || (last_partial && kt == nk - 1)) {
-        const int krow = k_lo + kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
+      if (SP == 1 || (t.last_partial && kt == t.nk - 1)) {
+        const int krow = t.k_lo + kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
         if constexpr (GATHER_A) {
           // the gathered operand repeats the expert's last row past its end: this one reads zeros there
-          dma16_lane_imm<OFF>(krow < k_hi ? sb_next + vob[i]
+          dma16_lane_imm<OFF>(krow < t.k_hi ? t.sb_next + t.vob[i]
                                           : reinterpret_cast<const char*>(g_zero_block) + (lane & 31) * 16 - OFF);
         } else {
           // ... and the other operand reads its last valid row there, so that zero times it is zero
-          dma16_lane_imm<OFF>(sb_next + vob[i] - (krow < k_hi ? 0 : static_cast<size_t>(krow - (k_hi - 1)) * a.N * 2));
+          dma16_lane_imm<OFF>(t.sb_next + t.vob[i] - (krow < t.k_hi ? 0 : static_cast<size_t>(krow - (t.k_hi - 1)) * a.N * 2));
         }
         return;
       }
     }
-    dma16_imm<OFF>(vob[i], sb_next);   // GATHER_B: rows past the expert's end were clamped when their tokens were fetched
+    dma16_imm<OFF>(t.vob[i], t.sb_next);   // GATHER_B: rows past the expert's end were clamped when their tokens were fetched
   };
-  auto a_end = [&](int kt) __attribute__((always_inline)) {
-    sa_next += a_step;
+  auto a_end = [&](TileState& t, int kt) __attribute__((always_inline)) {
+    t.sa_next += t.a_step;
     if constexpr (MODE == DGRAD_X) {
-      if (kt + 1 == nk_phase) sa_next = sa_phase1;
+      if (kt + 1 == t.nk_phase) t.sa_next = t.sa_phase1;
     }
   };
-  auto b_end = [&](int kt) __attribute__((always_inline)) {
-    sb_next += b_step;
+  auto b_end = [&](TileState& t, int kt) __attribute__((always_inline)) {
+    t.sb_next += t.b_step;
     if constexpr (MODE == DGRAD_X) {
-      if (kt + 1 == nk_phase) sb_next = sb_phase1;
+      if (kt + 1 == t.nk_phase) t.sb_next = t.sb_phase1;
     }
   };
   // GATHER_A/B: the tokens of the lane's eight reduction rows of step kt (rows 2 (8 w + i) + lane / 32), loaded
@@ -485,18 +519,18 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   // row: the other operand is zero there), and their turn into lane offsets of the gathered operand's loads.
   // The loads are asynchronous: apply_tok may only run after a wait that covers them.
   const uint32_t tok_voff = static_cast<uint32_t>(((wave * 8) * 2 + (lane >> 5)) * 4);   // row of load 0; load i: + 2 i rows
-  auto fetch_tok = [&](int kt, int (&tk)[8]) __attribute__((always_inline)) {
+  auto fetch_tok = [&](TileState& t, int kt, int (&tk)[8]) __attribute__((always_inline)) {
     if constexpr (GATHER_B || GATHER_A) {
-      if (k_lo + (kt + 1) * BK > k_hi) {
-        const int last = k_hi - k_lo - 1;
+      if (t.k_lo + (kt + 1) * BK > t.k_hi) {
+        const int last = t.k_hi - t.k_lo - 1;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           int r = kt * BK + (wave * 8 + i) * 2 + (lane >> 5);
           if (r > last) r = last;
-          tk[i] = load_i32<0>(static_cast<uint32_t>(r) * 4u, row_tok);
+          tk[i] = load_i32<0>(static_cast<uint32_t>(r) * 4u, t.row_tok);
         }
       } else {
-        const int32_t* base = row_tok + static_cast<size_t>(kt) * BK;
+        const int32_t* base = t.row_tok + static_cast<size_t>(kt) * BK;
         tk[0] = load_i32<0>(tok_voff, base);
         tk[1] = load_i32<8>(tok_voff, base);
         tk[2] = load_i32<16>(tok_voff, base);
@@ -508,14 +542,14 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
       }
     }
   };
-  auto apply_tok = [&](int (&tk)[8]) __attribute__((always_inline)) {
+  auto apply_tok = [&](TileState& t, int (&tk)[8]) __attribute__((always_inline)) {
     if constexpr (GATHER_B || GATHER_A) {
       const uint32_t row_bytes = static_cast<uint32_t>(GATHER_B ? a.N : a.M) * 2u;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         asm volatile("" : "+v"(tk[i]));   // not before the wait that precedes this call
-        const uint32_t off = static_cast<uint32_t>(tk[i]) * row_bytes + vcb[i];
-        if constexpr (GATHER_B) vob[i] = off; else voa[i] = off;
+        const uint32_t off = static_cast<uint32_t>(tk[i]) * row_bytes + t.vcb[i];
+        if constexpr (GATHER_B) t.vob[i] = off; else t.voa[i] = off;
       }
     }
   };
@@ -555,12 +589,6 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
 
   // ---------------- main loop ----------------------------------------------------
   f32x4_t acc[8][8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
   // two fragment sets: one feeds the MFMAs while the other is being read
   KnFrag fa[2][8], fb[2][8];
@@ -628,7 +656,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   // Step kt at ring phase P.  KIND 2: a step that loads A(kt+2) (before its barrier, into B(kt-1)'s old slot) and
   // B(kt+2) (behind it, into A(kt)'s slot); KIND 1: the second to last step (nothing left to load); KIND 0: the
   // last step (no barrier, no next fragments).
-  auto step = [&](int kt, auto phase_tag, auto kind_tag, auto nv_tag, auto sp_tag) __attribute__((always_inline)) {
+  auto step = [&](TileState& t, int kt, auto phase_tag, auto kind_tag, auto nv_tag, auto sp_tag) __attribute__((always_inline)) {
     constexpr int P = decltype(phase_tag)::value, KIND = decltype(kind_tag)::value, NV = decltype(nv_tag)::value;
     using SA = IC<slot_of_a(P)>;
     using SB = IC<slot_of_b(P)>;
@@ -639,92 +667,96 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     if constexpr (KIND == 2 && GATHER_A) {
       // the tokens of A(kt+2) were fetched a step ago and are covered by that step's wait; those of A(kt+3)
       // are requested before the loads of A(kt+2), the only ones this step's wait leaves in flight
-      apply_tok(tokn);
-      if (kt + 3 < nk) fetch_tok(kt + 3, tokn);
+      apply_tok(t, t.tokn);
+      if (kt + 3 < t.nk) fetch_tok(t, kt + 3, t.tokn);
     }
     sub_step(IC<0>{}, nv_tag, IC<NREADS>{},
              [&](auto op) __attribute__((always_inline)) { read_op(SA{}, SB{}, IC<1>{}, IC<1>{}, nv_tag, op); },
              IC<KIND == 2 ? 1 : 0>{},
              [&]() __attribute__((always_inline)) { set_m0<LA * TILE_BYTES>(lds_fill); },
-             [&](auto i) __attribute__((always_inline)) { a_part(kt + 2, i, sp_tag); });
-    if constexpr (KIND == 2) a_end(kt + 2);
+             [&](auto i) __attribute__((always_inline)) { a_part(t, kt + 2, i, sp_tag); });
+    if constexpr (KIND == 2) a_end(t, kt + 2);
     lds_wait<0>();
     if constexpr (KIND >= 1) {
       if constexpr (KIND == 2) wait_vm<8>(); else wait_vm<0>();   // this wave's loads of A(kt+2) may stay in flight
       wg_barrier();
     }
-    if constexpr (KIND == 2 && GATHER_B) apply_tok(tokn);   // fetched a step ago, older than the loads of A(kt+2)
+    if constexpr (KIND == 2 && GATHER_B) apply_tok(t, t.tokn);   // fetched a step ago, older than the loads of A(kt+2)
     sub_step(IC<1>{}, nv_tag, IC<KIND >= 1 ? NREADS : 0>{},
              [&](auto op) __attribute__((always_inline)) { read_op(NA{}, NB{}, IC<0>{}, IC<0>{}, nv_tag, op); },
              IC<KIND == 2 ? 1 : 0>{},
              [&]() __attribute__((always_inline)) { set_m0<SA::value * TILE_BYTES>(lds_fill); },
-             [&](auto i) __attribute__((always_inline)) { b_part(kt + 2, i, sp_tag); });
+             [&](auto i) __attribute__((always_inline)) { b_part(t, kt + 2, i, sp_tag); });
     if constexpr (KIND == 2) {
-      b_end(kt + 2);
+      b_end(t, kt + 2);
       if constexpr (GATHER_B) {
         // a whole step ahead of their use; the next step's wait covers them (they are older than its A loads)
-        if (kt + 3 < nk) fetch_tok(kt + 3, tokn);
+        if (kt + 3 < t.nk) fetch_tok(t, kt + 3, t.tokn);
       }
     }
     lds_wait<0>();
   };
 
-  // The last three steps of a tile are copies of their own: the last step that loads (it loads the tile's last
-  // step, the one that may be partial in a weight gradient: SP 1), the step that only awaits, and the last one.
-  // The tile enters the ring at the phase p0 that puts these three on phases 0, 1 and 2, so that the steps
-  // before them end on a round of the five phases.
-  const int nmain = nk >= 3 ? nk - 3 : 0;
-  const int p0 = nk >= 3 ? (NSLOT - nmain % NSLOT) % NSLOT : (nk == 2 ? 1 : 2);
-  auto main_loop = [&](auto nv_tag) __attribute__((always_inline)) {
-    if (nk <= 0) return;
-    // ---- first loads: steps 0 and 1 into the slots of phases p0 and p0 + 1
+  // The first loads of a tile: steps 0 and 1 into the slots of phases p0 and p0 + 1; awaited when the tile's
+  // main loop starts.  (Requesting them before the epilogue of the tile before, with the epilogue staged in the
+  // one slot they leave free, was built and measured: the loads' latency disappears, 3.5 us per tile, and the
+  // step takes as long as before, because the chip is power-limited and the main loops slow down by what the
+  // idle phases no longer give back.)
+  auto first_loads = [&](TileState& t) __attribute__((always_inline)) {
+    if (t.nk <= 0) return;
+    const int p0 = t.p0;
     const int p1 = (p0 + 1) % NSLOT;
     const uint32_t m_a0 = lds_fill + ((2 * p0) % NSLOT) * TILE_BYTES, m_b0 = lds_fill + ((2 * p0 + 1) % NSLOT) * TILE_BYTES;
     const uint32_t m_a1 = lds_fill + ((2 * p1) % NSLOT) * TILE_BYTES, m_b1 = lds_fill + ((2 * p1 + 1) % NSLOT) * TILE_BYTES;
     auto a_unit = [&](int kt, uint32_t m) __attribute__((always_inline)) {
       set_m0_rt(m);
       asm volatile("s_nop 0" ::: "memory");
-      static_for<8>([&](auto i) { a_part(kt, i, IC<2>{}); });
-      a_end(kt);
+      static_for<8>([&](auto i) { a_part(t, kt, i, IC<2>{}); });
+      a_end(t, kt);
     };
     auto b_unit = [&](int kt, uint32_t m) __attribute__((always_inline)) {
       set_m0_rt(m);
       asm volatile("s_nop 0" ::: "memory");
-      static_for<8>([&](auto i) { b_part(kt, i, IC<2>{}); });
-      b_end(kt);
+      static_for<8>([&](auto i) { b_part(t, kt, i, IC<2>{}); });
+      b_end(t, kt);
     };
     if constexpr (GATHER_B) {
       // the tokens of steps 0 and 1 are requested first and are older than the loads of A(0), A(1): one wait for both
-      fetch_tok(0, tokn);
-      if (nk > 1) fetch_tok(1, tokn1);
+      fetch_tok(t, 0, t.tokn);
+      if (t.nk > 1) fetch_tok(t, 1, t.tokn1);
       a_unit(0, m_a0);
-      if (nk > 1) { a_unit(1, m_a1); wait_vm<16>(); } else { wait_vm<8>(); }
-      apply_tok(tokn);
+      if (t.nk > 1) { a_unit(1, m_a1); wait_vm<16>(); } else { wait_vm<8>(); }
+      apply_tok(t, t.tokn);
       b_unit(0, m_b0);
-      if (nk > 1) { apply_tok(tokn1); b_unit(1, m_b1); }
-      if (nk > 1) wait_vm<8>(); else wait_vm<0>();     // only B(1) may stay in flight
+      if (t.nk > 1) { apply_tok(t, t.tokn1); b_unit(1, m_b1); }
     } else if constexpr (GATHER_A) {
-      fetch_tok(0, tokn);
-      if (nk > 1) fetch_tok(1, tokn1);
+      fetch_tok(t, 0, t.tokn);
+      if (t.nk > 1) fetch_tok(t, 1, t.tokn1);
       b_unit(0, m_b0);
-      if (nk > 1) { b_unit(1, m_b1); wait_vm<16>(); } else { wait_vm<8>(); }
-      apply_tok(tokn);
+      if (t.nk > 1) { b_unit(1, m_b1); wait_vm<16>(); } else { wait_vm<8>(); }
+      apply_tok(t, t.tokn);
       a_unit(0, m_a0);
-      if (nk > 1) {
-        apply_tok(tokn1);
-        if (nk > 2) fetch_tok(2, tokn);   // applied at the start of step 0: older than the loads of A(1)
+      if (t.nk > 1) {
+        apply_tok(t, t.tokn1);
+        if (t.nk > 2) fetch_tok(t, 2, t.tokn);   // applied at the start of step 0: older than the loads of A(1)
         a_unit(1, m_a1);
       }
-      if (nk > 1) wait_vm<8>(); else wait_vm<0>();     // only A(1) may stay in flight
     } else {
       b_unit(0, m_b0);
       a_unit(0, m_a0);
-      if (nk > 1) { b_unit(1, m_b1); a_unit(1, m_a1); wait_vm<16>(); } else { wait_vm<0>(); }
+      if (t.nk > 1) { b_unit(1, m_b1); a_unit(1, m_a1); }
     }
-    wg_barrier();
     if constexpr (GATHER_B) {
-      if (nk > 2) fetch_tok(2, tokn);   // applied behind step 0's barrier, whose wait covers it
+      if (t.nk > 2) fetch_tok(t, 2, t.tokn);   // applied behind step 0's barrier, whose wait covers it
     }
+  };
+  auto main_loop = [&](TileState& t, auto nv_tag) __attribute__((always_inline)) {
+    if (t.nk <= 0) return;
+    const int p0 = t.p0, nmain = t.nmain;
+    // The tile's first loads are awaited; those of step 1 may stay in flight (the stores of the epilogue before
+    // are older than all of them, and loads complete in order among themselves).
+    if (GATHER_A || GATHER_B || t.nk <= 1) wait_vm<0>(); else wait_vm<16>();
+    wg_barrier();
     // ---- first fragments: sub-step 0 of step 0, from the slots of phase p0
     constexpr int NV = decltype(nv_tag)::value;
     constexpr int NREADS = NV == 0 ? 0 : 2 * NV * A_OPS_PER_BLK + 8 * B_OPS_PER_BLK;
@@ -745,190 +777,191 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     int kt = 0;
     int skip = p0;
     while (kt < nmain) {
-      if (skip <= 0) { step(kt, IC<0>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
-      if (skip <= 1) { step(kt, IC<1>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
-      if (skip <= 2) { step(kt, IC<2>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
-      if (skip <= 3) { step(kt, IC<3>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
-      step(kt, IC<4>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt;
+      if (skip <= 0) { step(t, kt, IC<0>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
+      if (skip <= 1) { step(t, kt, IC<1>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
+      if (skip <= 2) { step(t, kt, IC<2>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
+      if (skip <= 3) { step(t, kt, IC<3>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt; }
+      step(t, kt, IC<4>{}, IC<2>{}, nv_tag, IC<0>{}); ++kt;
       skip = 0;
     }
     // ---- the last three steps
-    if (nk >= 3) step(nk - 3, IC<0>{}, IC<2>{}, nv_tag, IC<is_wgrad(MODE) ? 1 : 0>{});
-    if (nk >= 2) step(nk - 2, IC<1>{}, IC<1>{}, nv_tag, IC<0>{});
-    step(nk - 1, IC<2>{}, IC<0>{}, nv_tag, IC<0>{});
+    if (t.nk >= 3) step(t, t.nk - 3, IC<0>{}, IC<2>{}, nv_tag, IC<is_wgrad(MODE) ? 1 : 0>{});
+    if (t.nk >= 2) step(t, t.nk - 2, IC<1>{}, IC<1>{}, nv_tag, IC<0>{});
+    step(t, t.nk - 1, IC<2>{}, IC<0>{}, nv_tag, IC<0>{});
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs have written before the accumulators are read
   };
   // one copy of the loop per number of live 32-row groups: a wave whose 128 rows all lie past the
   // expert's end only keeps the loads and barriers going
-  if constexpr (is_wgrad(MODE)) {
-    main_loop(IC<4>{});
-  } else {
-    switch (nv) {
-      case 4: main_loop(IC<4>{}); break;
-      case 3: main_loop(IC<3>{}); break;
-      case 2: main_loop(IC<2>{}); break;
-      case 1: main_loop(IC<1>{}); break;
-      default: main_loop(IC<0>{}); break;
+  auto run_main = [&](TileState& t) __attribute__((always_inline)) {
+    if constexpr (is_wgrad(MODE)) {
+      main_loop(t, IC<4>{});
+    } else {
+      switch (t.nv) {
+        case 4: main_loop(t, IC<4>{}); break;
+        case 3: main_loop(t, IC<3>{}); break;
+        case 2: main_loop(t, IC<2>{}); break;
+        case 1: main_loop(t, IC<1>{}); break;
+        default: main_loop(t, IC<0>{}); break;
+      }
     }
-  }
-  const ArgPtr ae = reload_args<ARG>();     // the epilogue reads its arguments afresh
-  wg_barrier();                             // every wave is done with the operand tiles
-
+  };
   // ---------------- epilogue -----------------------------------------------------
-  // acc[i][j][c] is the wave's element (row, col) with row = 16 i + (lane & 15) and
-  // col = 16 j + 4 (lane / 16) + c.  The wave stages bf16 rows of 256 bytes in its own
-  // 32 KB of LDS (16-byte pieces swizzled by row & 15) and stores 16 bytes per lane.
+  // acc[i][j][c] is the wave's element (row, col) with row = 16 i + (lane & 15) and col = 16 j + 4 (lane / 16) + c.
+  // The wave stages bf16 rows of 256 bytes in 8 KB of LDS of its own (its share of ring slot 0; 16-byte pieces
+  // swizzled by the row), a few rows at a time, and stores 16 bytes per lane in full row segments.
   // The accumulators are read out of the accumulation registers at the point of use, by hand: left to the
   // compiler they are moved (and spilled) in bulk where the copies of the main loop join.
   auto accq = [&](auto i_tag, auto j_tag) __attribute__((always_inline)) -> f32x4_t {
     constexpr int i = decltype(i_tag)::value, j = decltype(j_tag)::value;
     f32x4_t v;
-    float t;
+    float x;
     const float c0 = acc[i][j][0], c1 = acc[i][j][1], c2 = acc[i][j][2], c3 = acc[i][j][3];
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(c0));  v[0] = t;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(c1));  v[1] = t;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(c2));  v[2] = t;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(c3));  v[3] = t;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(c0));  v[0] = x;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(c1));  v[1] = x;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(c2));  v[2] = x;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(c3));  v[3] = x;
     return v;
   };
-  const int l16 = lane & 15, lq = lane >> 4;
-  const int grow0 = m0 + wm * 128;                                     // wave's first output row
-  const int gcol0 = n0 + wn * (MODE == GATE_UP ? 64 : 128);            // wave's first output column
-  char* stage = lds + wave * WAVE_STAGE_BYTES;
-  // address of the 8 bytes of columns 4 lq .. + 3 of 16-column block `blk` in staged row `row`
-  auto quad_addr = [&](int row, int blk) __attribute__((always_inline)) -> char* {
-    return stage + row * 256 + (((2 * blk + (lq >> 1)) ^ (row & 15)) << 4) + (lq & 1) * 8;
-  };
-  auto put_quad = [&](int row, int blk, const f32x4_t& v) __attribute__((always_inline)) {
-    u32x2 o;
-    o.x = pack_bf16(v[0], v[1]);
-    o.y = pack_bf16(v[2], v[3]);
-    *reinterpret_cast<u32x2*>(quad_addr(row, blk)) = o;
-  };
-  // Stores ROWS staged rows of RB bytes (pieces swizzled by row & (RB / 16 - 1); region at `base`) to out rows
-  // first_row .. (row stride ld): each row's PIECES 16-byte pieces from piece PIECE0 on go to columns
-  // col0 + 8 piece.  Eight passes at a time: their LDS reads are issued together, then their stores (one wave
-  // per SIMD: nothing else would cover the latency of a read-then-store chain).
-  auto flush = [&](const char* base, auto rb_tag, uint16_t* out, size_t ld, int first_row, auto rows_tag, auto piece0_tag,
-                   auto pieces_tag, int col0, int ncols) __attribute__((always_inline)) {
-    constexpr int RB = decltype(rb_tag)::value, ROWS = decltype(rows_tag)::value;
-    constexpr int PIECE0 = decltype(piece0_tag)::value, PIECES = decltype(pieces_tag)::value;
-    constexpr int RPP = 64 / PIECES, PASSES = ROWS / RPP, SWZ = RB / 16 - 1;
-    const int prow = lane / PIECES, piece = lane % PIECES;
-    const int gc = col0 + piece * 8;
-    static_for<(PASSES + 7) / 8>([&](auto b_tag) {
-      constexpr int P0 = decltype(b_tag)::value * 8;
-      constexpr int NB = PASSES - P0 < 8 ? PASSES - P0 : 8;
-      u32x4 v[NB];
+  // GATE_UP with gate weights folded into h: the weights of the lane's eight rows, requested by hand right
+  // behind the main loop and awaited by hand where the epilogue first needs them.
+  float wv[8];
+  auto fetch_row_weights = [&](const TileState& t, const float* rw) __attribute__((always_inline)) {
 #pragma unroll
-      for (int k = 0; k < NB; ++k) {
-        const int row = (P0 + k) * RPP + prow;
-        v[k] = *reinterpret_cast<const u32x4*>(base + row * RB + (((PIECE0 + piece) ^ (row & SWZ)) << 4));
-      }
-#pragma unroll
-      for (int k = 0; k < NB; ++k) {
-        const int gr = first_row + (P0 + k) * RPP + prow;
-        if (gr < m_end && gc < ncols) *reinterpret_cast<u32x4*>(out + static_cast<size_t>(gr) * ld + gc) = v[k];
-      }
-    });
+    for (int i = 0; i < 8; ++i) {
+      int r = t.m0 + wm * 128 + i * 16 + (lane & 15);  if (r > t.m_end - 1) r = t.m_end - 1;
+      const float* ptr = rw + r;
+      asm volatile("global_load_dword %0, %1, off" : "=v"(wv[i]) : "v"(ptr) : "memory");
+    }
   };
 
-  if constexpr (MODE == GATE_UP) {
-    // blocks 0-3 are g, blocks 4-7 the same columns of u.
-    // gate weight of the lane's eight rows (1 unless the caller folds the weights into h)
-    float wv[8];
+  auto epilogue = [&](const TileState& t) __attribute__((always_inline)) {
+    const ArgPtr ae = reload_args<ARG>();     // the epilogue reads its arguments afresh
+    int tid = tid0;                           // laundered as in setup_tile
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
+    const int m0 = t.m0, m_end = t.m_end, n0 = t.n0;
+    const int grow0 = m0 + wm * 128;                                     // wave's first output row
+    const int gcol0 = n0 + wn * (MODE == GATE_UP ? 64 : 128);            // wave's first output column
+    char* stage = lds + wave * 8192;
+    // address of the 8 bytes of columns 4 lq .. + 3 of 16-column block `blk` in staged row `row`
+    auto quad_addr = [&](int row, int blk) __attribute__((always_inline)) -> char* {
+      return stage + row * 256 + (((2 * blk + (lq >> 1)) ^ (row & 15)) << 4) + (lq & 1) * 8;
+    };
+    auto put_quad = [&](int row, int blk, const f32x4_t& v) __attribute__((always_inline)) {
+      u32x2 o;
+      o.x = pack_bf16(v[0], v[1]);
+      o.y = pack_bf16(v[2], v[3]);
+      *reinterpret_cast<u32x2*>(quad_addr(row, blk)) = o;
+    };
+    // Stores ROWS staged rows of RB bytes (pieces swizzled by row & (RB / 16 - 1); region at `base`) to out rows
+    // first_row .. (row stride ld): each row's PIECES 16-byte pieces from piece PIECE0 on go to columns
+    // col0 + 8 piece.  The LDS reads of up to eight passes are issued together, then their stores (one wave per
+    // SIMD: nothing else would cover the latency of a read-then-store chain).
+    auto flush = [&](const char* base, auto rb_tag, uint16_t* out, size_t ld, int first_row, auto rows_tag, auto piece0_tag,
+                     auto pieces_tag, int col0, int ncols) __attribute__((always_inline)) {
+      constexpr int RB = decltype(rb_tag)::value, ROWS = decltype(rows_tag)::value;
+      constexpr int PIECE0 = decltype(piece0_tag)::value, PIECES = decltype(pieces_tag)::value;
+      constexpr int RPP = 64 / PIECES, PASSES = ROWS / RPP, SWZ = RB / 16 - 1;
+      const int prow = lane / PIECES, piece = lane % PIECES;
+      const int gc = col0 + piece * 8;
+      static_for<(PASSES + 7) / 8>([&](auto b_tag) {
+        constexpr int P0 = decltype(b_tag)::value * 8;
+        constexpr int NB = PASSES - P0 < 8 ? PASSES - P0 : 8;
+        u32x4 v[NB];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) wv[i] = 1.f;
-    if (ae->row_weight != nullptr) {
-      const float* rw = ae->row_weight;
+        for (int k = 0; k < NB; ++k) {
+          const int row = (P0 + k) * RPP + prow;
+          v[k] = *reinterpret_cast<const u32x4*>(base + row * RB + (((PIECE0 + piece) ^ (row & SWZ)) << 4));
+        }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        int r = grow0 + i * 16 + l16;  if (r > m_end - 1) r = m_end - 1;
-        wv[i] = rw[r];
+        for (int k = 0; k < NB; ++k) {
+          const int gr = first_row + (P0 + k) * RPP + prow;
+          if (gr < m_end && gc < ncols) *reinterpret_cast<u32x4*>(out + static_cast<size_t>(gr) * ld + gc) = v[k];
+        }
+      });
+    };
+
+    if constexpr (MODE == GATE_UP) {
+      // blocks 0-3 are g, blocks 4-7 the same columns of u.  Eight parts of 16 rows: g in pieces 0-7 and u in
+      // pieces 8-15 of 256-byte rows, h = silu(g) * u (from the fp32 accumulators, times the row's gate weight if
+      // the caller folds the weights into h) in 128-byte rows behind them.
+      const bool weighted = ae->row_weight != nullptr;
+      if (weighted) {
+        wait_vm<0>();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(wv[i]));
       }
-    }
-    // two halves of 64 rows: g in pieces 0-7 and u in pieces 8-15 of 256-byte rows, h = silu(g) * u (from the fp32
-    // accumulators) in 128-byte rows behind them; the stores of a half are in flight while the next is computed
-    char* hstage = stage + 64 * 256;
-    static_for<2>([&](auto hh_tag) {
-      constexpr int HH = decltype(hh_tag)::value;
-      constexpr int hh = HH;
-      static_for<4>([&](auto i2_tag) {
-        constexpr int i2 = decltype(i2_tag)::value;
-        const int row = i2 * 16 + l16;
+      char* hstage = stage + 16 * 256;
+      static_for<8>([&](auto i_tag) {
+        constexpr int i = decltype(i_tag)::value;
+        const int row = l16;
+        const float w = weighted ? wv[i] : 1.f;
         static_for<4>([&](auto j_tag) {
           constexpr int j = decltype(j_tag)::value;
-          const f32x4_t gv = accq(IC<HH * 4 + i2>{}, IC<j>{});
-          const f32x4_t uv = accq(IC<HH * 4 + i2>{}, IC<j + 4>{});
+          const f32x4_t gv = accq(i_tag, IC<j>{});
+          const f32x4_t uv = accq(i_tag, IC<j + 4>{});
           put_quad(row, j, gv);
           put_quad(row, j + 4, uv);
           u32x2 o;
           float h[4];
 #pragma unroll
-          for (int c = 0; c < 4; ++c) h[c] = silu_f(gv[c]) * uv[c] * wv[HH * 4 + i2];
+          for (int c = 0; c < 4; ++c) h[c] = silu_f(gv[c]) * uv[c] * w;
           o.x = pack_bf16(h[0], h[1]);
           o.y = pack_bf16(h[2], h[3]);
           *reinterpret_cast<u32x2*>(hstage + row * 128 + (((2 * j + (lq >> 1)) ^ (row & 7)) << 4) + (lq & 1) * 8) = o;
         });
+        __builtin_amdgcn_wave_barrier();
+        flush(stage, IC<256>{}, ae->O0, ae->N, grow0 + i * 16, IC<16>{}, IC<0>{}, IC<8>{}, gcol0, ae->N);
+        flush(stage, IC<256>{}, ae->O1, ae->N, grow0 + i * 16, IC<16>{}, IC<8>{}, IC<8>{}, gcol0, ae->N);
+        flush(hstage, IC<128>{}, ae->O2, ae->N, grow0 + i * 16, IC<16>{}, IC<0>{}, IC<8>{}, gcol0, ae->N);
+        __builtin_amdgcn_wave_barrier();
       });
-      __builtin_amdgcn_wave_barrier();
-      flush(stage, IC<256>{}, ae->O0, ae->N, grow0 + hh * 64, IC<64>{}, IC<0>{}, IC<8>{}, gcol0, ae->N);
-      flush(stage, IC<256>{}, ae->O1, ae->N, grow0 + hh * 64, IC<64>{}, IC<8>{}, IC<8>{}, gcol0, ae->N);
-      flush(hstage, IC<128>{}, ae->O2, ae->N, grow0 + hh * 64, IC<64>{}, IC<0>{}, IC<8>{}, gcol0, ae->N);
-      __builtin_amdgcn_wave_barrier();
-    });
-  } else if constexpr (is_dgrad_h(MODE)) {
-    // in four parts of 32 rows: g rows at stage[0, 8K), u rows at stage[8K, 16K).  The g/u rows of a part are
-    // requested before the previous part is processed, so their latency stays hidden.
-    // DGRAD_H_GATE: the accumulators hold dh0 = dout[token] . Wd; the row's gate weight w turns them into
-    // dh = w dh0, and the sum over a 64-column strip of dh0 * silu(g) * u is the strip's share of the
-    // gradient of w (a lane holds 16 of the strip's columns of its row, lanes ^ 16, ^ 32 the others).
-    constexpr bool GATE = (MODE == DGRAD_H_GATE);
-    constexpr int GU_PASSES = 8;   // 32 rows x 16 pieces = 512 pieces of 16 bytes, 64 per pass
-    u32x4 pg[GU_PASSES], pu[GU_PASSES];
-    auto gu_load = [&](int part) __attribute__((always_inline)) {
-      const int ncol = ae->N;
-      const uint16_t* gsrc = ae->G;
-      const uint16_t* usrc = ae->U;
+    } else if constexpr (is_dgrad_h(MODE)) {
+      // in eight parts of 16 rows: g rows at stage[0, 4K), u rows at stage[4K, 8K).  The g/u rows of a part are
+      // requested before the previous part is processed, so their latency stays hidden.
+      // DGRAD_H_GATE: the accumulators hold dh0 = dout[token] . Wd; the row's gate weight w turns them into
+      // dh = w dh0, and the sum over a 64-column strip of dh0 * silu(g) * u is the strip's share of the
+      // gradient of w (a lane holds 16 of the strip's columns of its row, lanes ^ 16, ^ 32 the others).
+      constexpr bool GATE = (MODE == DGRAD_H_GATE);
+      constexpr int GU_PASSES = 4;   // 16 rows x 16 pieces = 256 pieces of 16 bytes, 64 per pass
+      u32x4 pg[GU_PASSES], pu[GU_PASSES];
+      auto gu_load = [&](int part) __attribute__((always_inline)) {
+        const int ncol = ae->N;
+        const uint16_t* gsrc = ae->G;
+        const uint16_t* usrc = ae->U;
 #pragma unroll
-      for (int p = 0; p < GU_PASSES; ++p) {
-        const int row = p * 4 + (lane >> 4), piece = lane & 15;
-        int gr = grow0 + part * 32 + row;  if (gr > m_end - 1) gr = m_end - 1;
-        int gc = gcol0 + piece * 8;  if (gc > ncol - 8) gc = ncol - 8;
-        const size_t o = static_cast<size_t>(gr) * ncol + gc;
-        pg[p] = *reinterpret_cast<const u32x4*>(gsrc + o);
-        pu[p] = *reinterpret_cast<const u32x4*>(usrc + o);
-      }
-    };
-    gu_load(0);
-    constexpr int UOFF = 8192;
-    static_for<4>([&](auto part_tag) {
-      constexpr int part = decltype(part_tag)::value;
-      const int first = grow0 + part * 32;
-      float wrow[2] = {1.f, 1.f}, dsum[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
-      if constexpr (GATE) {
-        const float* rw = ae->row_weight;
-#pragma unroll
-        for (int i2 = 0; i2 < 2; ++i2) {
-          int r = first + i2 * 16 + l16;  if (r > m_end - 1) r = m_end - 1;
-          wrow[i2] = rw[r];
+        for (int p = 0; p < GU_PASSES; ++p) {
+          const int row = p * 4 + (lane >> 4), piece = lane & 15;
+          int gr = grow0 + part * 16 + row;  if (gr > m_end - 1) gr = m_end - 1;
+          int gc = gcol0 + piece * 8;  if (gc > ncol - 8) gc = ncol - 8;
+          const size_t o = static_cast<size_t>(gr) * ncol + gc;
+          pg[p] = *reinterpret_cast<const u32x4*>(gsrc + o);
+          pu[p] = *reinterpret_cast<const u32x4*>(usrc + o);
         }
-      }
+      };
+      gu_load(0);
+      constexpr int UOFF = 4096;
+      static_for<8>([&](auto part_tag) {
+        constexpr int part = decltype(part_tag)::value;
+        const int first = grow0 + part * 16;
+        float wrow = 1.f, dsum[2] = {0.f, 0.f};
+        if constexpr (GATE) {
+          int r = first + l16;  if (r > m_end - 1) r = m_end - 1;
+          wrow = ae->row_weight[r];
+        }
 #pragma unroll
-      for (int p = 0; p < GU_PASSES; ++p) {
-        const int row = p * 4 + (lane >> 4), piece = lane & 15;
-        const int so = row * 256 + ((piece ^ (row & 15)) << 4);
-        *reinterpret_cast<u32x4*>(stage + so) = pg[p];
-        *reinterpret_cast<u32x4*>(stage + UOFF + so) = pu[p];
-      }
-      if (part + 1 < 4) gu_load(part + 1);
-      __builtin_amdgcn_wave_barrier();
-      static_for<2>([&](auto i2_tag) {
-        constexpr int i2 = decltype(i2_tag)::value;
+        for (int p = 0; p < GU_PASSES; ++p) {
+          const int row = p * 4 + (lane >> 4), piece = lane & 15;
+          const int so = row * 256 + ((piece ^ (row & 15)) << 4);
+          *reinterpret_cast<u32x4*>(stage + so) = pg[p];
+          *reinterpret_cast<u32x4*>(stage + UOFF + so) = pu[p];
+        }
+        if (part + 1 < 8) gu_load(part + 1);
+        __builtin_amdgcn_wave_barrier();
         static_for<8>([&](auto j_tag) {
           constexpr int j = decltype(j_tag)::value;
-          const int row = i2 * 16 + l16;
-          const f32x4_t dhv = accq(IC<part * 2 + i2>{}, IC<j>{});
+          const int row = l16;
+          const f32x4_t dhv = accq(part_tag, j_tag);
           char* ga = quad_addr(row, j);
           char* ua = ga + UOFF;
           const u32x2 gq = *reinterpret_cast<const u32x2*>(ga);
@@ -943,14 +976,14 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
               const float dh0 = dhv[c];
               const float sl = g4[c] * sg;                 // silu(g)
               const float t0 = dh0 * u4[c];
-              dsum[i2][j >> 2] = __builtin_fmaf(t0, sl, dsum[i2][j >> 2]);
-              du[c] = (dh0 * wrow[i2]) * sl;
-              dg[c] = (t0 * wrow[i2]) * (sg * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f));
+              dsum[j >> 2] = __builtin_fmaf(t0, sl, dsum[j >> 2]);
+              du[c] = (dh0 * wrow) * sl;
+              dg[c] = (t0 * wrow) * (sg * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f));
             } else {
               const float dh = dhv[c];
-              const float t = dh * sg;                     // shared by both derivatives
-              du[c] = t * g4[c];
-              dg[c] = (t * u4[c]) * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f);
+              const float x = dh * sg;                     // shared by both derivatives
+              du[c] = x * g4[c];
+              dg[c] = (x * u4[c]) * __builtin_fmaf(g4[c], 1.0f - sg, 1.0f);
             }
           }
           u32x2 o;
@@ -959,41 +992,69 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
           o.x = pack_bf16(du[0], du[1]);  o.y = pack_bf16(du[2], du[3]);
           *reinterpret_cast<u32x2*>(ua) = o;
         });
-      });
-      if constexpr (GATE) {
-        const int strips = ae->N >> 6;
+        if constexpr (GATE) {
+          const int strips = ae->N >> 6;
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          if (gcol0 + s2 * 64 < ae->N) {     // a strip past the last column holds repeated columns: no share
-            float* part_out = ae->dgate_part + ((gcol0 >> 6) + s2);
-#pragma unroll
-            for (int i2 = 0; i2 < 2; ++i2) {
-              float t = dsum[i2][s2];
-              t += __shfl_xor(t, 16, 64);
-              t += __shfl_xor(t, 32, 64);
-              const int r = first + i2 * 16 + l16;
-              if (lq == 0 && r < m_end) part_out[static_cast<size_t>(r) * strips] = t;
+          for (int s2 = 0; s2 < 2; ++s2) {
+            if (gcol0 + s2 * 64 < ae->N) {     // a strip past the last column holds repeated columns: no share
+              float* part_out = ae->dgate_part + ((gcol0 >> 6) + s2);
+              float x = dsum[s2];
+              x += __shfl_xor(x, 16, 64);
+              x += __shfl_xor(x, 32, 64);
+              const int r = first + l16;
+              if (lq == 0 && r < m_end) part_out[static_cast<size_t>(r) * strips] = x;
             }
           }
         }
+        __builtin_amdgcn_wave_barrier();
+        flush(stage, IC<256>{}, ae->O0, ae->N, first, IC<16>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
+        flush(stage + UOFF, IC<256>{}, ae->O1, ae->N, first, IC<16>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
+        __builtin_amdgcn_wave_barrier();
+      });
+    } else {
+      uint16_t* out = t.second ? ae->O1 : ae->O0;
+      if constexpr (is_wgrad(MODE)) out += static_cast<size_t>(t.e) * ae->M * ae->N;
+      // four parts of 32 rows
+      static_for<4>([&](auto part_tag) {
+        constexpr int part = decltype(part_tag)::value;
+        static_for<2>([&](auto i2_tag) {
+          constexpr int i2 = decltype(i2_tag)::value;
+          static_for<8>([&](auto j_tag) { put_quad(i2 * 16 + l16, decltype(j_tag)::value, accq(IC<part * 2 + i2>{}, j_tag)); });
+        });
+        __builtin_amdgcn_wave_barrier();
+        flush(stage, IC<256>{}, out, ae->N, grow0 + part * 32, IC<32>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
+        __builtin_amdgcn_wave_barrier();
+      });
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's staging reads are done
+  };
+
+  // ---------------- the tile loop ------------------------------------------------
+  int tile = first_tile;
+  if (tile < total) {
+    TileState cur;
+    setup_tile(tile, cur);
+    first_loads(cur);
+    for (;;) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+      run_main(cur);
+      wg_barrier();                             // every wave is done with the operand tiles
+      if constexpr (MODE == GATE_UP) {
+        if (a.row_weight != nullptr) fetch_row_weights(cur, a.row_weight);
       }
-      __builtin_amdgcn_wave_barrier();
-      flush(stage, IC<256>{}, ae->O0, ae->N, first, IC<32>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
-      flush(stage + UOFF, IC<256>{}, ae->O1, ae->N, first, IC<32>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
-      __builtin_amdgcn_wave_barrier();
-    });
-  } else {
-    static_for<8>([&](auto i_tag) {
-      static_for<8>([&](auto j_tag) { put_quad(decltype(i_tag)::value * 16 + l16, decltype(j_tag)::value, accq(i_tag, j_tag)); });
-    });
-    __builtin_amdgcn_wave_barrier();
-    uint16_t* out = second ? ae->O1 : ae->O0;
-    if constexpr (is_wgrad(MODE)) out += static_cast<size_t>(e) * ae->M * ae->N;
-    flush(stage, IC<256>{}, out, ae->N, grow0, IC<128>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
+      epilogue(cur);
+      // a wave stages in, and loads into, its own 8 KB of a slot only: no barrier between epilogue and loads
+      tile += gridDim.x;
+      if (tile >= total) break;
+      setup_tile(tile, cur);
+      first_loads(cur);
+    }
   }
-  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's staging reads are done
-  wg_barrier();      // the staging area becomes operand stages again
-  }  // tile loop
   return tile - total;
 }
 
