@@ -56,18 +56,31 @@ def kernel_work(cfg, R):
 
 
 def measured_traffic(workload, kernel):
-    """HBM bytes per launch of `kernel` (fetch + write) from the committed rocprofv3 counter summary,
-    or None when there is none for this workload."""
-    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
-    key = kernel
+    """HBM bytes per launch of `kernel` (fetch + write) from the committed rocprofv3 counter summary, and the
+    file it came from; (None, None) when there is no summary for this workload.  The figure is NOT measured in
+    this run: counters need a run of their own under rocprofv3."""
+    rel = os.path.join("profiles", f"{workload}_hbm_traffic.txt")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             p = line.split()
-            if len(p) == 3 and p[0] == key:
-                return float(p[1]) + float(p[2])
+            if len(p) == 3 and p[0] == kernel:
+                return float(p[1]) + float(p[2]), rel
     except OSError:
         pass
-    return None
+    return None, None
+
+
+def gemm_algorithmic_bytes(cfg, R, kernel):
+    """Compulsory bf16 traffic of a grouped-GEMM launch (every operand read once, every result written once) in
+    the launch configuration bench.py times by default (rows gathered, gate weights folded into h)."""
+    Rd, Rf, Td = 2.0 * R * cfg.d, 2.0 * R * cfg.f, 2.0 * cfg.T * cfg.d
+    W1 = 2.0 * cfg.n_local * cfg.d * cfg.f
+    return {
+        "gemm_gate_up": Td + 2 * W1 + 3 * Rf,                       # x, Wg, Wu -> g, u, h
+        "gemm_down": Rf + W1 + Rd,                                  # h, Wd -> yp
+        "gemm_dgrad_h+wgrad_down": (Td + W1 + 2 * Rf + 2 * Rf) + (Td + Rf + W1),   # dout, Wd, g, u -> dg, du ; dout, hw -> dWd
+        "gemm_wgrad_gate_up+dgrad_x": (2 * Rf + Td + 2 * W1) + (2 * Rf + 2 * W1 + Rd),   # dg, du, x -> dWg, dWu ; dg, du, Wg, Wu -> dxp
+    }.get(kernel)
 
 
 def cpu_baseline(cfg, inp, sample_tokens):
@@ -107,6 +120,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="time the step as one HIP graph replay instead of a dozen stream launches "
                          "(measured: no faster, the launches already queue ahead of the GPU)")
+    ap.add_argument("--rotate", type=int, default=3,
+                    help="buffer sets (each larger than the 256 MB last-level cache share a kernel could keep) the "
+                         "HBM-bound row movers are rotated through for the cold-cache figure `gbs_cold`; 0 = skip")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -197,7 +213,15 @@ def main():
     else:
         roofline = {"kernel": dom, "bound": "hbm", "achieved": dk["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": dk["frac"], "traffic": None}
-    roofline["traffic"] = measured_traffic(cfg.name, dom)
+    traffic, traffic_file = measured_traffic(cfg.name, dom)
+    roofline["traffic"] = traffic
+    alg = gemm_algorithmic_bytes(cfg, R, dom) if fold else None
+    roofline["traffic_source"] = (None if traffic is None else
+                                  f"{traffic_file}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary committed with the repository, "
+                                  "NOT measured in this run (it may predate the library this run loaded)")
+    if traffic is not None and alg:
+        roofline["algorithmic_bytes"] = alg
+        roofline["traffic_over_algorithmic"] = round(traffic / alg, 3)
     gemm_us = sum(v["avg_us"] * v["launches_per_step"] for n, v in kernels.items() if n.startswith("gemm_"))
     gemm_tflops = 18.0 * R * cfg.d * cfg.f / (gemm_us * 1e-6) / 1e12 if gemm_us > 0 else 0.0
 
@@ -218,6 +242,42 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    # ---- cold-cache rate of the HBM-bound row movers: each kernel alone, its large operand rotated through
+    #      `--rotate` buffer sets so that no launch finds its rows in the 256 MB last-level cache
+    if args.rotate >= 2:
+        nset = args.rotate
+        rows = [torch.randn(R, cfg.d, device=dev, dtype=torch.bfloat16) for _ in range(nset)]
+        outs = [torch.empty(cfg.T, cfg.d, device=dev, dtype=torch.bfloat16) for _ in range(nset)]
+        reps = max(4 * nset, 12)
+        cold_calls = {"combine" if fold else "permute_bwd": lambda i: B.moe_unpermute_sum(rows[i], buf.slot_row, outs[i])}
+        if fold:
+            cold_calls["permute_bwd"] = lambda i: B.moe_permute_bwd(rows[i], buf.slot_row, outs[i])
+        else:
+            cold_calls["combine"] = lambda i: B.moe_unpermute_combine(rows[i], buf.slot_row, buf.topk_w, outs[i])
+            dyps = [torch.empty_like(r) for r in rows[:2]]
+            cold_calls["combine_bwd"] = lambda i: B.moe_unpermute_combine_bwd(outs[i], rows[i], buf.slot_row, buf.topk_w,
+                                                                              dyps[i % 2], buf.dgate)
+        for name, call in cold_calls.items():
+            for i in range(nset):
+                call(i)
+            torch.cuda.synchronize()
+            B.moe_prof_enable(True)
+            for i in range(reps):
+                call(i % nset)
+            torch.cuda.synchronize()
+            tot = [(ms, c) for n, ms, c in B.moe_prof_read()]
+            B.moe_prof_enable(False)
+            ms = sum(t for t, _ in tot) / max(sum(c for _, c in tot), 1)
+            if name in kernels and ms > 0:
+                amount = work[name][1]
+                kernels[name]["cold_us"] = round(ms * 1e3, 2)
+                kernels[name]["gbs_cold"] = round(amount / (ms * 1e-3) / 1e9, 1)
+                kernels[name]["frac_cold"] = round(kernels[name]["gbs_cold"] / PEAK_HBM_GBS, 4)
+        line["cold_cache"] = {"buffer_sets": nset, "bytes_per_set": rows[0].numel() * 2,
+                              "note": "gbs_cold / frac_cold in `kernels`: the kernel alone, its [R, d] operand rotated through "
+                                      "this many buffer sets, so every launch reads its rows from HBM; `gbs` is the rate "
+                                      "inside the step, where part of the rows may still lie in the last-level cache"}
+        del rows, outs
     # ---- the router and the backward of Stage 1 (they make the layer a drop-in block): timed apart, not in `value`
     if "Wr" in inp:
         Wr = torch.from_numpy(inp["Wr"]).to(dev)
@@ -270,7 +330,7 @@ def main():
         "workload_like_operands": {"tflops": round(tf_data, 1), "clock_ghz": round(ghz_data, 3)},
         "zero_operands": {"tflops": round(tf_zero, 1), "clock_ghz": round(ghz_zero, 3)},
         "grouped_gemm_frac_of_workload_like": round(gemm_tflops / tf_data, 4) if tf_data > 0 else None,
-        "note": "v_mfma_f32_32x32x16_bf16 only, operands in registers, 8 waves per CU, measured in this run; "
+        "note": "v_mfma_f32_16x16x32_bf16 only (the form the grouped GEMM uses), operands in registers, 8 waves per CU, measured in this run; "
                 "`roofline.peak` stays the published 2500 TFLOP/s"}
     if not args.no_cpu:
         n = min(args.cpu_sample_tokens, cfg.T)

@@ -321,7 +321,7 @@ int moe_prof_read(int index, char* name, int name_cap, float* total_ms, int* lau
 
 /*
  * Matrix-pipe probe for benchmarks (not part of the paper's method): what rate of
- * v_mfma_f32_32x32x16_bf16 the chip sustains for given operand VALUES.  The clock
+ * v_mfma_f32_16x16x32_bf16 (the form the grouped products use) the chip sustains for given operand VALUES.  The clock
  * of the chip follows its power draw, which depends on how many operand bits
  * toggle, so the ceiling for real data lies below the published peak.
  *   a    [workgroups*512, 32] bf16, device: 4 activation fragments per lane

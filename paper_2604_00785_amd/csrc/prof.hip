@@ -58,10 +58,9 @@ MoeLaunchScope::~MoeLaunchScope() {
 int moe_check_launch() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH; }
 
 namespace {
-// Nothing but v_mfma_f32_32x32x16_bf16: every lane keeps 4 + 2 operand fragments in registers (the
-// wave tile of the grouped GEMM, 8 accumulators) and multiplies them over and over.  No memory
-// traffic inside the loop, so the rate measured is the matrix pipe's at the clock the chip holds
-// for these operand values.
+// Nothing but v_mfma_f32_16x16x32_bf16, the form the grouped GEMM uses: every lane keeps 4 + 2 operand fragments
+// in registers (8 accumulators of 16x16) and multiplies them over and over.  No memory traffic inside the loop,
+// so the rate measured is the matrix pipe's at the clock the chip holds for these operand values.
 __device__ long long g_ceiling_clk[2];
 __global__ __launch_bounds__(512) void mfma_ceiling_kernel(const uint16_t* __restrict__ a, const uint16_t* __restrict__ b,
                                                            int iters, float* __restrict__ sink) {
@@ -71,20 +70,20 @@ __global__ __launch_bounds__(512) void mfma_ceiling_kernel(const uint16_t* __res
   for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(a + t * 32 + i * 8);
 #pragma unroll
   for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(b + t * 16 + j * 8);
-  f32x16_t acc[4][2];
+  f32x4_t acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
   const long long w0 = wall_clock64(), c0 = __builtin_readcyclecounter();
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
   }
   const long long c1 = __builtin_readcyclecounter(), w1 = wall_clock64();
   float s = 0.f;
@@ -93,7 +92,7 @@ __global__ __launch_bounds__(512) void mfma_ceiling_kernel(const uint16_t* __res
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s += acc[i][j][r];
+      for (int r = 0; r < 4; ++r) s += acc[i][j][r];
   sink[t] = s;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     g_ceiling_clk[0] = c1 - c0;   // core clock cycles
@@ -148,7 +147,7 @@ int moe_prof_mfma_ceiling(const moe_bf16* a, const moe_bf16* b, int workgroups, 
     rc = MOE_ERR_LAUNCH;
   g_pool.push_back(e0);
   g_pool.push_back(e1);
-  *flop = 2.0 * 32 * 32 * 16 * 8.0 * iters * 8.0 * workgroups;
+  *flop = 2.0 * 16 * 16 * 32 * 8.0 * iters * 8.0 * workgroups;
   *clock_ghz = clk[1] > 0 ? static_cast<double>(clk[0]) / (static_cast<double>(clk[1]) * 10.0) : 0.0;
   return rc == MOE_OK ? moe_check_launch() : rc;
 }
