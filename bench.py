@@ -48,6 +48,7 @@ def kernel_work(cfg, R):
         "combine_bwd": ("hbm", row * (T + R) + row * R),
         "permute_bwd": ("hbm", row * (R + T)),
         "route": ("hbm", 4.0 * T * cfg.E + 8.0 * T * k),
+        "route_count": ("hbm", 4.0 * T * cfg.E + 8.0 * T * k),   # routing with the per-chunk expert counts as a by-product
         "permute_count": ("hbm", 4.0 * T * k),
         "permute_scan": ("hbm", 0.0),
         "permute_place": ("hbm", 12.0 * T * k),

@@ -177,7 +177,9 @@ int moe_grouped_gemm_fwd_gather(const moe_bf16* x, int T, const int32_t* row_tok
  *   dxp = dg . Wg[e] + du . Wu[e];
  *   dWd[e] = dyp^T . h;  dWg[e] = dg^T . xp;  dWu[e] = du^T . xp   (zeros if e has no rows).
  *   dyp, xp, dxp [R_cap, d]; g, u, h [R_cap, f]; dWg, dWu [E, f, d]; dWd [E, d, f]; all bf16.
- *   ws at least moe_grouped_gemm_bwd_workspace_bytes(R_cap, f): holds dg and du (bf16).
+ *   ws at least moe_grouped_gemm_bwd_workspace_bytes(R_cap, f), 256-byte aligned.  On return it holds
+ *   dg [R_cap, f] bf16 at ws and du [R_cap, f] bf16 at ws + (that size / 2) (rows below
+ *   expert_offsets[E] written): a caller may read them, e.g. to check them.
  */
 int moe_grouped_gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp,
                          const moe_bf16* g, const moe_bf16* u, const moe_bf16* h,
@@ -196,6 +198,21 @@ int moe_grouped_gemm_bwd_gather(const moe_bf16* dyp, const moe_bf16* x, int T, c
                                 int E, int R_cap, int d, int f,
                                 moe_bf16* dxp, moe_bf16* dWg, moe_bf16* dWu, moe_bf16* dWd,
                                 void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stages 1-3 in one call (Algorithm 1: Softmax, TopK, token counting, index generation), and the Stage-4
+ * gather if xp is given: the results of moe_route followed by moe_permute (or moe_permute_gate), bit for
+ * bit, with one launch fewer: the routing kernel counts its own winners per local expert, so the pairs are
+ * not read back to be counted.
+ *   logits, topk_idx, topk_w, renormalize   as moe_route (both outputs are written in full)
+ *   x, xp                                   as moe_permute; both may be NULL (index generation only)
+ *   row_weight                              as moe_permute_gate, or NULL
+ *   expert_offsets, row_token, slot_row, ws as moe_permute
+ */
+int moe_route_permute(const float* logits, const moe_bf16* x, int T, int d, int E_total, int k, int renormalize,
+                      int e_begin, int e_count, int32_t* topk_idx, float* topk_w,
+                      int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row, float* row_weight,
+                      moe_bf16* xp, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * The layer with the gate weights folded into the expert MLP (Stages 2-5 and their derivatives give the

@@ -20,7 +20,7 @@ EXPORTS = [
     "moe_version", "moe_permute_workspace_bytes", "moe_grouped_gemm_bwd_workspace_bytes", "moe_workspace_bytes",
     "moe_route", "moe_permute", "moe_permute_bwd", "moe_grouped_gemm_fwd", "moe_grouped_gemm_bwd",
     "moe_grouped_gemm_fwd_gather", "moe_grouped_gemm_bwd_gather",
-    "moe_permute_gate", "moe_grouped_gemm_fwd_folded", "moe_unpermute_sum",
+    "moe_permute_gate", "moe_route_permute", "moe_grouped_gemm_fwd_folded", "moe_unpermute_sum",
     "moe_grouped_gemm_bwd_folded_workspace_bytes", "moe_grouped_gemm_bwd_folded",
     "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_prof_enable", "moe_prof_count", "moe_prof_read", "moe_prof_mfma_ceiling",
     "moe_router_fwd", "moe_route_bwd", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
@@ -73,6 +73,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "moe_grouped_gemm_fwd_gather": [vp, c_int, vp, vp, vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp],
         "moe_grouped_gemm_bwd_gather": [vp, vp, c_int, vp] + [vp] * 7 + [c_int] * 4 + [vp] * 4 + [vp, c_sz, vp],
         "moe_permute_gate": [vp, vp, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, c_sz, vp],
+        "moe_route_permute": [vp, vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, vp, vp, vp, c_sz, vp],
         "moe_grouped_gemm_fwd_folded": [vp, c_int, vp, vp, vp, vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp],
         "moe_unpermute_sum": [vp, vp, c_int, c_int, c_int, vp, vp],
         "moe_grouped_gemm_bwd_folded": [vp, vp, c_int, c_int, vp, vp, vp] + [vp] * 7 + [c_int] * 4 + [vp] * 5 + [vp, c_sz, vp],
@@ -265,6 +266,29 @@ def moe_permute_gate(topk_idx, topk_w, E_total: int, e_begin: int, e_count: int,
                                    ws.numel() * ws.element_size(), _stream()), "moe_permute_gate")
 
 
+def moe_route_permute(logits, x, k: int, renormalize: int, e_begin: int, e_count: int, topk_idx, topk_w,
+                      expert_offsets, row_token, slot_row, row_weight, xp, ws) -> None:
+    """Stages 1-3 in one call; ``x``/``xp`` and ``row_weight`` may be None."""
+    T, E = logits.shape
+    _want(logits, torch.float32, name="logits")
+    _want(topk_idx, torch.int32, (T, k), "topk_idx")
+    _want(topk_w, torch.float32, (T, k), "topk_w")
+    _want(expert_offsets, torch.int32, (e_count + 1,), "expert_offsets")
+    _want(row_token, torch.int32, (T * k,), "row_token")
+    _want(slot_row, torch.int32, (T, k), "slot_row")
+    d = 8
+    if x is not None:
+        _want(x, BF16, name="x")
+        d = x.shape[1]
+    if xp is not None:
+        _want(xp, BF16, (T * k, d), "xp")
+    if row_weight is not None:
+        _want(row_weight, torch.float32, (T * k,), "row_weight")
+    _check(load().moe_route_permute(_p(logits), _p(x), T, d, E, k, renormalize, e_begin, e_count, _p(topk_idx),
+                                    _p(topk_w), _p(expert_offsets), _p(row_token), _p(slot_row), _p(row_weight),
+                                    _p(xp), _p(ws), ws.numel() * ws.element_size(), _stream()), "moe_route_permute")
+
+
 def moe_grouped_gemm_fwd_folded(x, row_token, row_weight, expert_offsets, Wg, Wu, Wd, g, u, hw, ypw) -> None:
     T, d = x.shape
     R_cap = row_token.shape[0]
@@ -445,17 +469,17 @@ class MoELayerBuffers:
         self.ws = torch.zeros(max(moe_workspace_bytes(T, E, k, d, f), 256), dtype=torch.uint8, device=dev)
 
     def run_fwd(self, x, logits, Wg, Wu, Wd) -> None:
-        moe_route(logits, self.k, self.renormalize, self.topk_idx, self.topk_w)
         if self.fold:
             self._x = x
-            moe_permute_gate(self.topk_idx, self.topk_w, self.E, self.e_begin, self.e_count, self.expert_offsets,
-                             self.row_token, self.slot_row, self.row_weight, self.ws)
+            moe_route_permute(logits, None, self.k, self.renormalize, self.e_begin, self.e_count, self.topk_idx,
+                              self.topk_w, self.expert_offsets, self.row_token, self.slot_row, self.row_weight, None,
+                              self.ws)
             moe_grouped_gemm_fwd_folded(x, self.row_token, self.row_weight, self.expert_offsets, Wg, Wu, Wd, self.g,
                                         self.u, self.h, self.yp)
             moe_unpermute_sum(self.yp, self.slot_row, self.out)
             return
-        moe_permute(x, self.topk_idx, self.E, self.e_begin, self.e_count, self.expert_offsets, self.row_token,
-                    self.slot_row, self.xp, self.ws)
+        moe_route_permute(logits, x, self.k, self.renormalize, self.e_begin, self.e_count, self.topk_idx, self.topk_w,
+                          self.expert_offsets, self.row_token, self.slot_row, None, self.xp, self.ws)
         if self.gather:
             self._x = x          # the backward reads the layer input again
             moe_grouped_gemm_fwd_gather(x, self.row_token, self.expert_offsets, Wg, Wu, Wd, self.g, self.u, self.h,

@@ -1,70 +1,28 @@
 // Stages 2-3 of Algorithm 1 (token counting, index generation) and the Stage-4
 // gather, as an atomics-free stable counting sort:
 //
-//   count   every workgroup owns PERM_CHUNK consecutive (token, slot) pairs and
-//           counts them per local expert; each wave finds, with one ballot per
-//           bit of the expert id, the lanes of a 64-pair batch that chose the
-//           same expert, and the lowest lane of each such group adds the group
-//           size to the wave's own LDS row: no atomic anywhere.  -> block_hist[e][b]
-//   scan    one workgroup turns block_hist, read in expert-major order, into
-//           exclusive prefix sums: the first row of every (expert, workgroup)
-//           cell, and expert_offsets.  This is the paper's
-//           partial_cum_token_counts / cum_token_counts at workgroup granularity.
-//   place   every workgroup recounts its pairs, derives each wave's first row
-//           per expert, and ranks pairs inside a batch by the popcount of the
-//           lower lanes that chose the same expert -> slot_row, row_token.
+//   count   the (token, slot) pairs are cut into at most 256 chunks of consecutive pairs; one
+//           workgroup per chunk counts its pairs per local expert: each wave finds, with one
+//           ballot per bit of the expert id, the lanes of a 64-pair batch that chose the same
+//           expert, and the lowest lane of each such group adds the group size to the wave's own
+//           LDS row: no atomic anywhere.  -> hist[chunk][expert].  When the routing runs in the
+//           same call, the routing kernel counts its own winners and this launch does not exist.
+//   place   every workgroup first sums the table's columns: over all chunks (the experts' totals,
+//           whose exclusive scan is expert_offsets) and over the chunks in front of its own (the
+//           first row of its (expert, chunk) cell).  This is the paper's cum_token_counts /
+//           partial_cum_token_counts at chunk granularity, recomputed by every workgroup from a
+//           table that stays in L2 instead of by a kernel of its own.  It then recounts its pairs,
+//           derives each wave's first row per expert, and ranks pairs inside a batch by the
+//           popcount of the lower lanes that chose the same expert -> slot_row, row_token.
 //   rows    one wave per token copies x[t] to its (up to k) grouped rows with
 //           16-byte accesses: x is read once, xp is written in full rows.
-#include "common.h"
+#include "perm_common.h"
 
 namespace {
 
-constexpr int PERM_THREADS = 256;
-constexpr int PERM_WAVES = PERM_THREADS / MOE_WAVE;
-constexpr int PERM_ITERS = 1;                                  // 64-pair batches per wave
-constexpr int PERM_CHUNK = PERM_WAVES * PERM_ITERS * MOE_WAVE;  // pairs per workgroup
-
-__device__ __forceinline__ uint64_t lanemask_lt() {
-  const int lane = threadIdx.x % MOE_WAVE;
-  return lane == 0 ? 0ull : (~0ull >> (64 - lane));
-}
-
-// For every lane, the mask of lanes of its 64-pair batch that chose the same local expert: the
-// AND over the bits of the expert id of "lanes whose bit equals mine" (one ballot per bit, so
-// log2(e_count) steps whatever the number of distinct experts).  Lanes with e < 0 get 0.
-__device__ __forceinline__ uint64_t same_expert_mask(int e, int nbits) {
-  uint64_t m = __ballot(e >= 0);
-  for (int b = 0; b < nbits; ++b) {
-    const uint64_t set = __ballot((e >> b) & 1);
-    m &= ((e >> b) & 1) ? set : ~set;
-  }
-  return e >= 0 ? m : 0ull;
-}
-
-// Counts this wave's pairs per local expert into cnt[] (one LDS row per wave).
-// le[it] receives the local expert id of the lane's pair in batch `it`, or -1.
-__device__ __forceinline__ void count_wave(const int32_t* __restrict__ topk_idx, int n, int e_begin, int e_count,
-                                           int nbits, int first, int* cnt, int le[PERM_ITERS]) {
-  const int lane = threadIdx.x % MOE_WAVE;
-#pragma unroll
-  for (int it = 0; it < PERM_ITERS; ++it) {
-    const int idx = first + it * MOE_WAVE + lane;
-    int e = -1;
-    if (idx < n) {
-      e = topk_idx[idx] - e_begin;
-      if (e < 0 || e >= e_count) e = -1;
-    }
-    le[it] = e;
-    const uint64_t m = same_expert_mask(e, nbits);
-    // the lowest lane of every group adds the group's size: one writer per expert and batch
-    if (m != 0 && lane == __builtin_ctzll(m)) cnt[e] += __builtin_popcountll(m);
-    __builtin_amdgcn_wave_barrier();
-  }
-}
-
 __global__ __launch_bounds__(PERM_THREADS) void permute_count_kernel(const int32_t* __restrict__ topk_idx, int n,
-                                                                     int e_begin, int e_count, int nbits, int nblocks,
-                                                                     int32_t* __restrict__ block_hist) {
+                                                                     int e_begin, int e_count, int nbits, int chunk,
+                                                                     int32_t* __restrict__ hist) {
   __shared__ int wcnt[PERM_WAVES][MOE_MAX_EXPERTS];
   const int tid = threadIdx.x, w = tid / MOE_WAVE;
   for (int e = tid; e < e_count; e += PERM_THREADS) {
@@ -72,88 +30,124 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_count_kernel(const int32
     for (int v = 0; v < PERM_WAVES; ++v) wcnt[v][e] = 0;
   }
   __syncthreads();
-  int le[PERM_ITERS];
-  count_wave(topk_idx, n, e_begin, e_count, nbits, blockIdx.x * PERM_CHUNK + w * PERM_ITERS * MOE_WAVE, wcnt[w], le);
+  const int first = blockIdx.x * chunk;
+  const int len = min(chunk, n - first);
+  count_wave_span(len, nbits, wcnt[w], [&](int i) {
+    const int e = topk_idx[first + i] - e_begin;
+    return (e < 0 || e >= e_count) ? -1 : e;
+  });
   __syncthreads();
   for (int e = tid; e < e_count; e += PERM_THREADS) {
     int s = 0;
 #pragma unroll
     for (int v = 0; v < PERM_WAVES; ++v) s += wcnt[v][e];
-    block_hist[static_cast<size_t>(e) * nblocks + blockIdx.x] = s;
+    hist[static_cast<size_t>(blockIdx.x) * e_count + e] = s;
   }
 }
 
-// In-place exclusive scan of block_hist (length e_count*nblocks, padded to a multiple of 4 by the
-// workspace rounding) by one workgroup of 1024 threads: 4096 elements per sweep with 16-byte
-// accesses, a shuffle scan inside each wave, the 16 wave totals through LDS, a running carry.
-__global__ __launch_bounds__(1024) void permute_scan_kernel(int32_t* __restrict__ block_hist, int e_count, int nblocks,
-                                                            int32_t* __restrict__ expert_offsets) {
-  __shared__ int wsum[16];
-  const int tid = threadIdx.x, lane = tid % MOE_WAVE, w = tid / MOE_WAVE;
-  const int N = e_count * nblocks;
-  int carry = 0;
-  for (int base = 0; base < N; base += 4096) {
-    const int i = base + tid * 4;
-    int4 v = make_int4(0, 0, 0, 0);
-    if (i < N) v = *reinterpret_cast<const int4*>(block_hist + i);
-    if (i + 1 >= N) v.y = 0;
-    if (i + 2 >= N) v.z = 0;
-    if (i + 3 >= N) v.w = 0;
-    const int s = v.x + v.y + v.z + v.w;
+__global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32_t* __restrict__ topk_idx, int n, int k,
+                                                                     int e_begin, int e_count, int nbits, int chunk,
+                                                                     const int32_t* __restrict__ hist,
+                                                                     int32_t* __restrict__ expert_offsets,
+                                                                     int32_t* __restrict__ row_token,
+                                                                     int32_t* __restrict__ slot_row,
+                                                                     const float* __restrict__ topk_w,
+                                                                     float* __restrict__ row_weight) {
+  __shared__ int wcnt[PERM_WAVES][MOE_MAX_EXPERTS];
+  // partial column sums, [part][expert]: parts * e_count <= 1024 entries; after the reduction row 0 holds
+  // the sums (before: rows of the chunks in front of this one; total: the expert's rows)
+  __shared__ __attribute__((aligned(16))) int part_before[2 * MOE_MAX_EXPERTS];
+  __shared__ __attribute__((aligned(16))) int part_total[2 * MOE_MAX_EXPERTS];
+  __shared__ int first_row[MOE_MAX_EXPERTS];                  // first row of the expert
+  const int tid = threadIdx.x, w = tid / MOE_WAVE, lane = tid % MOE_WAVE;
+  const int b = blockIdx.x, nblocks = gridDim.x;
+
+  // this chunk's pairs; the lane's pair of its wave's first batch is loaded now, ahead of the table
+  const int first = b * chunk;
+  const int len = min(chunk, n - first);
+  auto load_local = [&](int i) {
+    const int e = topk_idx[first + i] - e_begin;
+    return (e < 0 || e >= e_count) ? -1 : e;
+  };
+  const int span = perm_wave_span(len);
+  const int lo = w * span, hi = min(len, lo + span);
+  const int i_pre = lo + lane;
+  const int e_pre = i_pre < hi ? load_local(i_pre) : -1;
+  auto local = [&](int i) { return i == i_pre ? e_pre : load_local(i); };
+
+  // ---- column sums of the table: a thread owns `vec` neighbouring columns of every parts-th chunk ----
+  const int vec = (e_count % 4 == 0) ? 4 : 1;                  // 16-byte reads when the rows allow it
+  const int ncol = e_count / vec;                             // column groups
+  int cols = 1;
+  while (cols < ncol && cols < PERM_THREADS) cols <<= 1;
+  const int parts = PERM_THREADS / cols;                      // parts * e_count <= 256 / cols * 4 * cols = 1024
+  const int p = tid / cols;
+  for (int cg = tid % cols; cg < ncol; cg += (parts == 1 ? PERM_THREADS : (1 << 30))) {
+    int bef[4] = {0, 0, 0, 0}, tot[4] = {0, 0, 0, 0};
+    if (vec == 4) {
+#pragma unroll 16
+      for (int q = p; q < nblocks; q += parts) {
+        const int4 v = *reinterpret_cast<const int4*>(hist + static_cast<size_t>(q) * e_count + cg * 4);
+        const int m = q < b ? -1 : 0;
+        tot[0] += v.x; tot[1] += v.y; tot[2] += v.z; tot[3] += v.w;
+        bef[0] += v.x & m; bef[1] += v.y & m; bef[2] += v.z & m; bef[3] += v.w & m;
+      }
+    } else {
+#pragma unroll 8
+      for (int q = p; q < nblocks; q += parts) {
+        const int v = hist[static_cast<size_t>(q) * e_count + cg];
+        tot[0] += v;
+        bef[0] += q < b ? v : 0;
+      }
+    }
+    for (int j = 0; j < vec; ++j) {
+      part_before[p * e_count + cg * vec + j] = bef[j];
+      part_total[p * e_count + cg * vec + j] = tot[j];
+    }
+  }
+  for (int e = tid; e < e_count; e += PERM_THREADS) {
+#pragma unroll
+    for (int v = 0; v < PERM_WAVES; ++v) wcnt[v][e] = 0;
+  }
+  __syncthreads();
+  for (int c = tid; c < e_count; c += PERM_THREADS) {
+    int bef = 0, tot = 0;
+    for (int q = 0; q < parts; ++q) { bef += part_before[q * e_count + c]; tot += part_total[q * e_count + c]; }
+    part_before[c] = bef;
+    part_total[c] = tot;
+  }
+  __syncthreads();
+  // ---- exclusive scan of the experts' totals by the first wave: ceil(e_count / 64) experts per lane ----
+  if (w == 0) {
+    const int seg = (e_count + MOE_WAVE - 1) / MOE_WAVE;
+    int s = 0;
+    for (int j = 0; j < seg; ++j) {
+      const int e = lane * seg + j;
+      s += e < e_count ? part_total[e] : 0;
+    }
     int inc = s;
 #pragma unroll
     for (int d = 1; d < MOE_WAVE; d <<= 1) {
       const int o = __shfl_up(inc, d, MOE_WAVE);
       if (lane >= d) inc += o;
     }
-    if (lane == MOE_WAVE - 1) wsum[w] = inc;
-    __syncthreads();
-    int before = 0, total = 0;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int t = wsum[q];
-      if (q < w) before += t;
-      total += t;
+    int run = inc - s;
+    for (int j = 0; j < seg; ++j) {
+      const int e = lane * seg + j;
+      if (e < e_count) {
+        first_row[e] = run;
+        if (b == 0) expert_offsets[e] = run;
+        run += part_total[e];
+      }
     }
-    __syncthreads();
-    int4 o;
-    o.x = carry + before + inc - s;
-    o.y = o.x + v.x;
-    o.z = o.y + v.y;
-    o.w = o.z + v.z;
-    if (i < N) {
-      *reinterpret_cast<int4*>(block_hist + i) = o;
-      const int r[4] = {o.x, o.y, o.z, o.w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (i + j < N && (i + j) % nblocks == 0) expert_offsets[(i + j) / nblocks] = r[j];
-    }
-    carry += total;
+    if (b == 0 && lane == MOE_WAVE - 1) expert_offsets[e_count] = inc;
   }
-  if (tid == 0) expert_offsets[e_count] = carry;
-}
 
-__global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32_t* __restrict__ topk_idx, int n, int k,
-                                                                     int e_begin, int e_count, int nbits, int nblocks,
-                                                                     const int32_t* __restrict__ block_base,
-                                                                     int32_t* __restrict__ row_token,
-                                                                     int32_t* __restrict__ slot_row,
-                                                                     const float* __restrict__ topk_w,
-                                                                     float* __restrict__ row_weight) {
-  __shared__ int wcnt[PERM_WAVES][MOE_MAX_EXPERTS];
-  const int tid = threadIdx.x, w = tid / MOE_WAVE, lane = tid % MOE_WAVE;
-  for (int e = tid; e < e_count; e += PERM_THREADS) {
-#pragma unroll
-    for (int v = 0; v < PERM_WAVES; ++v) wcnt[v][e] = 0;
-  }
+  // ---- this chunk: counts per wave, each wave's first row per expert, ranks ----
+  count_wave_span(len, nbits, wcnt[w], local);
   __syncthreads();
-  int le[PERM_ITERS];
-  const int first = blockIdx.x * PERM_CHUNK + w * PERM_ITERS * MOE_WAVE;
-  count_wave(topk_idx, n, e_begin, e_count, nbits, first, wcnt[w], le);
-  __syncthreads();
-  // counts -> first row of each wave for each expert
   for (int e = tid; e < e_count; e += PERM_THREADS) {
-    int base = block_base[static_cast<size_t>(e) * nblocks + blockIdx.x];
+    int base = first_row[e] + part_before[e];
 #pragma unroll
     for (int v = 0; v < PERM_WAVES; ++v) {
       const int c = wcnt[v][e];
@@ -164,10 +158,9 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32
   __syncthreads();
   int* next = wcnt[w];
   const uint64_t lt = lanemask_lt();
-#pragma unroll
-  for (int it = 0; it < PERM_ITERS; ++it) {
-    const int idx = first + it * MOE_WAVE + lane;
-    const int e = le[it];
+  for (int f0 = lo; f0 < hi; f0 += MOE_WAVE) {
+    const int i = f0 + lane;
+    const int e = i < hi ? local(i) : -1;
     int row = -1;
     const uint64_t m = same_expert_mask(e, nbits);
     if (m != 0) {
@@ -177,7 +170,8 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32
       if (lane == __builtin_ctzll(m)) next[e] = base + __builtin_popcountll(m);
     }
     __builtin_amdgcn_wave_barrier();
-    if (idx < n) {
+    if (i < hi) {
+      const int idx = first + i;
       slot_row[idx] = row;
       if (row >= 0) {
         row_token[row] = idx / k;
@@ -215,23 +209,40 @@ __global__ __launch_bounds__(256) void permute_rows_kernel(const uint4* __restri
   }
 }
 
-inline int perm_blocks(int T, int k) {
-  const long long n = static_cast<long long>(T) * k;
-  return static_cast<int>((n + PERM_CHUNK - 1) / PERM_CHUNK);
+// Chunks of the plain path (topk_idx given): whole multiples of 256 pairs, as few as keep the table at
+// perm_max_chunks rows.
+inline int perm_chunk_pairs(long long n, int e_count) {
+  const long long units = (n + 255) / 256;
+  const long long per = (units + perm_max_chunks(e_count) - 1) / perm_max_chunks(e_count);
+  return static_cast<int>(per * 256);
 }
 
 }  // namespace
 
 extern "C" size_t moe_permute_workspace_bytes(int T, int k, int e_count) {
   if (T <= 0 || k <= 0 || e_count <= 0) return 0;
-  const size_t cells = static_cast<size_t>(e_count) * perm_blocks(T, k);
-  return (cells * sizeof(int32_t) + 16 + 255) & ~static_cast<size_t>(255);   // + one 16-byte access of slack
+  // one table row per 256 pairs covers every chunking (chunks never hold fewer pairs than that)
+  const size_t rows = (static_cast<size_t>(T) * k + 255) / 256;
+  return (rows * e_count * sizeof(int32_t) + 16 + 255) & ~static_cast<size_t>(255);
 }
 
 namespace {
-int permute_impl(const moe_bf16* x, const int32_t* topk_idx, const float* topk_w, int T, int d, int E_total, int k,
-                 int e_begin, int e_count, int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row,
-                 float* row_weight, moe_bf16* xp, void* ws, size_t ws_bytes, void* stream) {
+void launch_rows(const moe_bf16* x, const int32_t* slot_row, int T, int d, int k, moe_bf16* xp, hipStream_t s) {
+  const int chunks = d / 8;
+  dim3 grid((T + 3) / 4), block(256);
+  const uint4* xs = reinterpret_cast<const uint4*>(x);
+  uint4* xd = reinterpret_cast<uint4*>(xp);
+  if (chunks <= 64)
+    MOE_LAUNCH("permute_rows", permute_rows_kernel<1>, grid, block, 0, s, xs, slot_row, T, k, chunks, xd);
+  else if (chunks <= 128)
+    MOE_LAUNCH("permute_rows", permute_rows_kernel<2>, grid, block, 0, s, xs, slot_row, T, k, chunks, xd);
+  else
+    MOE_LAUNCH("permute_rows", permute_rows_kernel<4>, grid, block, 0, s, xs, slot_row, T, k, chunks, xd);
+}
+
+int check_permute_args(const moe_bf16* x, const int32_t* topk_idx, int T, int d, int E_total, int k, int e_begin,
+                       int e_count, const int32_t* expert_offsets, const int32_t* row_token, const int32_t* slot_row,
+                       const moe_bf16* xp, const void* ws, size_t ws_bytes) {
   // xp == NULL: index generation only (for callers that let the GEMMs gather the rows); x is not read then
   if (!topk_idx || !expert_offsets || !row_token || !slot_row || !ws || (xp && !x)) return MOE_ERR_INVALID;
   if (T <= 0 || d <= 0 || d % 8 != 0 || E_total <= 0 || k <= 0 || k > E_total) return MOE_ERR_INVALID;
@@ -241,30 +252,66 @@ int permute_impl(const moe_bf16* x, const int32_t* topk_idx, const float* topk_w
       !moe_aligned16(slot_row) || !moe_aligned16(row_token) || !moe_aligned16(expert_offsets))
     return MOE_ERR_INVALID;
   if (ws_bytes < moe_permute_workspace_bytes(T, k, e_count)) return MOE_ERR_WORKSPACE;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  const int n = T * k, nb = perm_blocks(T, k);
+  return MOE_OK;
+}
+
+int expert_bits(int e_count) {
   int nbits = 0;
   while ((1 << nbits) < e_count) ++nbits;
-  int32_t* block_hist = static_cast<int32_t*>(ws);
+  return nbits;
+}
+
+int permute_impl(const moe_bf16* x, const int32_t* topk_idx, const float* topk_w, int T, int d, int E_total, int k,
+                 int e_begin, int e_count, int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row,
+                 float* row_weight, moe_bf16* xp, void* ws, size_t ws_bytes, void* stream) {
+  const int bad = check_permute_args(x, topk_idx, T, d, E_total, k, e_begin, e_count, expert_offsets, row_token, slot_row,
+                                     xp, ws, ws_bytes);
+  if (bad != MOE_OK) return bad;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int n = T * k, nbits = expert_bits(e_count);
+  const int chunk = perm_chunk_pairs(n, e_count), nb = (n + chunk - 1) / chunk;
+  int32_t* hist = static_cast<int32_t*>(ws);
   MOE_LAUNCH("permute_count", permute_count_kernel, dim3(nb), dim3(PERM_THREADS), 0, s, topk_idx, n, e_begin, e_count,
-             nbits, nb, block_hist);
-  MOE_LAUNCH("permute_scan", permute_scan_kernel, dim3(1), dim3(1024), 0, s, block_hist, e_count, nb, expert_offsets);
+             nbits, chunk, hist);
   MOE_LAUNCH("permute_place", permute_place_kernel, dim3(nb), dim3(PERM_THREADS), 0, s, topk_idx, n, k, e_begin,
-             e_count, nbits, nb, static_cast<const int32_t*>(block_hist), row_token, slot_row, topk_w, row_weight);
-  if (!xp) return moe_check_launch();
-  const int chunks = d / 8;
-  dim3 grid((T + 3) / 4), block(256);
-  const uint4* xs = reinterpret_cast<const uint4*>(x);
-  uint4* xd = reinterpret_cast<uint4*>(xp);
-  if (chunks <= 64)
-    MOE_LAUNCH("permute_rows", permute_rows_kernel<1>, grid, block, 0, s, xs, static_cast<const int32_t*>(slot_row), T, k, chunks, xd);
-  else if (chunks <= 128)
-    MOE_LAUNCH("permute_rows", permute_rows_kernel<2>, grid, block, 0, s, xs, static_cast<const int32_t*>(slot_row), T, k, chunks, xd);
-  else
-    MOE_LAUNCH("permute_rows", permute_rows_kernel<4>, grid, block, 0, s, xs, static_cast<const int32_t*>(slot_row), T, k, chunks, xd);
+             e_count, nbits, chunk, static_cast<const int32_t*>(hist), expert_offsets, row_token, slot_row, topk_w,
+             row_weight);
+  if (xp) launch_rows(x, slot_row, T, d, k, xp, s);
   return moe_check_launch();
 }
 }  // namespace
+
+// Stages 1-3 (and the Stage-4 gather if xp is given) in one call: the routing kernel counts its own
+// winners per chunk of tokens, so the pairs are read back once (by the placing kernel) instead of twice.
+extern "C" int moe_route_permute(const float* logits, const moe_bf16* x, int T, int d, int E_total, int k,
+                                 int renormalize, int e_begin, int e_count, int32_t* topk_idx, float* topk_w,
+                                 int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row, float* row_weight,
+                                 moe_bf16* xp, void* ws, size_t ws_bytes, void* stream) {
+  if (!logits || !topk_w || !moe_aligned16(logits) || !moe_aligned16(topk_w)) return MOE_ERR_INVALID;
+  if (row_weight && !moe_aligned16(row_weight)) return MOE_ERR_INVALID;
+  const int bad = check_permute_args(x, topk_idx, T, d, E_total, k, e_begin, e_count, expert_offsets, row_token, slot_row,
+                                     xp, ws, ws_bytes);
+  if (bad != MOE_OK) return bad;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int n = T * k, nbits = expert_bits(e_count);
+  int32_t* hist = static_cast<int32_t*>(ws);
+  int chunk = 0, nb = 0;
+  if (!moe_launch_route_count(logits, T, E_total, k, renormalize != 0, e_begin, e_count, nbits, topk_idx, topk_w, hist,
+                              &chunk, &nb, s)) {
+    const int r = moe_route(logits, T, E_total, k, renormalize, topk_idx, topk_w, stream);
+    if (r != MOE_OK) return r;
+    chunk = perm_chunk_pairs(n, e_count);
+    nb = (n + chunk - 1) / chunk;
+    MOE_LAUNCH("permute_count", permute_count_kernel, dim3(nb), dim3(PERM_THREADS), 0, s,
+               static_cast<const int32_t*>(topk_idx), n, e_begin, e_count, nbits, chunk, hist);
+  }
+  MOE_LAUNCH("permute_place", permute_place_kernel, dim3(nb), dim3(PERM_THREADS), 0, s,
+             static_cast<const int32_t*>(topk_idx), n, k, e_begin, e_count, nbits, chunk,
+             static_cast<const int32_t*>(hist), expert_offsets, row_token, slot_row,
+             static_cast<const float*>(topk_w), row_weight);
+  if (xp) launch_rows(x, slot_row, T, d, k, xp, s);
+  return moe_check_launch();
+}
 
 extern "C" int moe_permute(const moe_bf16* x, const int32_t* topk_idx, int T, int d, int E_total, int k, int e_begin,
                            int e_count, int32_t* expert_offsets, int32_t* row_token, int32_t* slot_row, moe_bf16* xp,

@@ -81,22 +81,58 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.abs(got - ref).max() / scale)
 
 
-def outlier_fraction(got: np.ndarray, ref: np.ndarray) -> float:
-    """Share of elements off by more than 2e-2 relative plus a small absolute floor."""
+# Absolute floor of the element-wise check, in units of rms(ref).  Measured on the full-size workloads
+# (printed by test_full_size_config): the 99.9th percentile of |d| / rms(ref) lies between 0.7e-2 (dgate)
+# and 2.0e-2 (dxp), and weight gradients of experts with a handful of rows reach it too, so a floor below
+# 2e-2 would flag more than the 1e-3 share of elements the check allows without any of them being wrong.
+OUTLIER_FLOOR = 2e-2
+
+
+def outlier_fraction(got: np.ndarray, ref: np.ndarray, floor: float = OUTLIER_FLOOR) -> float:
+    """Share of elements off by more than 2e-2 relative plus `floor` * rms(ref).
+
+    The floor covers elements near zero, whose error does not shrink with them: every result is a sum of
+    products of values that were themselves rounded to bf16 (relative error up to 2^-9 = 2e-3 each), so an
+    element's error is a few 1e-3 of the tensor's rms whatever its own size."""
     if ref.size == 0:
         return 0.0
-    rms = float(np.sqrt(np.mean(ref * ref)))
-    bad = np.abs(got - ref) > REL_TOL * np.abs(ref) + 2e-2 * rms
+    bad = np.abs(got - ref) > REL_TOL * np.abs(ref) + floor * ref_rms(ref)
     return float(bad.mean())
+
+
+def ref_rms(ref: np.ndarray) -> float:
+    return float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+
+
+# (name, max|d|/max|ref|, p99.9 of |d|/rms(ref), max of |d|/rms(ref), outlier share) of every assert_close since the
+# last clear: the full-size tests print it, so that the margins under the tolerances are on record.
+ERR_LOG: list = []
 
 
 def assert_close(got, ref, name, tol=REL_TOL):
     assert got.shape == ref.shape, (name, got.shape, ref.shape)
     assert np.all(np.isfinite(got)), f"{name}: non-finite values (unwritten or overflowed elements)"
     e = rel_err(got, ref)
-    assert e <= tol, f"{name}: max|d|/max|ref| = {e:.3e} > {tol}"
     fr = outlier_fraction(got, ref)
-    assert fr <= 1e-3, f"{name}: {fr:.2e} of elements off by more than {REL_TOL} relative"
+    rms = ref_rms(ref)
+    if rms > 0.0:
+        d = np.abs(got - ref).ravel() / rms
+        ERR_LOG.append((name, e, float(np.quantile(d, 0.999)), float(d.max()), fr))
+    assert e <= tol, f"{name}: max|d|/max|ref| = {e:.3e} > {tol}"
+    assert fr <= 1e-3, f"{name}: {fr:.2e} of elements off by more than {REL_TOL} relative + {OUTLIER_FLOOR} rms"
+
+
+def error_table() -> str:
+    """ERR_LOG grouped by tensor (the part of the name in front of '['): worst case of each column."""
+    worst: Dict[str, list] = {}
+    for name, e, q, m, fr in ERR_LOG:
+        key = name.split("[")[0]
+        w = worst.setdefault(key, [0.0, 0.0, 0.0, 0.0, 0])
+        w[0], w[1], w[2], w[3], w[4] = max(w[0], e), max(w[1], q), max(w[2], m), max(w[3], fr), w[4] + 1
+    lines = ["%-8s %6s %16s %18s %14s %12s" % ("tensor", "checks", "max|d|/max|ref|", "p99.9 |d|/rms(ref)", "max |d|/rms", "outlier share")]
+    for key, w in worst.items():
+        lines.append("%-8s %6d %16.3e %18.3e %14.3e %12.2e" % (key, w[4], w[0], w[1], w[2], w[3]))
+    return "\n".join(lines)
 
 
 def row_weights(ref: Dict[str, np.ndarray]) -> np.ndarray:

@@ -48,7 +48,9 @@ def test_route(T, E, k, renorm):
 # ----------------------------------------------------------------------------- permute
 @pytest.mark.parametrize("T,E,k,d,eb,ec", [
     (256, 8, 2, 128, 0, 8), (1000, 64, 8, 256, 0, 64), (1000, 64, 8, 64, 16, 8), (513, 128, 8, 2048, 0, 128),
-    (129, 12, 5, 4096, 3, 7), (7, 4, 1, 8, 0, 4), (4096, 512, 4, 72, 0, 512), (3000, 16, 4, 1032, 0, 16)])
+    (129, 12, 5, 4096, 3, 7), (7, 4, 1, 8, 0, 4), (4096, 512, 4, 72, 0, 512), (3000, 16, 4, 1032, 0, 16),
+    (20000, 64, 8, 8, 0, 64),       # more than 256 * 256 pairs: chunks of several 256-pair units
+    (9000, 300, 8, 8, 10, 280)])    # more than 128 local experts: at most 128 chunks, two table columns per thread
 def test_permute(T, E, k, d, eb, ec):
     print(f"permute T={T} E={E} k={k} d={d} local=[{eb},{eb+ec})", flush=True)
     rng = np.random.default_rng(T * 3 + E)
@@ -76,6 +78,57 @@ def test_permute(T, E, k, d, eb, ec):
     off2, rt2, sr2 = torch.zeros_like(off), torch.zeros_like(rt), torch.zeros_like(sr)
     B.moe_permute(x, dev_i32(idx), E, eb, ec, off2, rt2, sr2, xp, ws)
     torch.cuda.synchronize()
+    assert torch.equal(off, off2) and torch.equal(sr, sr2) and torch.equal(rt[:R], rt2[:R])
+
+
+# ----------------------------------------------------------------------------- route + permute in one call
+@pytest.mark.parametrize("T,E,k,eb,ec", [
+    (256, 8, 2, 0, 8), (1000, 64, 8, 0, 64), (1000, 64, 8, 16, 8), (777, 128, 8, 0, 128), (50, 5, 5, 1, 3),
+    (130, 100, 7, 0, 100), (64, 300, 70, 20, 200), (33, 512, 9, 0, 512), (1, 64, 8, 0, 64), (5, 1, 1, 0, 1),
+    (8192, 64, 8, 0, 64),           # the headline shape: two passes of 16 tokens per workgroup
+    (20000, 64, 8, 8, 48),          # several passes per workgroup, a last chunk that is not full
+    (4100, 128, 16, 0, 128)])
+@pytest.mark.parametrize("renorm,gate", [(0, False), (1, True)])
+def test_route_permute_one_call(T, E, k, eb, ec, renorm, gate):
+    print(f"route_permute T={T} E={E} k={k} local=[{eb},{eb+ec}) renorm={renorm} gate={gate}", flush=True)
+    rng = np.random.default_rng(T + 5 * E + k)
+    logits = (rng.standard_normal((T, E)) * 2).astype(np.float32)
+    logits[::7] = np.round(logits[::7])          # ties
+    d = 16
+    xb = W.f32_to_bf16_bits(rng.standard_normal((T, d)).astype(np.float32))
+    x, lg = H.bf16_to_dev(xb), torch.from_numpy(logits).to(DEV)
+    R_cap = T * k
+    mk = lambda shape, dt: torch.full(shape, -7, dtype=dt, device=DEV)
+    idx, w = mk((T, k), torch.int32), mk((T, k), torch.float32)
+    off, rt, sr = mk((ec + 1,), torch.int32), mk((R_cap,), torch.int32), mk((T, k), torch.int32)
+    rw = mk((R_cap,), torch.float32) if gate else None
+    xp = None if gate else torch.zeros(R_cap, d, dtype=torch.bfloat16, device=DEV)
+    ws = torch.full((max(B.moe_permute_workspace_bytes(T, k, ec), 16),), 0x5A, dtype=torch.uint8, device=DEV)
+    B.moe_route_permute(lg, None if gate else x, k, renorm, eb, ec, idx, w, off, rt, sr, rw, xp, ws)
+    torch.cuda.synchronize()
+    ridx, rwts = O.route(logits, k, renorm)
+    roff, rrt, rsr, rxp = O.permute(O.decode_bf16(xb), ridx, eb, ec)
+    R = int(roff[-1])
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    np.testing.assert_allclose(w.cpu().numpy(), rwts, rtol=H.GATE_TOL)
+    assert np.array_equal(off.cpu().numpy(), roff)
+    assert np.array_equal(sr.cpu().numpy(), rsr)
+    assert np.array_equal(rt.cpu().numpy()[:R], rrt)
+    assert np.all(rt.cpu().numpy()[R:] == -7)
+    if gate:
+        got_w = w.cpu().numpy()
+        want = np.zeros(R, dtype=np.float32)
+        want[rsr[rsr >= 0]] = got_w[rsr >= 0]
+        assert np.array_equal(rw.cpu().numpy()[:R], want)     # a copy of the gate weights, row by row
+    else:
+        assert np.array_equal(H.bf16_from_dev(xp)[:R], rxp)
+    # the two-call form gives the same bits
+    idx2, w2 = mk((T, k), torch.int32), mk((T, k), torch.float32)
+    off2, rt2, sr2 = mk((ec + 1,), torch.int32), mk((R_cap,), torch.int32), mk((T, k), torch.int32)
+    B.moe_route(lg, k, renorm, idx2, w2)
+    B.moe_permute(x, idx2, E, eb, ec, off2, rt2, sr2, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(w, w2)
     assert torch.equal(off, off2) and torch.equal(sr, sr2) and torch.equal(rt[:R], rt2[:R])
 
 
@@ -169,6 +222,11 @@ def test_grouped_gemm_fwd_bwd_isolated(counts, d, f):
     gdxp = H.bf16_from_dev(dxp)
     H.assert_close(gdxp[:R], bw["dxp"], "dxp")
     assert np.all(np.isnan(gdxp[R:]))
+    # the two intermediate gradients the workspace holds on return: dg at its start, du half way in
+    half = ws.numel() // 2
+    for n, at in (("dg", 0), ("du", half)):
+        t = ws[at:at + R_cap * f * 2].view(torch.bfloat16).view(R_cap, f)
+        H.assert_close(H.bf16_from_dev(t)[:R], bw[n], n)
     for n, t in (("dWg", dWg), ("dWu", dWu), ("dWd", dWd)):
         gw = H.bf16_from_dev(t)
         for e in range(E):
