@@ -197,18 +197,49 @@ __device__ __forceinline__ int count_row_tiles(const int32_t* offsets, int E, in
 // run of consecutive tiles, then share each weight panel among all row tiles of the expert at the same
 // time, so that it is fetched from memory once (weights are the larger operand and are used by only
 // rows_e / 256 tiles each; activations of a row tile recur every rows_e / 256 tiles).
-// With at most 64 experts the lane's two offsets are read once per kernel (lo0, hi0) instead of once
-// per tile: the lookup then needs no memory access, which would otherwise sit in front of every
-// tile's first loads.
-__device__ __forceinline__ void find_tile(const int32_t* offsets, int E, int lo0, int hi0, int n_tiles, int tile, int lane,
-                                          int& e, int& m0, int& m_end, int& nt) {
-  int base = 0;
+//
+// With at most 64 experts (one per lane) the experts are not listed in index order: those whose tile count
+// is a whole number of XCD runs come first, then those that fill half a run, then the rest.  The first
+// two groups then start on run boundaries, so such an expert's tiles are worked on by one XCD at one
+// time and its activation rows are fetched into one L2 once; an expert that straddles two runs has its
+// rows fetched by both.  The lane keeps its expert's row range and first list position for the whole
+// kernel, so the lookup needs no memory access (which would otherwise sit in front of every tile's
+// first loads) and no scan.
+__device__ __forceinline__ int sorted_first_tile(int tiles, int run, int lane) {
+  const int r = tiles % run;
+  const int cls = r == 0 ? 0 : (2 * r == run ? 1 : 2);
+  int base = 0, first = 0;
+#pragma unroll
+  for (int c = 0; c < 3; ++c) {
+    const int mine = cls == c ? tiles : 0;
+    const int inc = wave_incl_scan(mine, lane);
+    if (cls == c) first = base + inc - mine;
+    base += __shfl(inc, 63, 64);
+  }
+  return first;
+}
+__device__ __forceinline__ void find_tile(const int32_t* offsets, int E, int lo0, int hi0, int first0, int n_tiles, int tile,
+                                          int lane, int& e, int& m0, int& m_end, int& nt) {
   e = 0; m0 = 0; m_end = 0; nt = 0;
+  if (E <= 64) {
+    const int row_tiles = (hi0 - lo0 + BM - 1) / BM;
+    const int tiles = row_tiles * n_tiles;
+    const unsigned long long hit = __ballot(tiles > 0 && first0 <= tile && tile < first0 + tiles);
+    if (hit) {
+      const int l = __ffsll(hit) - 1;
+      e = l;
+      const int q = tile - __shfl(first0, l, 64);
+      const int rt = __shfl(row_tiles, l, 64);
+      nt = q / rt;
+      m0 = __shfl(lo0, l, 64) + (q - nt * rt) * BM;
+      m_end = __shfl(hi0, l, 64);
+    }
+    return;
+  }
+  int base = 0;
   for (int e0 = 0; e0 < E; e0 += 64) {
     const int ee = e0 + lane;
-    int lo, hi;
-    if (E <= 64) { lo = lo0; hi = hi0; }
-    else { lo = ee < E ? offsets[ee] : 0; hi = ee < E ? offsets[ee + 1] : 0; }
+    const int lo = ee < E ? offsets[ee] : 0, hi = ee < E ? offsets[ee + 1] : 0;
     const int row_tiles = (hi - lo + BM - 1) / BM;
     const int tiles = row_tiles * n_tiles;
     const int inc = wave_incl_scan(tiles, lane);
@@ -286,6 +317,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   // ---------------- tile list ---------------------------------------------------
   int total;
   int lo0 = 0, hi0 = 0;   // this lane's expert's row range, kept for the whole kernel when E <= 64
+  int first0 = 0;         // ... and the list position of its first tile
   // WGRAD / WGRAD_GATHER with a second A operand (A1 -> O1): two weight gradients that share their B
   // operand in one launch; an expert's tiles of the first come before its tiles of the second
   int wpair = 1;
@@ -294,7 +326,10 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     total = a.E * a.m_tiles_cap * a.n_tiles * wpair;
   } else {
     total = count_row_tiles(a.offsets, a.E, tid0 & 63) * a.n_tiles;
-    if (a.E <= 64 && (tid0 & 63) < a.E) { lo0 = a.offsets[tid0 & 63]; hi0 = a.offsets[(tid0 & 63) + 1]; }
+    if (a.E <= 64) {
+      if ((tid0 & 63) < a.E) { lo0 = a.offsets[tid0 & 63]; hi0 = a.offsets[(tid0 & 63) + 1]; }
+      first0 = sorted_first_tile((hi0 - lo0 + BM - 1) / BM * a.n_tiles, gridDim.x >> 3, tid0 & 63);
+    }
   }
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<size_t>(LDS_PTR(lds)));
   // M0 base of this wave's loads: the middle of its 8 KB share of tile slot 0 (immediates reach -4096 .. +3072)
@@ -320,7 +355,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     m0 = mi * BM;                       // output row of dW
     m_end = a.M;
   } else {
-    find_tile(a.offsets, a.E, lo0, hi0, a.n_tiles, tile, lane, e, m0, m_end, nt);
+    find_tile(a.offsets, a.E, lo0, hi0, first0, a.n_tiles, tile, lane, e, m0, m_end, nt);
     nt = __builtin_amdgcn_readfirstlane(nt);
   }
   // tile coordinates are wave-uniform: keep them in scalar registers, so that everything derived
