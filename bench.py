@@ -274,10 +274,26 @@ def main():
                 kernels[name]["cold_us"] = round(ms * 1e3, 2)
                 kernels[name]["gbs_cold"] = round(amount / (ms * 1e-3) / 1e9, 1)
                 kernels[name]["frac_cold"] = round(kernels[name]["gbs_cold"] / PEAK_HBM_GBS, 4)
+        # what a kernel that only reads gets from the same rotating buffers: the memory system's practical rate
+        sink = torch.empty(2048 * 256, dtype=torch.int32, device=dev)
+        for i in range(nset):
+            B.moe_prof_stream_read(rows[i], sink, 2048)
+        torch.cuda.synchronize()
+        B.moe_prof_enable(True)
+        for i in range(reps):
+            B.moe_prof_stream_read(rows[i % nset], sink, 2048)
+        torch.cuda.synchronize()
+        sr = [(ms, c) for n, ms, c in B.moe_prof_read()]
+        B.moe_prof_enable(False)
+        sr_ms = sum(t for t, _ in sr) / max(sum(c for _, c in sr), 1)
+        stream_gbs = rows[0].numel() * 2 / (sr_ms * 1e-3) / 1e9 if sr_ms > 0 else None
         line["cold_cache"] = {"buffer_sets": nset, "bytes_per_set": rows[0].numel() * 2,
+                              "stream_read_gbs_cold": None if stream_gbs is None else round(stream_gbs, 1),
                               "note": "gbs_cold / frac_cold in `kernels`: the kernel alone, its [R, d] operand rotated through "
                                       "this many buffer sets, so every launch reads its rows from HBM; `gbs` is the rate "
-                                      "inside the step, where part of the rows may still lie in the last-level cache"}
+                                      "inside the step, where part of the rows may still lie in the last-level cache; "
+                                      "stream_read_gbs_cold: a kernel that only reads (16-byte loads, contiguous) over the same "
+                                      "rotating buffers, i.e. what this memory system delivers at best"}
         del rows, outs
     # ---- the router and the backward of Stage 1 (they make the layer a drop-in block): timed apart, not in `value`
     if "Wr" in inp:

@@ -352,6 +352,16 @@ int moe_prof_read(int index, char* name, int name_cap, float* total_ms, int* lau
 int moe_prof_mfma_ceiling(const moe_bf16* a, const moe_bf16* b, int workgroups, int iters, float* sink,
                           float* ms, double* flop, double* clock_ghz, void* stream);
 
+/*
+ * Memory probe for benchmarks (not part of the paper's method): a kernel that only reads.  `workgroups`
+ * workgroups of 256 threads read the first bytes / 16384 whole 16 KB blocks of src (device, 16-byte aligned)
+ * with 16-byte loads and write one word per thread to sink [workgroups * 256] (device).  Enqueued on
+ * `stream` like any other call (timed through moe_prof_enable / moe_prof_read under the name
+ * "stream_read"); the rate it reaches on buffers that no cache holds is what the row movers' rates
+ * should be read against.
+ */
+int moe_prof_stream_read(const void* src, size_t bytes, uint32_t* sink, int workgroups, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ EXPORTS = [
     "moe_grouped_gemm_fwd_gather", "moe_grouped_gemm_bwd_gather",
     "moe_permute_gate", "moe_route_permute", "moe_grouped_gemm_fwd_folded", "moe_unpermute_sum",
     "moe_grouped_gemm_bwd_folded_workspace_bytes", "moe_grouped_gemm_bwd_folded",
-    "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_prof_enable", "moe_prof_count", "moe_prof_read", "moe_prof_mfma_ceiling",
+    "moe_unpermute_combine", "moe_unpermute_combine_bwd", "moe_prof_enable", "moe_prof_count", "moe_prof_read", "moe_prof_mfma_ceiling", "moe_prof_stream_read",
     "moe_router_fwd", "moe_route_bwd", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
     "moe_permute_static_ws_capacity", "moe_permute_static_ws",
 ]
@@ -85,6 +85,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "moe_prof_enable": [c_int],
         "moe_prof_count": [],
         "moe_prof_read": [c_int, ctypes.c_char_p, c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(c_int)],
+        "moe_prof_stream_read": [vp, c_sz, vp, c_int, vp],
         "moe_prof_mfma_ceiling": [vp, vp, c_int, c_int, vp, ctypes.POINTER(ctypes.c_float),
                                   ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp],
     }
@@ -424,6 +425,13 @@ def moe_prof_mfma_ceiling(a: torch.Tensor, b: torch.Tensor, iters: int) -> Tuple
     _check(load().moe_prof_mfma_ceiling(_p(a), _p(b), n, iters, _p(sink), ctypes.byref(ms), ctypes.byref(flop),
                                         ctypes.byref(ghz), _stream()), "moe_prof_mfma_ceiling")
     return flop.value / (ms.value * 1e-3) / 1e12, ghz.value
+
+
+def moe_prof_stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int) -> None:
+    """Enqueue the read-only probe over ``src``; ``sink`` int32 [workgroups * 256]."""
+    _want(sink, torch.int32, (workgroups * 256,), "sink")
+    _check(load().moe_prof_stream_read(_p(src), src.numel() * src.element_size(), _p(sink), workgroups, _stream()),
+           "moe_prof_stream_read")
 
 
 class MoELayerBuffers:

@@ -99,6 +99,25 @@ __global__ __launch_bounds__(512) void mfma_ceiling_kernel(const uint16_t* __res
     g_ceiling_clk[1] = w1 - w0;   // 100 MHz ticks
   }
 }
+// Streaming-read probe: every workgroup reads whole 16 KB blocks of the buffer with 16-byte loads, four in
+// flight per lane, and folds them into one word per thread: what the memory system delivers to a kernel that
+// does nothing but read.
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t blocks, uint32_t* __restrict__ sink) {
+  uint32_t acc = 0;
+  for (size_t b = blockIdx.x; b < blocks; b += gridDim.x) {
+    const uint4* p = src + b * 1024 + threadIdx.x;
+    uint4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {   // non-temporal, as the row movers read their rows
+      typedef unsigned int u32x4_nt __attribute__((ext_vector_type(4)));
+      const u32x4_nt w = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(p + j * 256));
+      v[j] = make_uint4(w.x, w.y, w.z, w.w);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+  }
+  sink[static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x] = acc;
+}
 }  // namespace
 
 extern "C" {
@@ -150,6 +169,14 @@ int moe_prof_mfma_ceiling(const moe_bf16* a, const moe_bf16* b, int workgroups, 
   *flop = 2.0 * 16 * 16 * 32 * 8.0 * iters * 8.0 * workgroups;
   *clock_ghz = clk[1] > 0 ? static_cast<double>(clk[0]) / (static_cast<double>(clk[1]) * 10.0) : 0.0;
   return rc == MOE_OK ? moe_check_launch() : rc;
+}
+
+int moe_prof_stream_read(const void* src, size_t bytes, uint32_t* sink, int workgroups, void* stream) {
+  if (!src || !sink || workgroups <= 0 || bytes < 16384 || !moe_aligned16(src)) return MOE_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  MOE_LAUNCH("stream_read", stream_read_kernel, dim3(workgroups), dim3(256), 0, s, static_cast<const uint4*>(src),
+             bytes / 16384, sink);
+  return moe_check_launch();
 }
 
 }  // extern "C"
