@@ -15,14 +15,17 @@
 //     advanced by scalar adds plus a 32-bit lane offset computed once per tile; the eight loads a
 //     wave issues per operand tile share one M0 value (the instruction's immediate offset moves
 //     the LDS address; the lane offset takes the same amount out of the global address again);
-//   * the last two K steps of a tile (which load nothing) are separate copies of the step, and a
-//     tile enters the ring of LDS slots at the phase that makes those two steps phases 0 and 1.
+//   * the last three K steps of a tile (the last one that loads, which is the one that may load a
+//     partial step of a weight gradient; the one that only awaits; the last one) are separate copies
+//     of the step, and a tile enters the ring of LDS slots at the phase that puts those three on
+//     phases 0, 1 and 2.
 //
 // The two operand tiles of a step (32 KB each) live in a ring of five LDS slots (160 KB, all
-// there is): A(t) in slot 2t mod 5, B(t) in slot (2t+1) mod 5.  The barrier of step t comes
-// after its first 32-deep sub-step: behind it the tiles of step t+1 are complete and the two
-// slots of step t are free; B(t+2) is then loaded into A(t)'s slot, and A(t+3) into B(t)'s slot
-// during the first sub-step of step t+1.  Fragments are double-buffered in registers: the reads
+// there is): A(t) in slot 2t mod 5, B(t) in slot (2t+1) mod 5, so two and a half steps are
+// resident.  Step t loads A(t+2) during its first 32-deep sub-step, into the slot B(t-1) left;
+// its barrier follows that sub-step: behind it the tiles of step t+1 are complete (the wave's own
+// loads of A(t+2) may still be in flight) and every wave is done with A(t), whose slot B(t+2) is
+// loaded into during the second sub-step.  Fragments are double-buffered in registers: the reads
 // of the next sub-step are issued between the MFMAs of the current one.
 //
 // Tile layouts.  An operand that is contiguous along K in memory (activations [rows, K],
@@ -31,18 +34,19 @@
 // applied on the global side of the fill, since a direct-to-LDS load writes LDS linearly.  An
 // operand that is contiguous along its other dimension (weights in dgrad, both operands in
 // wgrad) is kept as it lies in memory, [64 k][256 n] with 512-byte rows, and read with the
-// transposing LDS load ds_read_b64_tr_b16, two per fragment.
+// transposing LDS load ds_read_b64_tr_b16, two per fragment (it moves half the bytes per cycle
+// of ds_read_b128, which makes the weight gradients LDS-bound).
 //
 // The MFMAs are issued as (weight fragment) x (activation fragment), so a lane ends up with
-// four consecutive output COLUMNS of one row.  The epilogue rounds to bf16, stages each wave's
-// 128x128 piece in that wave's own 32 KB of LDS and writes it out in full 256-byte row segments;
-// the SwiGLU forward and backward formulas are applied on the way, on the fp32 accumulators.
+// four consecutive output COLUMNS of one row.  The epilogue reads the accumulators by hand, rounds
+// to bf16, stages 16 or 32 rows of the wave's 128x128 piece at a time in the wave's own 8 KB of LDS
+// and writes them out in full 256-byte row segments; the SwiGLU forward and backward formulas are
+// applied on the way, on the fp32 accumulators.
 //
 // Tiles of the row-grouped products are found on the device from expert_offsets: every wave
-// turns the tile number into (expert, first row, column tile) with a wave-wide prefix sum over
-// ceil(rows_e / 256) * column tiles; inside an expert the row tiles are innermost; experts
-// without rows own no tile; rows past an expert's end are clamped on load and masked on store,
-// and 32-row groups without a valid row issue no MFMA.
+// turns the tile number into (expert, first row, column tile); inside an expert the row tiles are
+// innermost; experts without rows own no tile; rows past an expert's end are clamped on load and
+// masked on store, and 32-row groups without a valid row issue no MFMA.
 #include <type_traits>
 #include <utility>
 #include "common.h"
@@ -54,7 +58,6 @@ constexpr int GEMM_THREADS = 256;
 constexpr int TILE_BYTES = BM * BK * 2;               // one operand tile (32 KB)
 constexpr int NSLOT = 5;                              // ring of operand tile slots
 constexpr int LDS_BYTES = NSLOT * TILE_BYTES;         // 160 KB: everything a workgroup can have
-constexpr int WAVE_STAGE_BYTES = 32768;               // epilogue staging per wave: 128 rows of 256 bytes
 constexpr int LOAD_BIAS = 4096;                       // see dma16_imm
 constexpr int slot_of_a(int p) { return (2 * p) % NSLOT; }       // p = ring phase of the step
 constexpr int slot_of_b(int p) { return (2 * p + 1) % NSLOT; }

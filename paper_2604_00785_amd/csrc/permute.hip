@@ -329,7 +329,7 @@ extern "C" int moe_permute_gate(const int32_t* topk_idx, const float* topk_w, in
 }
 
 // ---------------------------------------------------------------------------------------------
-// moe_permute for callers that cannot provide a workspace: the [expert][workgroup] histogram table
+// moe_permute for callers that cannot provide a workspace: the [chunk][expert] count table
 // lives in a device array that is part of the library image (every GPU the library runs on holds
 // its own copy until the process ends).
 namespace {
@@ -370,8 +370,8 @@ extern "C" int moe_permute_static_ws(const moe_bf16* x, const int32_t* topk_idx,
   if (moe_permute_workspace_bytes(T, k, e_count) > STATIC_WS_BYTES) return MOE_ERR_WORKSPACE;
   void* ws = scratch_address();
   if (ws == nullptr) return MOE_ERR_LAUNCH;
-  // every table cell the scan reads is written by the counting kernel of the same call first, so
-  // nothing has to be cleared between calls
+  // every table cell the placing kernel reads is written by the counting kernel of the same call first,
+  // so nothing has to be cleared between calls
   return permute_impl(x, topk_idx, nullptr, T, d, E_total, k, e_begin, e_count, expert_offsets, row_token, slot_row,
                       nullptr, xp, ws, STATIC_WS_BYTES, stream);
 }
