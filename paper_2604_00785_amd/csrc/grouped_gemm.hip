@@ -860,8 +860,8 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(c3));  v[3] = x;
     return v;
   };
-  // GATE_UP with gate weights folded into h: the weights of the lane's eight rows, requested by hand right
-  // behind the main loop and awaited by hand where the epilogue first needs them.
+  // GATE_UP with gate weights folded into h, DGRAD_H_GATE: the weights of the lane's eight rows, requested by
+  // hand right behind the main loop and awaited by hand where the epilogue first needs them.
   float wv[8];
   auto fetch_row_weights = [&](const TileState& t, const float* rw) __attribute__((always_inline)) {
 #pragma unroll
@@ -894,7 +894,9 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     // Stores ROWS staged rows of RB bytes (pieces swizzled by row & (RB / 16 - 1); region at `base`) to out rows
     // first_row .. (row stride ld): each row's PIECES 16-byte pieces from piece PIECE0 on go to columns
     // col0 + 8 piece.  The LDS reads of up to eight passes are issued together, then their stores (one wave per
-    // SIMD: nothing else would cover the latency of a read-then-store chain).
+    // SIMD: nothing else would cover the latency of a read-then-store chain).  When every row and column of the
+    // block exists (a wave-uniform test) the stores are unconditional and their addresses one add apart;
+    // otherwise each is masked by its row and column.
     auto flush = [&](const char* base, auto rb_tag, uint16_t* out, size_t ld, int first_row, auto rows_tag, auto piece0_tag,
                      auto pieces_tag, int col0, int ncols) __attribute__((always_inline)) {
       constexpr int RB = decltype(rb_tag)::value, ROWS = decltype(rows_tag)::value;
@@ -902,6 +904,9 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
       constexpr int RPP = 64 / PIECES, PASSES = ROWS / RPP, SWZ = RB / 16 - 1;
       const int prow = lane / PIECES, piece = lane % PIECES;
       const int gc = col0 + piece * 8;
+      const bool whole = first_row + ROWS <= m_end && col0 + PIECES * 8 <= ncols;
+      char* const p0 = reinterpret_cast<char*>(out + static_cast<size_t>(first_row + prow) * ld + gc);
+      const size_t pass_bytes = static_cast<size_t>(RPP) * ld * 2;
       static_for<(PASSES + 7) / 8>([&](auto b_tag) {
         constexpr int P0 = decltype(b_tag)::value * 8;
         constexpr int NB = PASSES - P0 < 8 ? PASSES - P0 : 8;
@@ -911,10 +916,15 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
           const int row = (P0 + k) * RPP + prow;
           v[k] = *reinterpret_cast<const u32x4*>(base + row * RB + (((PIECE0 + piece) ^ (row & SWZ)) << 4));
         }
+        if (whole) {
 #pragma unroll
-        for (int k = 0; k < NB; ++k) {
-          const int gr = first_row + (P0 + k) * RPP + prow;
-          if (gr < m_end && gc < ncols) *reinterpret_cast<u32x4*>(out + static_cast<size_t>(gr) * ld + gc) = v[k];
+          for (int k = 0; k < NB; ++k) *reinterpret_cast<u32x4*>(p0 + (P0 + k) * pass_bytes) = v[k];
+        } else {
+#pragma unroll
+          for (int k = 0; k < NB; ++k) {
+            const int gr = first_row + (P0 + k) * RPP + prow;
+            if (gr < m_end && gc < ncols) *reinterpret_cast<u32x4*>(p0 + (P0 + k) * pass_bytes) = v[k];
+          }
         }
       });
     };
@@ -955,52 +965,75 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
         __builtin_amdgcn_wave_barrier();
       });
     } else if constexpr (is_dgrad_h(MODE)) {
-      // in eight parts of 16 rows: g rows at stage[0, 4K), u rows at stage[4K, 8K).  The g/u rows of a part are
-      // requested before the previous part is processed, so their latency stays hidden.
+      // In eight parts of 16 rows, staged alternately in the wave's share of the first and of the second ring
+      // slot: g rows at [0, 4K), u rows at [4K, 8K) of the part's buffer, overwritten in place by dg and du.
+      // Order of the memory operations of part p: compute p; await the g/u rows of part p+1 and stage them;
+      // store part p; request the g/u rows of part p+2.  Waiting for loads also waits for every store issued
+      // before them (stores and loads share a counter and complete in no fixed order), so the wait is placed
+      // where the youngest stores are a whole part old, never right behind a part's own stores.
       // DGRAD_H_GATE: the accumulators hold dh0 = dout[token] . Wd; the row's gate weight w turns them into
       // dh = w dh0, and the sum over a 64-column strip of dh0 * silu(g) * u is the strip's share of the
       // gradient of w (a lane holds 16 of the strip's columns of its row, lanes ^ 16, ^ 32 the others).
       constexpr bool GATE = (MODE == DGRAD_H_GATE);
       constexpr int GU_PASSES = 4;   // 16 rows x 16 pieces = 256 pieces of 16 bytes, 64 per pass
+      constexpr int UOFF = 4096;
       u32x4 pg[GU_PASSES], pu[GU_PASSES];
       auto gu_load = [&](int part) __attribute__((always_inline)) {
         const int ncol = ae->N;
         const uint16_t* gsrc = ae->G;
         const uint16_t* usrc = ae->U;
+        const int r0 = grow0 + part * 16;
+        if (r0 + 16 <= m_end && gcol0 + 128 <= ncol) {   // wave-uniform: the whole part exists, nothing to clamp
+          const size_t o = static_cast<size_t>(r0 + (lane >> 4)) * ncol + gcol0 + (lane & 15) * 8;
+          const size_t pass = static_cast<size_t>(4) * ncol;
+#pragma unroll
+          for (int p = 0; p < GU_PASSES; ++p) {
+            pg[p] = *reinterpret_cast<const u32x4*>(gsrc + o + p * pass);
+            pu[p] = *reinterpret_cast<const u32x4*>(usrc + o + p * pass);
+          }
+          return;
+        }
 #pragma unroll
         for (int p = 0; p < GU_PASSES; ++p) {
           const int row = p * 4 + (lane >> 4), piece = lane & 15;
-          int gr = grow0 + part * 16 + row;  if (gr > m_end - 1) gr = m_end - 1;
+          int gr = r0 + row;  if (gr > m_end - 1) gr = m_end - 1;
           int gc = gcol0 + piece * 8;  if (gc > ncol - 8) gc = ncol - 8;
           const size_t o = static_cast<size_t>(gr) * ncol + gc;
           pg[p] = *reinterpret_cast<const u32x4*>(gsrc + o);
           pu[p] = *reinterpret_cast<const u32x4*>(usrc + o);
         }
       };
-      gu_load(0);
-      constexpr int UOFF = 4096;
-      static_for<8>([&](auto part_tag) {
-        constexpr int part = decltype(part_tag)::value;
-        const int first = grow0 + part * 16;
-        float wrow = 1.f, dsum[2] = {0.f, 0.f};
-        if constexpr (GATE) {
-          int r = first + l16;  if (r > m_end - 1) r = m_end - 1;
-          wrow = ae->row_weight[r];
-        }
+      auto gu_stage = [&](char* buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int p = 0; p < GU_PASSES; ++p) {
           const int row = p * 4 + (lane >> 4), piece = lane & 15;
           const int so = row * 256 + ((piece ^ (row & 15)) << 4);
-          *reinterpret_cast<u32x4*>(stage + so) = pg[p];
-          *reinterpret_cast<u32x4*>(stage + UOFF + so) = pu[p];
+          *reinterpret_cast<u32x4*>(buf + so) = pg[p];
+          *reinterpret_cast<u32x4*>(buf + UOFF + so) = pu[p];
         }
-        if (part + 1 < 8) gu_load(part + 1);
+      };
+      char* const bufs[2] = {stage, stage + TILE_BYTES};
+      if constexpr (GATE) {
+        wait_vm<0>();               // the row weights requested behind the main loop
+#pragma unroll
+        for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(wv[i]));
+      }
+      gu_load(0);
+      gu_stage(bufs[0]);
+      gu_load(1);
+      float dpart[8][2];
+      static_for<8>([&](auto part_tag) {
+        constexpr int part = decltype(part_tag)::value;
+        const int first = grow0 + part * 16;
+        char* const buf = bufs[part & 1];
+        const float wrow = GATE ? wv[part] : 1.f;
+        float dsum[2] = {0.f, 0.f};
         __builtin_amdgcn_wave_barrier();
         static_for<8>([&](auto j_tag) {
           constexpr int j = decltype(j_tag)::value;
           const int row = l16;
           const f32x4_t dhv = accq(part_tag, j_tag);
-          char* ga = quad_addr(row, j);
+          char* ga = buf + (quad_addr(row, j) - stage);
           char* ua = ga + UOFF;
           const u32x2 gq = *reinterpret_cast<const u32x2*>(ga);
           const u32x2 uq = *reinterpret_cast<const u32x2*>(ua);
@@ -1031,24 +1064,38 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
           *reinterpret_cast<u32x2*>(ua) = o;
         });
         if constexpr (GATE) {
-          const int strips = ae->N >> 6;
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            float x = dsum[s2];
+            x += __shfl_xor(x, 16, 64);
+            x += __shfl_xor(x, 32, 64);
+            dpart[part][s2] = x;
+          }
+        }
+        __builtin_amdgcn_wave_barrier();
+        if constexpr (part + 1 < 8) gu_stage(bufs[(part + 1) & 1]);   // awaits the loads of part + 1
+        __builtin_amdgcn_wave_barrier();
+        flush(buf, IC<256>{}, ae->O0, ae->N, first, IC<16>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
+        flush(buf + UOFF, IC<256>{}, ae->O1, ae->N, first, IC<16>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
+        __builtin_amdgcn_wave_barrier();
+        if constexpr (part + 2 < 8) gu_load(part + 2);
+      });
+      if constexpr (GATE) {
+        // the strips' shares of the gate gradient, stored behind everything else (a store in the middle of a
+        // part would be one more thing the next wait for loads has to sit out)
+        const int strips = ae->N >> 6;
+        static_for<8>([&](auto part_tag) {
+          constexpr int part = decltype(part_tag)::value;
+          const int r = grow0 + part * 16 + l16;
 #pragma unroll
           for (int s2 = 0; s2 < 2; ++s2) {
             if (gcol0 + s2 * 64 < ae->N) {     // a strip past the last column holds repeated columns: no share
               float* part_out = ae->dgate_part + ((gcol0 >> 6) + s2);
-              float x = dsum[s2];
-              x += __shfl_xor(x, 16, 64);
-              x += __shfl_xor(x, 32, 64);
-              const int r = first + l16;
-              if (lq == 0 && r < m_end) part_out[static_cast<size_t>(r) * strips] = x;
+              if (lq == 0 && r < m_end) part_out[static_cast<size_t>(r) * strips] = dpart[part][s2];
             }
           }
-        }
-        __builtin_amdgcn_wave_barrier();
-        flush(stage, IC<256>{}, ae->O0, ae->N, first, IC<16>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
-        flush(stage + UOFF, IC<256>{}, ae->O1, ae->N, first, IC<16>{}, IC<0>{}, IC<16>{}, gcol0, ae->N);
-        __builtin_amdgcn_wave_barrier();
-      });
+        });
+      }
     } else {
       uint16_t* out = t.second ? ae->O1 : ae->O0;
       if constexpr (is_wgrad(MODE)) out += static_cast<size_t>(t.e) * ae->M * ae->N;
@@ -1085,6 +1132,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
       if constexpr (MODE == GATE_UP) {
         if (a.row_weight != nullptr) fetch_row_weights(cur, a.row_weight);
       }
+      if constexpr (MODE == DGRAD_H_GATE) fetch_row_weights(cur, a.row_weight);
       epilogue(cur);
       // a wave stages in, and loads into, its own 8 KB of a slot only: no barrier between epilogue and loads
       tile += gridDim.x;
