@@ -1013,6 +1013,9 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
         }
       };
       char* const bufs[2] = {stage, stage + TILE_BYTES};
+      int qoff[8];                  // offsets of the lane's quads in a part's buffer: the same for every part
+#pragma unroll
+      for (int j = 0; j < 8; ++j) qoff[j] = static_cast<int>(quad_addr(l16, j) - stage);
       if constexpr (GATE) {
         wait_vm<0>();               // the row weights requested behind the main loop
 #pragma unroll
@@ -1029,14 +1032,21 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
         const float wrow = GATE ? wv[part] : 1.f;
         float dsum[2] = {0.f, 0.f};
         __builtin_amdgcn_wave_barrier();
+        // the lane's eight g and u quads of the part, read in one go: the quads are overwritten in place below, so
+        // reads issued one by one would each wait behind the previous quad's write
+        u32x2 gqs[8], uqs[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          gqs[j] = *reinterpret_cast<const u32x2*>(buf + qoff[j]);
+          uqs[j] = *reinterpret_cast<const u32x2*>(buf + qoff[j] + UOFF);
+        }
         static_for<8>([&](auto j_tag) {
           constexpr int j = decltype(j_tag)::value;
-          const int row = l16;
           const f32x4_t dhv = accq(part_tag, j_tag);
-          char* ga = buf + (quad_addr(row, j) - stage);
+          char* ga = buf + qoff[j];
           char* ua = ga + UOFF;
-          const u32x2 gq = *reinterpret_cast<const u32x2*>(ga);
-          const u32x2 uq = *reinterpret_cast<const u32x2*>(ua);
+          const u32x2 gq = gqs[j];
+          const u32x2 uq = uqs[j];
           const float g4[4] = {bf16lo(gq.x), bf16hi(gq.x), bf16lo(gq.y), bf16hi(gq.y)};
           const float u4[4] = {bf16lo(uq.x), bf16hi(uq.x), bf16lo(uq.y), bf16hi(uq.y)};
           float dg[4], du[4];
