@@ -30,7 +30,7 @@
 //
 // Tile layouts.  An operand that is contiguous along K in memory (activations [rows, K],
 // forward weights [N, K]) is kept as [256 rows][64 k] with 128-byte rows whose eight 16-byte
-// pieces are XOR-swizzled by the row (fragment = one ds_read_b128 per lane); the swizzle is
+// pieces are rotated by the row (fragment = one ds_read_b128 per lane); the swizzle is
 // applied on the global side of the fill, since a direct-to-LDS load writes LDS linearly.  An
 // operand that is contiguous along its other dimension (weights in dgrad, both operands in
 // wgrad) is kept as it lies in memory, [64 k][256 n] with 512-byte rows, and read with the
@@ -112,10 +112,11 @@ struct GemmArgs {
 // 512 bytes of zeros: what the reduction rows past an expert's end read in the weight-gradient products.
 __device__ __attribute__((aligned(512))) uint32_t g_zero_block[128];
 
-// [256 rows][64 k] tile: byte offset of the 16-byte piece `chunk` (0..7) of `row`.
-__device__ __forceinline__ int kc_off(int row, int chunk) {
-  return row * 128 + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 4);
-}
+// [256 rows][64 k] tile, 128-byte rows: the 16-byte piece `logical` (0..7) of `row` lies at physical piece
+// (logical + row) mod 8.  A fragment read (16 rows x 4 neighbouring pieces per instruction) then costs 8.5
+// cycles per CU, as a linear read does; XOR-ing the piece with (row ^ row >> 3) & 7 costs 8.9, no swizzle 16.
+// This is the inverse: which logical piece a fill has to fetch for physical piece `phys`.
+__device__ __forceinline__ int kc_logical_piece(int row, int phys) { return (phys - row) & 7; }
 // [64 k][256 n] tile: 16-byte pieces of a k row are XOR-swizzled with 4*(k & 3), which spreads the
 // four k rows that 16 lanes of a transposing read touch over four different 64-byte bank groups.
 __device__ __forceinline__ int kn_piece(int krow, int piece) { return piece ^ ((krow & 3) << 2); }
@@ -380,7 +381,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   // ---------------- operand sources -------------------------------------------
   // Per K step and operand tile a wave issues eight direct-to-LDS loads of 1 KB each:
   //  K-contiguous source ([row][k]): load i of wave w fills tile rows 64 w + 8 i .. + 8;
-  //    lane l -> row + l/8, physical piece l%8, i.e. the logical piece that kc_off maps there.
+  //    lane l -> row + l/8, physical piece l%8, i.e. logical piece kc_logical_piece(row, l%8).
   //    The base advances by 64 elements per step.
   //  n-contiguous source ([k][n]): load i of wave w fills k rows 2 (8 w + i), + 1;
   //    lane l -> k row + l/32, physical piece l%32 = logical piece kn_piece(k row, l%32).
@@ -445,7 +446,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = (wave * 8 + i) * 8 + (lane >> 3);
-      const int chunk = (kc_off(row, lane & 7) >> 4) & 7;   // the swizzle is its own inverse
+      const int chunk = kc_logical_piece(row, lane & 7);
       int r = row;
       if (m0 + r > m_end - 1) r = m_end - 1 - m0;
       const uint32_t fix = static_cast<uint32_t>(LOAD_BIAS - (i - 4) * 1024);
@@ -468,7 +469,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int row = (wave * 8 + i) * 8 + (lane >> 3);   // LDS row of the B tile
-        const int chunk = (kc_off(row, lane & 7) >> 4) & 7;
+        const int chunk = kc_logical_piece(row, lane & 7);
         int col = first_col + i * 8 + (lane >> 3);
         if (n0 + col > a.N - 1) col = a.N - 1 - n0;
         vob[i] = static_cast<uint32_t>((col * a.K + chunk * 8) * 2) + static_cast<uint32_t>(LOAD_BIAS - (i - 4) * 1024);
@@ -596,8 +597,8 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
   // Slot, block and sub-step are immediate offsets of the LDS reads, which reach 64 KB: one set of
   // per-lane addresses serves slots 0-1, one slots 2-3, one slot 4; four addresses per set and operand.
   //  [row][k] tile: block b = rows 16 b + (lane & 15), sub-step s (32 k) = logical piece 4 s + lane / 16.
-  //    The row swizzle is (lane & 7) ^ (lane bit 3) ^ (2 b & 6), so the address of (b, s) is
-  //    base[((2 b & 6) ^ 4 s) / 2] + 2048 b.
+  //    The row's share of the swizzle is lane & 7 whatever the block, so the address of (b, s) is
+  //    base[s] + 2048 b.
   //  [k][n] tile: block b = columns 16 b + (lane & 15); within 16 lanes, lane i supplies the address of four
   //    consecutive n of k row i / 4, n group i % 4, and lane l receives k rows 0..3 of column l; lanes
   //    16 g .. 16 g + 15 take k rows 8 g .. of the sub-step.  The k-row swizzle XORs bits 1-2 of the block
@@ -611,7 +612,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     for (int x = 0; x < 4; ++x) {
       const int i16 = lane & 15;
       // [row][k]
-      const int pc = ((lane >> 4) ^ (lane & 7) ^ ((lane >> 3) & 1) ^ (2 * x)) & 7;
+      const int pc = ((x & 1) * 4 + (lane >> 4) + (lane & 7)) & 7;   // sub-step x & 1; the block is an immediate offset
       const uint32_t kc_a = org + (wm * 128 + i16) * 128 + pc * 16;
       const uint32_t kc_b = org + (wn * 128 + i16) * 128 + pc * 16;
       // [k][n]
@@ -642,8 +643,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
         constexpr int half = OP % 2;
         fa[SET][blk].h[half] = lds_read_tr_b64<(SA & 1) * TILE_BYTES + S * 16384 + half * 2048 + (blk & 1) * 32>(fa_base[SA >> 1][blk >> 1]);
       } else {
-        constexpr int X = (((2 * blk) & 6) ^ (4 * S)) >> 1;
-        fa[SET][blk].v = lds_read_b128<(SA & 1) * TILE_BYTES + blk * 2048>(fa_base[SA >> 1][X]);
+        fa[SET][blk].v = lds_read_b128<(SA & 1) * TILE_BYTES + blk * 2048>(fa_base[SA >> 1][S]);
       }
     } else {
       constexpr int OB = OP - A_OPS;
@@ -652,8 +652,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
         constexpr int half = OB % 2;
         fb[SET][blk].h[half] = lds_read_tr_b64<(SB & 1) * TILE_BYTES + S * 16384 + half * 2048 + (blk & 1) * 32>(fb_base[SB >> 1][blk >> 1]);
       } else {
-        constexpr int X = (((2 * blk) & 6) ^ (4 * S)) >> 1;
-        fb[SET][blk].v = lds_read_b128<(SB & 1) * TILE_BYTES + blk * 2048>(fb_base[SB >> 1][X]);
+        fb[SET][blk].v = lds_read_b128<(SB & 1) * TILE_BYTES + blk * 2048>(fb_base[SB >> 1][S]);
       }
     }
   };
