@@ -202,42 +202,56 @@ __device__ __forceinline__ int count_row_tiles(const int32_t* offsets, int E, in
 // time, so that it is fetched from memory once (weights are the larger operand and are used by only
 // rows_e / 256 tiles each; activations of a row tile recur every rows_e / 256 tiles).
 //
-// With at most 64 experts (one per lane) the experts are not listed in index order: those whose tile count
+// With at most 128 experts (two per lane) the experts are not listed in index order: those whose tile count
 // is a whole number of XCD runs come first, then those that fill half a run, then the rest.  The first
 // two groups then start on run boundaries, so such an expert's tiles are worked on by one XCD at one
 // time and its activation rows are fetched into one L2 once; an expert that straddles two runs has its
 // rows fetched by both.  The lane keeps its expert's row range and first list position for the whole
 // kernel, so the lookup needs no memory access (which would otherwise sit in front of every tile's
 // first loads) and no scan.
-__device__ __forceinline__ int sorted_first_tile(int tiles, int run, int lane) {
-  const int r = tiles % run;
-  const int cls = r == 0 ? 0 : (2 * r == run ? 1 : 2);
-  int base = 0, first = 0;
+// (kept as six plain registers: a struct of arrays behind a reference ends up in scratch memory)
+__device__ __forceinline__ void sorted_first_tiles(int tiles0, int tiles1, int run, int lane, int& first0, int& first1) {
+  const int r0 = tiles0 % run, r1 = tiles1 % run;
+  const int cls0 = r0 == 0 ? 0 : (2 * r0 == run ? 1 : 2);
+  const int cls1 = r1 == 0 ? 0 : (2 * r1 == run ? 1 : 2);
+  int base = 0;
+  first0 = 0;
+  first1 = 0;
 #pragma unroll
   for (int c = 0; c < 3; ++c) {
-    const int mine = cls == c ? tiles : 0;
-    const int inc = wave_incl_scan(mine, lane);
-    if (cls == c) first = base + inc - mine;
-    base += __shfl(inc, 63, 64);
+    const int mine0 = cls0 == c ? tiles0 : 0;
+    const int inc0 = wave_incl_scan(mine0, lane);
+    if (cls0 == c) first0 = base + inc0 - mine0;
+    base += __shfl(inc0, 63, 64);
+    const int mine1 = cls1 == c ? tiles1 : 0;
+    const int inc1 = wave_incl_scan(mine1, lane);
+    if (cls1 == c) first1 = base + inc1 - mine1;
+    base += __shfl(inc1, 63, 64);
   }
-  return first;
 }
-__device__ __forceinline__ void find_tile(const int32_t* offsets, int E, int lo0, int hi0, int first0, int n_tiles, int tile,
-                                          int lane, int& e, int& m0, int& m_end, int& nt) {
+constexpr int LANE_EXPERTS_MAX = 128;
+// One half (experts 64 h .. 64 h + 63, one per lane) of the register-resident lookup.
+__device__ __forceinline__ bool find_tile_half(int h, int lo, int hi, int first, int n_tiles, int tile, int& e, int& m0,
+                                               int& m_end, int& nt) {
+  const int row_tiles = (hi - lo + BM - 1) / BM;
+  const int tiles = row_tiles * n_tiles;
+  const unsigned long long hit = __ballot(tiles > 0 && first <= tile && tile < first + tiles);
+  if (!hit) return false;
+  const int l = __ffsll(hit) - 1;
+  e = h * 64 + l;
+  const int q = tile - __shfl(first, l, 64);
+  const int rt = __shfl(row_tiles, l, 64);
+  nt = q / rt;
+  m0 = __shfl(lo, l, 64) + (q - nt * rt) * BM;
+  m_end = __shfl(hi, l, 64);
+  return true;
+}
+__device__ __forceinline__ void find_tile(const int32_t* offsets, int E, int lo0, int hi0, int first0, int lo1, int hi1,
+                                          int first1, int n_tiles, int tile, int lane, int& e, int& m0, int& m_end, int& nt) {
   e = 0; m0 = 0; m_end = 0; nt = 0;
-  if (E <= 64) {
-    const int row_tiles = (hi0 - lo0 + BM - 1) / BM;
-    const int tiles = row_tiles * n_tiles;
-    const unsigned long long hit = __ballot(tiles > 0 && first0 <= tile && tile < first0 + tiles);
-    if (hit) {
-      const int l = __ffsll(hit) - 1;
-      e = l;
-      const int q = tile - __shfl(first0, l, 64);
-      const int rt = __shfl(row_tiles, l, 64);
-      nt = q / rt;
-      m0 = __shfl(lo0, l, 64) + (q - nt * rt) * BM;
-      m_end = __shfl(hi0, l, 64);
-    }
+  if (E <= LANE_EXPERTS_MAX) {
+    if (find_tile_half(0, lo0, hi0, first0, n_tiles, tile, e, m0, m_end, nt)) return;
+    find_tile_half(1, lo1, hi1, first1, n_tiles, tile, e, m0, m_end, nt);
     return;
   }
   int base = 0;
@@ -320,8 +334,9 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
 
   // ---------------- tile list ---------------------------------------------------
   int total;
-  int lo0 = 0, hi0 = 0;   // this lane's expert's row range, kept for the whole kernel when E <= 64
-  int first0 = 0;         // ... and the list position of its first tile
+  // experts `lane` and `lane + 64`: row range and list position of the first tile, kept for the whole kernel
+  // when E <= LANE_EXPERTS_MAX
+  int lo0 = 0, hi0 = 0, first0 = 0, lo1 = 0, hi1 = 0, first1 = 0;
   // WGRAD / WGRAD_GATHER with a second A operand (A1 -> O1): two weight gradients that share their B
   // operand in one launch; an expert's tiles of the first come before its tiles of the second
   int wpair = 1;
@@ -330,9 +345,12 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     total = a.E * a.m_tiles_cap * a.n_tiles * wpair;
   } else {
     total = count_row_tiles(a.offsets, a.E, tid0 & 63) * a.n_tiles;
-    if (a.E <= 64) {
-      if ((tid0 & 63) < a.E) { lo0 = a.offsets[tid0 & 63]; hi0 = a.offsets[(tid0 & 63) + 1]; }
-      first0 = sorted_first_tile((hi0 - lo0 + BM - 1) / BM * a.n_tiles, gridDim.x >> 3, tid0 & 63);
+    if (a.E <= LANE_EXPERTS_MAX) {
+      const int e0 = tid0 & 63, e1 = 64 + (tid0 & 63);
+      if (e0 < a.E) { lo0 = a.offsets[e0]; hi0 = a.offsets[e0 + 1]; }
+      if (e1 < a.E) { lo1 = a.offsets[e1]; hi1 = a.offsets[e1 + 1]; }
+      sorted_first_tiles((hi0 - lo0 + BM - 1) / BM * a.n_tiles, (hi1 - lo1 + BM - 1) / BM * a.n_tiles, gridDim.x >> 3,
+                         tid0 & 63, first0, first1);
     }
   }
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<size_t>(LDS_PTR(lds)));
@@ -359,7 +377,7 @@ __device__ __forceinline__ int gemm_tile_list(const GemmArgs& a, int first_tile)
     m0 = mi * BM;                       // output row of dW
     m_end = a.M;
   } else {
-    find_tile(a.offsets, a.E, lo0, hi0, first0, a.n_tiles, tile, lane, e, m0, m_end, nt);
+    find_tile(a.offsets, a.E, lo0, hi0, first0, lo1, hi1, first1, a.n_tiles, tile, lane, e, m0, m_end, nt);
     nt = __builtin_amdgcn_readfirstlane(nt);
   }
   // tile coordinates are wave-uniform: keep them in scalar registers, so that everything derived

@@ -187,7 +187,8 @@ def test_permute_then_combine_is_identity():
     ([70, 1, 63, 64, 65, 128, 320, 330, 449], 64, 64),   # one reduction step forward; 1..8 steps in the weight gradients
     ([130, 130, 130], 320, 448),                  # 5 and 7 reduction steps: one and more rounds of the tile ring
     ([257, 511], 384, 704),                       # 6 and 11 steps, rows just past a tile boundary
-    ([3] * 130, 64, 128),                         # more experts than one wave scans in a pass
+    ([3] * 130, 64, 128),                         # more experts than a lane keeps in registers: per-tile prefix sums
+    ([300 if e % 9 == 0 else 7 for e in range(100)], 64, 128),   # two experts per lane, mixed tile counts
 ])
 def test_grouped_gemm_fwd_bwd_isolated(counts, d, f):
     print(f"gemm counts={counts} d={d} f={f}", flush=True)
