@@ -10,9 +10,9 @@
 // divided by the sum over all experts, or over the winners when renormalising.
 //
 // When the index generation of Stages 2-3 follows in the same call, a workgroup routes a chunk of
-// tokens (several passes of 256 / G tokens), keeps the chunk's winners in LDS and counts them per
-// local expert afterwards: the [chunk][expert] table of the counting sort is then a by-product of
-// the routing and the pairs need not be read back for it.
+// tokens (one or more passes of 256 / G tokens) and counts its winners per local expert straight from
+// the registers that hold them: the [chunk][expert] table of the counting sort is then a by-product
+// of the routing and the pairs need not be read back for it.
 #include "perm_common.h"
 
 namespace {
@@ -50,8 +50,6 @@ template <int G> __device__ __forceinline__ uint64_t group_max_u64(uint64_t best
   return best;
 }
 
-constexpr int ROUTE_CHUNK_MAX = 8192;   // pairs of a chunk the counting variant can keep in LDS
-
 // COUNT: also write hist[blockIdx.x][local expert] = winners of this workgroup's tokens per local expert.
 template <int G, int VPL, bool COUNT>
 __global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ logits, int T, int E, int k,
@@ -59,8 +57,7 @@ __global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ lo
                                                     float* __restrict__ topk_w, int passes, int e_begin, int e_count,
                                                     int nbits, int32_t* __restrict__ hist) {
   constexpr int GROUPS_PER_BLOCK = 256 / G;
-  __shared__ int pairs[COUNT ? ROUTE_CHUNK_MAX : 1];                    // local expert of every winner, or -1
-  __shared__ int wcnt[COUNT ? PERM_WAVES : 1][COUNT ? MOE_MAX_EXPERTS : 1];
+  __shared__ int wcnt[COUNT ? PERM_WAVES : 1][COUNT ? MOE_MAX_EXPERTS : 1];   // per wave: winners per local expert
   const int tid = threadIdx.x;
   const int gl = tid % G;  // lane inside the group
   if constexpr (COUNT) {
@@ -68,6 +65,7 @@ __global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ lo
 #pragma unroll
       for (int v = 0; v < PERM_WAVES; ++v) wcnt[v][e] = 0;
     }
+    __syncthreads();
   }
 
   auto load_row = [&](int pass, float (&val)[VPL]) {
@@ -149,18 +147,28 @@ __global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ lo
           topk_idx[static_cast<size_t>(t) * k + i] = my_idx[j];
           topk_w[static_cast<size_t>(t) * k + i] = expf(my_val[j] - row_max) * inv;
         }
-        if constexpr (COUNT) {
-          const int le = my_idx[j] - e_begin;
-          pairs[(pass * GROUPS_PER_BLOCK + tid / G) * k + i] = (live && le >= 0 && le < e_count) ? le : -1;
+      }
+    }
+    if constexpr (COUNT) {
+      // The winners are counted where they are: slot j of the wave's lanes is one batch of up to 64 pairs (lane gl
+      // of a group holds winner gl + j G), counted with the ballots of the counting sort; the lowest lane of every
+      // group of equal experts adds the group's size to the wave's own LDS row.
+      int* cnt = wcnt[tid / MOE_WAVE];
+      const int lane = tid % MOE_WAVE;
+#pragma unroll
+      for (int j = 0; j < VPL; ++j) {
+        if (j * G < k) {   // uniform: some lane holds a winner in this slot
+          int le = (live && gl + j * G < k) ? my_idx[j] - e_begin : -1;
+          if (le < 0 || le >= e_count) le = -1;
+          const uint64_t m = same_expert_mask(le, nbits);
+          if (m != 0 && lane == __builtin_ctzll(m)) cnt[le] += __builtin_popcountll(m);
+          __builtin_amdgcn_wave_barrier();
         }
       }
     }
   }
 
   if constexpr (COUNT) {
-    __syncthreads();
-    const int w = tid / MOE_WAVE;
-    count_wave_span(passes * GROUPS_PER_BLOCK * k, nbits, wcnt[w], [&](int i) { return pairs[i]; });
     __syncthreads();
     for (int e = tid; e < e_count; e += 256) {
       int s = 0;
@@ -190,7 +198,7 @@ bool launch_route_count(const float* logits, int T, int E, int k, int renorm, in
   const int cap = groups * perm_max_chunks(e_count);
   const int for_chunks = (T + cap - 1) / cap;
   const int passes = for_pairs > for_chunks ? for_pairs : for_chunks;
-  if (static_cast<long long>(passes) * groups * k > ROUTE_CHUNK_MAX) return false;
+  if (static_cast<long long>(passes) * groups * k > 0x3FFFFFFF) return false;
   const int tokens = passes * groups;
   *chunk = tokens * k;
   *nblocks = (T + tokens - 1) / tokens;
