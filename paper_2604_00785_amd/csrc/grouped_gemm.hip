@@ -1371,8 +1371,7 @@ int gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, const int32_t* row_token, 
                                                        static_cast<long long>(a.n_tiles) * m_tiles,
                                             s, "gemm_dgrad_h+wgrad_down");
   if (rc != MOE_OK) return rc;
-  // dWg = dg^T xp and dWu = du^T xp (one list: both read the same rows of xp) ; dxp = dg . Wg + du . Wu
-  // (last, so that the dx reduction that follows finds dxp in the last-level cache)
+  // dxp = dg . Wg + du . Wu ; dWg = dg^T xp and dWu = du^T xp (one list: both read the same rows of xp)
   GemmArgs w{};
   w.offsets = expert_offsets; w.E = E; w.row_token = row_token;
   w.A0 = dg; w.A1 = du; w.B0 = U16(xp); w.O0 = dWg; w.O1 = dWu; w.M = f; w.N = d;
@@ -1383,8 +1382,9 @@ int gemm_bwd(const moe_bf16* dyp, const moe_bf16* xp, const int32_t* row_token, 
   b.A0 = dg; b.A1 = du; b.B0 = U16(Wg); b.B1 = U16(Wu); b.O0 = dxp;
   b.K = f; b.N = d; b.n_tiles = (d + BN - 1) / BN;
   const long long tiles = 2ll * w.n_tiles * w.m_tiles_cap * E + static_cast<long long>(b.n_tiles) * m_tiles;
-  if (row_token != nullptr) return launch_gemm_pair<WGRAD_GATHER, DGRAD_X>(w, b, tiles, s, "gemm_wgrad_gate_up+dgrad_x");
-  return launch_gemm_pair<WGRAD, DGRAD_X>(w, b, tiles, s, "gemm_wgrad_gate_up+dgrad_x");
+  // dgrad_x first: its tiles are the long ones, the weight gradients' many short tiles fill its tail
+  if (row_token != nullptr) return launch_gemm_pair<DGRAD_X, WGRAD_GATHER>(b, w, tiles, s, "gemm_wgrad_gate_up+dgrad_x");
+  return launch_gemm_pair<DGRAD_X, WGRAD>(b, w, tiles, s, "gemm_wgrad_gate_up+dgrad_x");
 }
 }  // namespace
 
@@ -1491,6 +1491,9 @@ extern "C" int moe_grouped_gemm_bwd_folded(const moe_bf16* dout, const moe_bf16*
   b.offsets = expert_offsets; b.E = E; b.m_tiles_cap = m_tiles;
   b.A0 = dg; b.A1 = du; b.B0 = U16(Wg); b.B1 = U16(Wu); b.O0 = dxp;
   b.K = f; b.N = d; b.n_tiles = (d + BN - 1) / BN;
-  return launch_gemm_pair<WGRAD_GATHER, DGRAD_X>(w, b, 2ll * w.n_tiles * w.m_tiles_cap * E + static_cast<long long>(b.n_tiles) * m_tiles,
+  // dgrad_x first: its tiles are the long ones, the weight gradients' many short tiles fill its tail.  (The other
+  // order used to pay off through dxp still lying in the last-level cache when moe_permute_bwd read it; since that
+  // kernel streams its rows with non-temporal loads it no longer depends on that.)
+  return launch_gemm_pair<DGRAD_X, WGRAD_GATHER>(b, w, 2ll * w.n_tiles * w.m_tiles_cap * E + static_cast<long long>(b.n_tiles) * m_tiles,
                                                  s, "gemm_wgrad_gate_up+dgrad_x");
 }
