@@ -54,11 +54,11 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32
                                                                      const float* __restrict__ topk_w,
                                                                      float* __restrict__ row_weight) {
   __shared__ int wcnt[PERM_WAVES][MOE_MAX_EXPERTS];
-  // partial column sums, [part][expert]: parts * e_count <= 1024 entries; after the reduction row 0 holds
-  // the sums (before: rows of the chunks in front of this one; total: the expert's rows)
+  // partial column sums, [part][expert]: parts * e_count <= 1024 entries (before: rows of the chunks in front
+  // of this one; total: the expert's rows)
   __shared__ __attribute__((aligned(16))) int part_before[2 * MOE_MAX_EXPERTS];
   __shared__ __attribute__((aligned(16))) int part_total[2 * MOE_MAX_EXPERTS];
-  __shared__ int first_row[MOE_MAX_EXPERTS];                  // first row of the expert
+  __shared__ int first_row[MOE_MAX_EXPERTS];                  // first row of this chunk's cell of the expert
   const int tid = threadIdx.x, w = tid / MOE_WAVE, lane = tid % MOE_WAVE;
   const int b = blockIdx.x, nblocks = gridDim.x;
 
@@ -110,20 +110,22 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32
     for (int v = 0; v < PERM_WAVES; ++v) wcnt[v][e] = 0;
   }
   __syncthreads();
-  for (int c = tid; c < e_count; c += PERM_THREADS) {
-    int bef = 0, tot = 0;
-    for (int q = 0; q < parts; ++q) { bef += part_before[q * e_count + c]; tot += part_total[q * e_count + c]; }
-    part_before[c] = bef;
-    part_total[c] = tot;
-  }
-  __syncthreads();
-  // ---- exclusive scan of the experts' totals by the first wave: ceil(e_count / 64) experts per lane ----
+  // ---- the first wave adds up the parts (ceil(e_count / 64) experts per lane), scans the experts' totals and
+  //      leaves in first_row the first row of this chunk's cell of every expert ----
   if (w == 0) {
-    const int seg = (e_count + MOE_WAVE - 1) / MOE_WAVE;
+    const int seg = (e_count + MOE_WAVE - 1) / MOE_WAVE;   // <= MOE_MAX_EXPERTS / 64 = 8
+    int befs[MOE_MAX_EXPERTS / MOE_WAVE], tots[MOE_MAX_EXPERTS / MOE_WAVE];
     int s = 0;
-    for (int j = 0; j < seg; ++j) {
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_EXPERTS / MOE_WAVE; ++j) {
       const int e = lane * seg + j;
-      s += e < e_count ? part_total[e] : 0;
+      int bef = 0, tot = 0;
+      if (j < seg && e < e_count) {
+        for (int q = 0; q < parts; ++q) { bef += part_before[q * e_count + e]; tot += part_total[q * e_count + e]; }
+      }
+      befs[j] = bef;
+      tots[j] = tot;
+      s += tot;
     }
     int inc = s;
 #pragma unroll
@@ -132,12 +134,13 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32
       if (lane >= d) inc += o;
     }
     int run = inc - s;
-    for (int j = 0; j < seg; ++j) {
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_EXPERTS / MOE_WAVE; ++j) {
       const int e = lane * seg + j;
-      if (e < e_count) {
-        first_row[e] = run;
+      if (j < seg && e < e_count) {
+        first_row[e] = run + befs[j];
         if (b == 0) expert_offsets[e] = run;
-        run += part_total[e];
+        run += tots[j];
       }
     }
     if (b == 0 && lane == MOE_WAVE - 1) expert_offsets[e_count] = inc;
@@ -147,7 +150,7 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_place_kernel(const int32
   count_wave_span(len, nbits, wcnt[w], local);
   __syncthreads();
   for (int e = tid; e < e_count; e += PERM_THREADS) {
-    int base = first_row[e] + part_before[e];
+    int base = first_row[e];
 #pragma unroll
     for (int v = 0; v < PERM_WAVES; ++v) {
       const int c = wcnt[v][e];
