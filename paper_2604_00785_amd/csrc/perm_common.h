@@ -55,8 +55,9 @@ inline int perm_max_chunks(int e_count) {
   return by_cells < 256 ? 256 : (by_cells > 4096 ? 4096 : by_cells);
 }
 
-// Launches Stage 1 with the per-chunk expert counts as a by-product (route.hip).  Returns false if the
-// shape does not fit the fused kernel (the caller then routes and counts with two launches).
+// Launches Stage 1 with the per-chunk expert counts as a by-product (route.hip); hist has room for hist_cells
+// counts.  Returns false if the shape does not fit the fused kernel (the caller then routes and counts with
+// two launches).
 bool moe_launch_route_count(const float* logits, int T, int E, int k, int renormalize, int e_begin, int e_count,
-                            int nbits, int32_t* topk_idx, float* topk_w, int32_t* hist, int* chunk, int* nblocks,
-                            hipStream_t s);
+                            int nbits, int32_t* topk_idx, float* topk_w, int32_t* hist, size_t hist_cells, int* chunk,
+                            int* nblocks, hipStream_t s);

@@ -300,7 +300,7 @@ extern "C" int moe_route_permute(const float* logits, const moe_bf16* x, int T, 
   int32_t* hist = static_cast<int32_t*>(ws);
   int chunk = 0, nb = 0;
   if (!moe_launch_route_count(logits, T, E_total, k, renormalize != 0, e_begin, e_count, nbits, topk_idx, topk_w, hist,
-                              &chunk, &nb, s)) {
+                              ws_bytes / sizeof(int32_t), &chunk, &nb, s)) {
     const int r = moe_route(logits, T, E_total, k, renormalize, topk_idx, topk_w, stream);
     if (r != MOE_OK) return r;
     chunk = perm_chunk_pairs(n, e_count);

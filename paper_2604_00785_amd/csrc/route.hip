@@ -187,17 +187,18 @@ void launch_route(const float* logits, int T, int E, int k, int renorm, int32_t*
              static_cast<int32_t*>(nullptr));
 }
 
-// Tokens per workgroup: whole passes of 256 / G tokens, enough of them that a chunk holds at least 256 pairs
-// (the table then has no more rows than the workspace is sized for) and that there are at most
-// perm_max_chunks chunks.
+// Tokens per workgroup: whole passes of 256 / G tokens; as few passes as keep the chunks at perm_max_chunks
+// or fewer and the [chunk][expert] table inside the workspace the caller gave (a workspace of the minimum
+// size holds one table row per 256 pairs, which can mean several passes when k is small).
 template <int G, int VPL>
 bool launch_route_count(const float* logits, int T, int E, int k, int renorm, int e_begin, int e_count, int nbits,
-                        int32_t* idx, float* w, int32_t* hist, int* chunk, int* nblocks, hipStream_t s) {
+                        int32_t* idx, float* w, int32_t* hist, size_t hist_cells, int* chunk, int* nblocks, hipStream_t s) {
   const int groups = 256 / G;
-  const int for_pairs = (256 + groups * k - 1) / (groups * k);
-  const int cap = groups * perm_max_chunks(e_count);
-  const int for_chunks = (T + cap - 1) / cap;
-  const int passes = for_pairs > for_chunks ? for_pairs : for_chunks;
+  const long long rows_fit = static_cast<long long>(hist_cells / static_cast<size_t>(e_count));
+  const long long max_chunks = rows_fit < perm_max_chunks(e_count) ? rows_fit : perm_max_chunks(e_count);
+  if (max_chunks < 1) return false;
+  const long long cap = groups * max_chunks;
+  const int passes = static_cast<int>((T + cap - 1) / cap);
   if (static_cast<long long>(passes) * groups * k > 0x3FFFFFFF) return false;
   const int tokens = passes * groups;
   *chunk = tokens * k;
@@ -210,11 +211,12 @@ bool launch_route_count(const float* logits, int T, int E, int k, int renorm, in
 }  // namespace
 
 bool moe_launch_route_count(const float* logits, int T, int E, int k, int renormalize, int e_begin, int e_count,
-                            int nbits, int32_t* topk_idx, float* topk_w, int32_t* hist, int* chunk, int* nblocks,
-                            hipStream_t s) {
+                            int nbits, int32_t* topk_idx, float* topk_w, int32_t* hist, size_t hist_cells, int* chunk,
+                            int* nblocks, hipStream_t s) {
   if (E > MOE_MAX_EXPERTS) return false;
 #define MOE_ROUTE_COUNT(G, VPL) \
-  launch_route_count<G, VPL>(logits, T, E, k, renormalize, e_begin, e_count, nbits, topk_idx, topk_w, hist, chunk, nblocks, s)
+  launch_route_count<G, VPL>(logits, T, E, k, renormalize, e_begin, e_count, nbits, topk_idx, topk_w, hist, hist_cells, chunk, \
+                             nblocks, s)
   // eight logits per lane where the expert count allows: twice the tokens per pass of the plain launch, so
   // that one pass already fills a chunk at the usual shapes (a second pass would run after the first)
   if (E <= 8) return MOE_ROUTE_COUNT(8, 1);

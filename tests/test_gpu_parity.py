@@ -132,6 +132,32 @@ def test_route_permute_one_call(T, E, k, eb, ec, renorm, gate):
     assert torch.equal(off, off2) and torch.equal(sr, sr2) and torch.equal(rt[:R], rt2[:R])
 
 
+@pytest.mark.parametrize("T,E,k,eb,ec", [(3000, 96, 6, 8, 8), (8192, 64, 8, 0, 64), (700, 16, 2, 0, 16), (24576, 96, 6, 88, 8)])
+def test_route_permute_with_a_large_workspace(T, E, k, eb, ec):
+    """A workspace beyond the minimum lets the routing kernel use short chunks (one pass of tokens per workgroup,
+    fewer than 256 pairs when k is small): same results."""
+    print(f"route_permute, 4 MiB workspace: T={T} E={E} k={k} local=[{eb},{eb+ec})", flush=True)
+    rng = np.random.default_rng(T + E)
+    logits = (rng.standard_normal((T, E)) * 2).astype(np.float32)
+    logits[::5] = np.round(logits[::5])
+    lg = torch.from_numpy(logits).to(DEV)
+    mk = lambda shape, dt: torch.full(shape, -7, dtype=dt, device=DEV)
+    idx, w = mk((T, k), torch.int32), mk((T, k), torch.float32)
+    off, rt, sr = mk((ec + 1,), torch.int32), mk((T * k,), torch.int32), mk((T, k), torch.int32)
+    rw = mk((T * k,), torch.float32)
+    ws = torch.full((4 << 20,), 0xA5, dtype=torch.uint8, device=DEV)
+    B.moe_route_permute(lg, None, k, 1, eb, ec, idx, w, off, rt, sr, rw, None, ws)
+    torch.cuda.synchronize()
+    ridx, rwts = O.route(logits, k, 1)
+    roff, rrt, rsr, _ = O.permute(np.zeros((T, 1)), ridx, eb, ec)
+    R = int(roff[-1])
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    np.testing.assert_allclose(w.cpu().numpy(), rwts, rtol=H.GATE_TOL)
+    assert np.array_equal(off.cpu().numpy(), roff)
+    assert np.array_equal(sr.cpu().numpy(), rsr)
+    assert np.array_equal(rt.cpu().numpy()[:R], rrt)
+
+
 # ----------------------------------------------------------------------------- combine (+bwd), permute_bwd
 @pytest.mark.parametrize("T,E,k,d,eb,ec", [(256, 8, 2, 128, 0, 8), (500, 64, 8, 2048, 0, 64), (300, 16, 4, 4096, 4, 8),
                                            (77, 6, 3, 264, 0, 6)])
