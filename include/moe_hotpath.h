@@ -207,7 +207,9 @@ int moe_grouped_gemm_bwd_gather(const moe_bf16* dyp, const moe_bf16* x, int T, c
  *   logits, topk_idx, topk_w, renormalize   as moe_route (both outputs are written in full)
  *   x, xp                                   as moe_permute; both may be NULL (index generation only)
  *   row_weight                              as moe_permute_gate, or NULL
- *   expert_offsets, row_token, slot_row, ws as moe_permute
+ *   expert_offsets, row_token, slot_row, ws as moe_permute (a workspace beyond the minimum is put to use: the
+ *                                           count table may then have more, shorter rows of tokens, which
+ *                                           spares the routing kernel a second pass; the results do not change)
  */
 int moe_route_permute(const float* logits, const moe_bf16* x, int T, int d, int E_total, int k, int renormalize,
                       int e_begin, int e_count, int32_t* topk_idx, float* topk_w,
