@@ -263,6 +263,23 @@ def test_grouped_gemm_fwd_bwd_isolated(counts, d, f):
                 H.assert_close(gw[e], bw[n][e], f"{n}[{e}]")
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_grouped_gemm_random_shapes(seed):
+    """Seeded random expert counts and widths: whole and ragged row tiles, experts whose tile count fills a whole
+    run of tiles next to ones that do not, empty experts, one to 140 experts."""
+    rng = np.random.default_rng(1000 + seed)
+    E = int(rng.choice([1, 2, 7, 33, 64, 65, 100, 128, 129, 140]))
+    d = int(rng.choice([64, 128, 192, 256, 512]))
+    f = int(rng.choice([64, 128, 256, 320, 512]))
+    kinds = rng.integers(0, 5, size=E)
+    counts = [int({0: 0, 1: 256, 2: rng.integers(1, 40), 3: rng.integers(250, 270), 4: rng.integers(500, 530)}[k]) for k in kinds]
+    if E > 64:
+        counts = [min(c, 40) if i % 5 else c for i, c in enumerate(counts)]     # keep the total small
+    if sum(counts) == 0:
+        counts[0] = 17
+    test_grouped_gemm_fwd_bwd_isolated(counts, d, f)
+
+
 # ----------------------------------------------------------------------------- whole path, small configs
 @pytest.mark.parametrize("name", ["tiny", "skew"])
 def test_layer_small_configs(name):
