@@ -309,6 +309,27 @@ def test_layer_ragged_shapes(T, d, E, k, f, eb, ec, renorm):
     H.compare_layer(res, ref, ec)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_layer_random_shapes(seed):
+    """Seeded random layer shapes and local expert ranges through each of the three forms of the path."""
+    rng = np.random.default_rng(77 + seed)
+    E = int(rng.choice([3, 8, 16, 64, 100, 128, 200]))
+    k = int(rng.integers(1, min(E, 8) + 1))
+    T = int(rng.choice([37, 256, 600, 1111]))    # (a single token is its own test: one ill-conditioned dot product
+                                                 # is no basis for a relative bound)
+    d, f = int(rng.choice([64, 128, 192])), int(rng.choice([64, 128, 320]))
+    eb = int(rng.integers(0, E))
+    ec = int(rng.integers(1, min(E - eb, 150) + 1))
+    renorm = int(rng.integers(0, 2))
+    mode = [dict(), dict(gather=True), dict(fold=True)][seed % 3]
+    print(f"layer T={T} d={d} E={E} k={k} f={f} local=[{eb},{eb+ec}) renorm={renorm} {mode}", flush=True)
+    cfg = W.MoEConfig("custom", T=T, d=d, E=E, k=k, f=f, e_begin=eb, e_count=ec, renormalize=renorm, seed=500 + seed)
+    inp = W.make_inputs(cfg)
+    res = H.run_layer(cfg, inp, **mode)
+    ref = O.layer_fwd_bwd(inp, k, eb, ec, renorm)
+    H.compare_layer(res, ref, ec)
+
+
 @pytest.mark.parametrize("T,d,E,k,f,eb,ec,renorm", [
     (256, 128, 8, 2, 256, 0, 8, 1),       # the tiny config's shape
     (700, 192, 6, 3, 320, 0, 6, 1),       # ragged in every dimension
